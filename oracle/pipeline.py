@@ -1,0 +1,62 @@
+"""K workers of the CPU oracle driven by the simulated nF1B schedule.
+
+Test infrastructure (CPU oracle).  Tasks are executed in time-point order;
+within a time-point the workers do not interact (what one produces reaches its
+neighbour at the next time-point), so the order inside a time-point is free.
+Each worker reads and updates only its own weights, in place: a forward pass
+sees whatever the worker's weights are when the micro-batch gets there, and a
+backward pass the weights at that moment.
+"""
+import numpy as np
+
+from . import schedule as S
+from .stage import Stage
+
+
+def run(cfg, params, batches, trace=None):
+    """Train `len(batches)` mini-batches.
+
+    cfg: a workloads.Config (shape tables only); params: per stage, per layer dicts of arrays;
+    batches: list of (x [M, ...], labels [M]).  trace: optional dict that receives every task's
+    tensors under (kind, b, j, stage) keys.
+    Returns dict(losses=[per mini-batch mean of the micro-batch losses], ops=version log,
+    stages=[Stage]).
+    """
+    K, N, M = cfg.K, cfg.N, cfg.M
+    micro = M // N
+    stages = [Stage(cfg.stages[s], params[s], cfg.lr, cfg.momentum, M, N) for s in range(K)]
+    sim = S.simulate(K, N, len(batches))
+    fwd_out = {}
+    bwd_out = {}
+    micro_losses = {}
+    for (t, s, kind, b, j, sv, nv) in sim["ops"]:
+        st = stages[s]
+        assert st.version == sv, "worker version differs from the simulated log"
+        if kind == S.FWD:
+            x_all, y_all = batches[b - 1]
+            if s == 0:
+                x = x_all[j * micro:(j + 1) * micro]
+            else:
+                x = fwd_out.pop((b, j, s - 1))
+            if s == K - 1:
+                logits, loss = st.forward_micro((b, j), x, y_all[j * micro:(j + 1) * micro])
+                micro_losses.setdefault(b, []).append(loss)
+                out = logits
+            else:
+                out = st.forward_micro((b, j), x)
+                fwd_out[(b, j, s)] = out
+            if trace is not None:
+                trace[("F", b, j, s)] = np.array(out)
+        else:
+            slots = [(b, jj) for jj in range(N)]
+            dy = None if s == K - 1 else bwd_out.pop((b, s + 1))
+            dx = st.backward(slots, dy)
+            if s > 0:
+                bwd_out[(b, s)] = dx
+            if trace is not None:
+                trace[("B", b, -1, s)] = np.array(dx)
+                trace[("G", b, -1, s)] = [None if g is None else {k: np.array(v) for k, v in g.items()}
+                                          for g in st.grads]
+            st.update()
+    losses = [float(np.mean(micro_losses[b])) for b in range(1, len(batches) + 1)]
+    return {"losses": losses, "ops": sim["ops"], "stages": stages}

@@ -1,0 +1,100 @@
+"""One pipeline worker of the CPU oracle: consecutive layers, stash, backward, update.
+
+Test infrastructure (CPU oracle).  Follows the Methodology section: a
+micro-batch of M/N samples is the unit of the forward pass; once the N
+micro-batches of a mini-batch have been forwarded, ONE backward pass is made
+over the whole mini-batch on the gradient of the average micro-batch loss,
+with the stage's weights as they are at that moment (no weight version is
+kept from the forward pass); then the weights are updated in place
+(update rule of TiMePReSt with SGD; momentum, which the paper leaves open, is
+buf <- mu*buf + g, w <- w - lr*buf, buf_0 = 0).
+"""
+import numpy as np
+
+from . import layers as L
+
+
+class Stage:
+    def __init__(self, layer_specs, params, lr, momentum, M, N):
+        if M % N != 0:
+            raise ValueError("mini-batch size must be a multiple of the number of micro-batches")
+        self.specs = layer_specs
+        self.params = [{k: np.array(v, dtype=np.float64) for k, v in p.items()} for p in params]
+        self.bufs = [{k: np.zeros_like(v) for k, v in p.items()} for p in self.params]
+        self.grads = [None] * len(layer_specs)
+        self.lr, self.mu, self.M, self.N = float(lr), float(momentum), M, N
+        self.is_last = layer_specs[-1]["kind"] == "softmax_ce"
+        self.stash = {}
+        self.version = 0
+
+    # -- forward of one micro-batch -------------------------------------------------------
+    def forward_micro(self, slot, x, labels=None):
+        """Returns the stage output; on the last stage returns (logits, micro-batch mean loss)."""
+        if slot in self.stash:
+            raise RuntimeError("stash slot %r is in use" % (slot,))
+        caches = []
+        a = np.asarray(x, dtype=np.float64)
+        loss = None
+        for spec, p in zip(self.specs, self.params):
+            k = spec["kind"]
+            if k == "linear":
+                a, c = L.linear_forward(a, p["w"], p["b"], spec["relu"])
+            elif k == "conv":
+                a, c = L.conv_forward(a, p["w"], p["b"], spec["stride"], spec["pad"], spec["relu"])
+            elif k == "maxpool":
+                a, c = L.maxpool_forward(a, spec["k"], spec["stride"])
+            elif k == "softmax_ce":
+                loss, c = L.softmax_ce_forward(a, np.asarray(labels))
+            else:
+                raise ValueError(k)
+            caches.append(c)
+        self.stash[slot] = caches
+        return (a, loss) if self.is_last else a
+
+    # -- one backward pass over the mini-batch --------------------------------------------
+    def backward(self, slots, dy=None):
+        """dy: gradient w.r.t. the stage output for all M samples (rows in slot order); None on
+        the last stage.  Returns the gradient w.r.t. the stage input, same row order.  Consumes
+        the slots.  Parameter gradients are summed over the micro-batches."""
+        if len(slots) != self.N:
+            raise ValueError("a backward pass covers the N micro-batches of one mini-batch")
+        micro = self.M // self.N
+        acc = [None] * len(self.specs)
+        dxs = []
+        for i, slot in enumerate(slots):
+            caches = self.stash.pop(slot)
+            g = None if dy is None else np.asarray(dy[i * micro:(i + 1) * micro], dtype=np.float64)
+            for li in range(len(self.specs) - 1, -1, -1):
+                spec, p, c = self.specs[li], self.params[li], caches[li]
+                k = spec["kind"]
+                if k == "softmax_ce":
+                    g = L.softmax_ce_backward(c, self.M)
+                    continue
+                if k == "linear":
+                    g = g.reshape(g.shape[0], -1)
+                    g, dw, db = L.linear_backward(g, c, p["w"], spec["relu"])
+                elif k == "conv":
+                    g = g.reshape(c["y"].shape)
+                    g, dw, db = L.conv_backward(g, c, p["w"], spec["stride"], spec["pad"], spec["relu"])
+                elif k == "maxpool":
+                    g = L.maxpool_backward(g.reshape(c["win"].shape), c, spec["k"], spec["stride"])
+                    continue
+                if acc[li] is None:
+                    acc[li] = {"w": dw, "b": db}
+                else:
+                    acc[li]["w"] = acc[li]["w"] + dw
+                    acc[li]["b"] = acc[li]["b"] + db
+            dxs.append(g)
+        self.grads = acc
+        return np.concatenate(dxs, axis=0)
+
+    # -- in-place update -------------------------------------------------------------------
+    def update(self):
+        for p, buf, g in zip(self.params, self.bufs, self.grads):
+            if g is None:
+                continue
+            for k in p:
+                buf[k] *= self.mu
+                buf[k] += g[k]
+                p[k] -= self.lr * buf[k]
+        self.version += 1

@@ -1,0 +1,186 @@
+"""Pins of the oracle's layer arithmetic: closed forms, finite differences, library autograd."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import layers as L
+
+torch.set_default_dtype(torch.float64)
+
+
+def _fd(f, x, eps=1e-6):
+    """Central finite-difference gradient of scalar f at x."""
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + eps
+        fp = f()
+        x[i] = old - eps
+        fm = f()
+        x[i] = old
+        g[i] = (fp - fm) / (2 * eps)
+    return g
+
+
+def _rel(a, b):
+    return np.max(np.abs(a - b)) / (np.max(np.abs(b)) + 1e-300)
+
+
+# ------------------------------------------------------------------ softmax cross-entropy
+def test_ce_uniform_logits_closed_form():
+    C, B, M = 10, 6, 24
+    labels = np.arange(B) % C
+    loss, c = L.softmax_ce_forward(np.full((B, C), 3.7), labels)
+    assert abs(loss - np.log(C)) < 1e-14
+    g = L.softmax_ce_backward(c, M)
+    want = np.full((B, C), 1.0 / C)
+    want[np.arange(B), labels] -= 1.0
+    assert np.allclose(g, want / M, atol=1e-16)
+
+
+def test_ce_rows_sum_to_zero_and_shift_invariance():
+    rng = np.random.default_rng(0)
+    z = rng.standard_normal((5, 7)) * 4
+    y = rng.integers(0, 7, 5)
+    l1, c1 = L.softmax_ce_forward(z, y)
+    l2, c2 = L.softmax_ce_forward(z + 1000.0, y)
+    assert abs(l1 - l2) < 1e-9
+    assert np.allclose(L.softmax_ce_backward(c1, 5).sum(axis=1), 0.0, atol=1e-15)
+
+
+def test_ce_against_library_and_finite_differences():
+    rng = np.random.default_rng(1)
+    z = rng.standard_normal((8, 10))
+    y = rng.integers(0, 10, 8)
+    loss, c = L.softmax_ce_forward(z, y)
+    zt = torch.tensor(z, requires_grad=True)
+    lt = F.cross_entropy(zt, torch.tensor(y))
+    lt.backward()
+    assert abs(loss - lt.item()) < 1e-12
+    # gradient of the mean over these 8 rows == softmax_ce_backward with M = 8
+    assert _rel(L.softmax_ce_backward(c, 8), zt.grad.numpy()) < 1e-12
+    g_fd = _fd(lambda: L.softmax_ce_forward(z, y)[0], z)
+    assert _rel(L.softmax_ce_backward(c, 8), g_fd) < 1e-7
+    # a mini-batch of M = 32 of which this is one micro-batch: gradient scales by 8/32
+    assert np.allclose(L.softmax_ce_backward(c, 32) * 4, L.softmax_ce_backward(c, 8))
+
+
+# ------------------------------------------------------------------ linear
+@pytest.mark.parametrize("relu", [False, True])
+def test_linear_against_library_autograd(relu):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((5, 7)); w = rng.standard_normal((4, 7)); b = rng.standard_normal(4)
+    dy = rng.standard_normal((5, 4))
+    y, c = L.linear_forward(x, w, b, relu)
+    dx, dw, db = L.linear_backward(dy, c, w, relu)
+    xt, wt, bt = (torch.tensor(a, requires_grad=True) for a in (x, w, b))
+    yt = F.linear(xt, wt, bt)
+    if relu:
+        yt = F.relu(yt)
+    yt.backward(torch.tensor(dy))
+    assert _rel(y, yt.detach().numpy()) < 1e-13
+    assert _rel(dx, xt.grad.numpy()) < 1e-13
+    assert _rel(dw, wt.grad.numpy()) < 1e-13
+    assert _rel(db, bt.grad.numpy()) < 1e-13
+
+
+def test_linear_finite_differences():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((3, 5)); w = rng.standard_normal((4, 5)); b = rng.standard_normal(4)
+    r = rng.standard_normal((3, 4))
+    f = lambda: float((L.linear_forward(x, w, b, True)[0] * r).sum())
+    y, c = L.linear_forward(x, w, b, True)
+    dx, dw, db = L.linear_backward(r, c, w, True)
+    assert _rel(dx, _fd(f, x)) < 1e-7
+    assert _rel(dw, _fd(f, w)) < 1e-7
+    assert _rel(db, _fd(f, b)) < 1e-7
+
+
+def test_linear_backward_uses_the_weights_it_is_given():
+    # dx must come from the weights passed to backward, dw and the mask from the stored forward
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((3, 5)); w0 = rng.standard_normal((4, 5)); w1 = rng.standard_normal((4, 5))
+    b = rng.standard_normal(4); dy = rng.standard_normal((3, 4))
+    y, c = L.linear_forward(x, w0, b, True)
+    dx, dw, db = L.linear_backward(dy, c, w1, True)
+    dz = dy * (x @ w0.T + b > 0)
+    assert np.allclose(dx, dz @ w1)
+    assert np.allclose(dw, dz.T @ x)
+
+
+# ------------------------------------------------------------------ convolution
+@pytest.mark.parametrize("R,stride,pad,relu", [(3, 1, 1, True), (3, 1, 1, False), (1, 1, 0, False),
+                                               (3, 2, 1, True), (1, 2, 0, False), (7, 2, 3, True)])
+def test_conv_against_library_autograd(R, stride, pad, relu):
+    rng = np.random.default_rng(5)
+    n, h, wd, ci, co = 2, 9, 8, 3, 4
+    x = rng.standard_normal((n, h, wd, ci)); w = rng.standard_normal((co, R, R, ci)); b = rng.standard_normal(co)
+    y, c = L.conv_forward(x, w, b, stride, pad, relu)
+    dy = rng.standard_normal(y.shape)
+    dx, dw, db = L.conv_backward(dy, c, w, stride, pad, relu)
+    xt = torch.tensor(x.transpose(0, 3, 1, 2).copy(), requires_grad=True)
+    wt = torch.tensor(w.transpose(0, 3, 1, 2).copy(), requires_grad=True)
+    bt = torch.tensor(b, requires_grad=True)
+    yt = F.conv2d(xt, wt, bt, stride=stride, padding=pad)
+    if relu:
+        yt = F.relu(yt)
+    yt.backward(torch.tensor(dy.transpose(0, 3, 1, 2).copy()))
+    assert y.shape == tuple(yt.permute(0, 2, 3, 1).shape)
+    assert _rel(y, yt.detach().permute(0, 2, 3, 1).numpy()) < 1e-12
+    assert _rel(dx, xt.grad.permute(0, 2, 3, 1).numpy()) < 1e-12
+    assert _rel(dw, wt.grad.permute(0, 2, 3, 1).numpy()) < 1e-12
+    assert _rel(db, bt.grad.numpy()) < 1e-12
+
+
+def test_conv_brute_force_tiny():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((1, 4, 5, 2)); w = rng.standard_normal((3, 3, 3, 2)); b = rng.standard_normal(3)
+    y, _ = L.conv_forward(x, w, b, 1, 1, False)
+    for p in range(4):
+        for q in range(5):
+            for o in range(3):
+                acc = b[o]
+                for r in range(3):
+                    for s in range(3):
+                        hh, ww = p + r - 1, q + s - 1
+                        if 0 <= hh < 4 and 0 <= ww < 5:
+                            for ch in range(2):
+                                acc += x[0, hh, ww, ch] * w[o, r, s, ch]
+                assert abs(acc - y[0, p, q, o]) < 1e-12
+
+
+def test_conv_1x1_is_a_linear_layer():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((2, 3, 3, 5)); w = rng.standard_normal((4, 1, 1, 5)); b = rng.standard_normal(4)
+    y, _ = L.conv_forward(x, w, b, 1, 0, True)
+    y2, _ = L.linear_forward(x.reshape(-1, 5), w.reshape(4, 5), b, True)
+    assert np.allclose(y.reshape(-1, 4), y2)
+
+
+# ------------------------------------------------------------------ max pooling
+@pytest.mark.parametrize("k,stride", [(2, 2), (3, 2)])
+def test_maxpool_against_library_autograd(k, stride):
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((2, 8, 9, 3))
+    y, c = L.maxpool_forward(x, k, stride)
+    dy = rng.standard_normal(y.shape)
+    dx = L.maxpool_backward(dy, c, k, stride)
+    xt = torch.tensor(x.transpose(0, 3, 1, 2).copy(), requires_grad=True)
+    yt = F.max_pool2d(xt, k, stride)
+    yt.backward(torch.tensor(dy.transpose(0, 3, 1, 2).copy()))
+    assert np.array_equal(y, yt.detach().permute(0, 2, 3, 1).numpy())
+    assert np.allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy())
+
+
+def test_maxpool_gradient_goes_to_one_winner_per_window():
+    x = np.zeros((1, 2, 2, 1)); x[0, 1, 0, 0] = 2.0
+    y, c = L.maxpool_forward(x, 2, 2)
+    dx = L.maxpool_backward(np.ones_like(y), c, 2, 2)
+    assert y[0, 0, 0, 0] == 2.0 and dx[0, 1, 0, 0] == 1.0 and dx.sum() == 1.0
+    # all-equal window: exactly one element (the first) receives the gradient
+    y, c = L.maxpool_forward(np.zeros((1, 2, 2, 1)), 2, 2)
+    dx = L.maxpool_backward(np.ones_like(y), c, 2, 2)
+    assert dx.sum() == 1.0 and dx[0, 0, 0, 0] == 1.0

@@ -1,0 +1,193 @@
+"""Pins of the oracle's stage and pipeline: micro-batching, textbook SGD, momentum closed form."""
+import copy
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import pipeline, schedule as S
+from oracle.stage import Stage
+from workloads import Config, get_config, init_params, make_batch
+from workloads.configs import conv, linear, maxpool, softmax_ce
+
+torch.set_default_dtype(torch.float64)
+
+
+def _small_conv_cfg(K=1, N=2, M=4):
+    layers = [conv(6, 6, 2, 4), maxpool(6, 6, 4), conv(3, 3, 4, 4), linear(36, 8, True),
+              linear(8, 5, False), softmax_ce(5)]
+    if K == 1:
+        stages = [layers]
+    elif K == 2:
+        stages = [layers[:2], layers[2:]]
+    else:
+        stages = [layers[:2], layers[2:3], layers[3:]]
+    return Config(name="t", dtype="f32", M=M, N=N, stages=stages, in_shape=(6, 6, 2), classes=5,
+                  seed=11, lr=0.05, momentum=0.9)
+
+
+def _torch_net_loss(cfg, params, x, labels):
+    """Whole-network mean cross-entropy written with library ops (independent of the oracle)."""
+    a = torch.tensor(np.asarray(x, dtype=np.float64))
+    for st, ps in zip(cfg.stages, params):
+        for spec, p in zip(st, ps):
+            k = spec["kind"]
+            if k == "linear":
+                a = F.linear(a.reshape(a.shape[0], -1), p["w"], p["b"])
+                if spec["relu"]:
+                    a = F.relu(a)
+            elif k == "conv":
+                a = F.conv2d(a.permute(0, 3, 1, 2), p["w"].permute(0, 3, 1, 2), p["b"],
+                             stride=spec["stride"], padding=spec["pad"]).permute(0, 2, 3, 1)
+                if spec["relu"]:
+                    a = F.relu(a)
+            elif k == "maxpool":
+                a = F.max_pool2d(a.permute(0, 3, 1, 2), spec["k"], spec["stride"]).permute(0, 2, 3, 1)
+            elif k == "softmax_ce":
+                return F.cross_entropy(a, torch.tensor(np.asarray(labels, dtype=np.int64)))
+    raise AssertionError
+
+
+def _torch_params(params):
+    return [[{k: torch.tensor(np.asarray(v, dtype=np.float64), requires_grad=True) for k, v in p.items()}
+             for p in ps] for ps in params]
+
+
+@pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=2, N=2)])
+def test_micro_batched_forward_and_gradients_equal_full_batch(cfg_fn):
+    cfg = cfg_fn()
+    params = init_params(cfg, bias_std=0.1)
+    x, y = make_batch(cfg, 0)
+    micro = cfg.micro
+    stages = [Stage(cfg.stages[s], params[s], cfg.lr, cfg.momentum, cfg.M, cfg.N) for s in range(cfg.K)]
+    outs, losses = [], []
+    for j in range(cfg.N):
+        a = x[j * micro:(j + 1) * micro]
+        for s, st in enumerate(stages):
+            if s == cfg.K - 1:
+                a, loss = st.forward_micro(j, a, y[j * micro:(j + 1) * micro])
+                losses.append(loss)
+            else:
+                a = st.forward_micro(j, a)
+        outs.append(a)
+    g = None
+    for st in reversed(stages):
+        g = st.backward(list(range(cfg.N)), g)
+    # library evaluation of the WHOLE mini-batch at once
+    tp = _torch_params(params)
+    lt = _torch_net_loss(cfg, tp, x, y)
+    lt.backward()
+    assert abs(np.mean(losses) - lt.item()) < 1e-12
+    for st, ps in zip(stages, tp):
+        for g_o, p_t in zip(st.grads, ps):
+            if g_o is None:
+                continue
+            for k in g_o:
+                ref = p_t[k].grad.numpy()
+                assert np.max(np.abs(g_o[k] - ref)) <= 1e-12 * (1 + np.max(np.abs(ref))), k
+
+
+@pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=1, N=2)])
+def test_single_worker_equals_textbook_sgd_momentum(cfg_fn):
+    cfg = cfg_fn()
+    flat_layers = [l for st in cfg.stages for l in st]
+    cfg1 = copy.copy(cfg)
+    cfg1.stages = [flat_layers]                       # K = 1
+    params = init_params(cfg, bias_std=0.1)
+    flat_params = [[p for ps in params for p in ps]]
+    steps = 20 if cfg.name == "tiny_mlp_f32" else 6
+    batches = [make_batch(cfg, i) for i in range(steps)]
+    res = pipeline.run(cfg1, flat_params, batches)
+    tp = _torch_params(flat_params)
+    leaves = [p[k] for p in tp[0] for k in p]
+    opt = torch.optim.SGD(leaves, lr=cfg.lr, momentum=cfg.momentum)
+    for i, (x, y) in enumerate(batches):
+        opt.zero_grad()
+        loss = _torch_net_loss(cfg1, tp, x, y)
+        loss.backward()
+        opt.step()
+        assert abs(loss.item() - res["losses"][i]) < 1e-10 * max(1.0, abs(loss.item()))
+    for p_o, p_t in zip(res["stages"][0].params, tp[0]):
+        for k in p_o:
+            assert np.allclose(p_o[k], p_t[k].detach().numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_first_minibatch_of_a_pipeline_equals_a_sequential_step():
+    # while every worker still holds the initial weights (no update has happened anywhere), the
+    # first mini-batch's loss and gradients are those of the plain network
+    cfg = get_config("tiny_mlp_f32")
+    params = init_params(cfg, bias_std=0.1)
+    batches = [make_batch(cfg, i) for i in range(3)]
+    trace = {}
+    res = pipeline.run(cfg, params, batches, trace=trace)
+    tp = _torch_params(params)
+    lt = _torch_net_loss(cfg, tp, *batches[0])
+    lt.backward()
+    assert abs(res["losses"][0] - lt.item()) < 1e-12
+    for s in range(cfg.K):
+        for g_o, p_t in zip(trace[("G", 1, -1, s)], tp[s]):
+            if g_o is not None:
+                assert np.allclose(g_o["w"], p_t["w"].grad.numpy(), atol=1e-13)
+
+
+def test_backward_differentiates_at_the_latest_weights():
+    # A worker forwards with w0, is then given other weights, and backpropagates: dx must use the
+    # new weights while dw uses the stored activations (Challenge 1, Solution).
+    rng = np.random.default_rng(0)
+    spec = [linear(6, 5, True), linear(5, 4, False)]
+    p0 = [{"w": rng.standard_normal((5, 6)), "b": rng.standard_normal(5)},
+          {"w": rng.standard_normal((4, 5)), "b": rng.standard_normal(4)}]
+    st = Stage(spec, p0, 0.1, 0.0, 4, 2)
+    xs = [rng.standard_normal((2, 6)) for _ in range(2)]
+    for j in range(2):
+        st.forward_micro(j, xs[j])
+    w_new = [rng.standard_normal((5, 6)), rng.standard_normal((4, 5))]
+    st.params[0]["w"][...] = w_new[0]
+    st.params[1]["w"][...] = w_new[1]
+    dy = rng.standard_normal((4, 4))
+    dx = st.backward([0, 1], dy)
+    x = np.concatenate(xs)
+    h_pre = x @ p0[0]["w"].T + p0[0]["b"]
+    h = np.maximum(h_pre, 0)
+    dh = (dy @ w_new[1]) * (h_pre > 0)
+    assert np.allclose(dx, dh @ w_new[0])
+    assert np.allclose(st.grads[1]["w"], dy.T @ h)
+    assert np.allclose(st.grads[0]["w"], dh.T @ x)
+
+
+def test_momentum_closed_form_for_constant_gradient():
+    spec = [linear(3, 2, False)]
+    st = Stage(spec, [{"w": np.zeros((2, 3)), "b": np.zeros(2)}], 0.1, 0.9, 2, 1)
+    g = np.arange(6, dtype=np.float64).reshape(2, 3) + 1
+    w_want = np.zeros((2, 3))
+    for t in range(1, 8):
+        st.grads = [{"w": g.copy(), "b": np.ones(2)}]
+        st.update()
+        buf_t = g * (1 - 0.9 ** t) / (1 - 0.9)
+        assert np.allclose(st.bufs[0]["w"], buf_t)
+        w_want -= 0.1 * buf_t
+        assert np.allclose(st.params[0]["w"], w_want)
+    assert st.version == 7
+
+
+def test_unequal_micro_batches_rejected_and_slot_reuse_rejected():
+    with pytest.raises(ValueError):
+        Stage([linear(3, 2, False)], [{"w": np.zeros((2, 3)), "b": np.zeros(2)}], 0.1, 0.9, 10, 4)
+    st = Stage([linear(3, 2, False)], [{"w": np.zeros((2, 3)), "b": np.zeros(2)}], 0.1, 0.9, 4, 2)
+    st.forward_micro(0, np.zeros((2, 3)))
+    with pytest.raises(RuntimeError):
+        st.forward_micro(0, np.zeros((2, 3)))
+
+
+def test_pipeline_version_log_matches_simulation_and_losses_are_finite():
+    cfg = get_config("tiny_mlp_f32")
+    params = init_params(cfg)
+    batches = [make_batch(cfg, i) for i in range(cfg.steps)]
+    res = pipeline.run(cfg, params, batches)
+    assert res["ops"] == S.simulate(cfg.K, cfg.N, cfg.steps)["ops"]
+    assert all(np.isfinite(res["losses"]))
+    assert [st.version for st in res["stages"]] == [cfg.steps] * cfg.K
+    # K=2 differs from sequential SGD only through forwards that saw newer weights on worker 2:
+    # the loss curve must still go down on this easy problem
+    assert np.mean(res["losses"][-5:]) < np.mean(res["losses"][:5])
