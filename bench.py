@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the TiMePReSt stage-training hot path on one MI355X.
+
+A step is one mini-batch through the whole path: on each of the K stages the N micro-batch forward
+passes, the single backward pass with the latest weights and the in-place momentum update, issued
+in nF1B order on K HIP streams by tmps_schedule_run.  Inputs are synthetic (seeded Gaussian inputs,
+uniform labels, He-normal weights) and resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job samples/s, the roofline of the dominant kernel class (measured
+with HIP events on the kernels' own streams in a second pass of the same workload), and the CPU
+oracle timed on a bounded sample of the same workload as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def algorithmic_work(cfg):
+    """Per kernel class and per mini-batch: (launches, FLOPs, algorithmic bytes) from the shapes alone.
+
+    Dense GEMMs count 2*rows*Din*Dout FLOPs and their operand/result bytes once; the update counts
+    22 bytes per parameter in bf16 stages (read w, buf, g fp32; write w, buf fp32 and the bf16 copy)
+    or 20 in fp32 stages."""
+    asz = 2 if cfg.dtype == "bf16" else 4
+    M, N, mb = cfg.M, cfg.N, cfg.micro
+    work = {}
+
+    def add(k, launches, flops, nbytes):
+        a = work.setdefault(k, [0, 0.0, 0.0])
+        a[0] += launches
+        a[1] += flops
+        a[2] += nbytes
+
+    for si, st in enumerate(cfg.stages):
+        P = 0
+        for li, sp in enumerate(st):
+            if sp["kind"] == "linear":
+                din, dout = sp["din"], sp["dout"]
+                P += din * dout + dout
+                add("dense_fwd", N, N * 2.0 * mb * din * dout, N * (mb * din * asz + din * dout * asz + mb * dout * asz))
+                add("dense_wgrad", 1, 2.0 * M * din * dout, M * (din + dout) * asz + (din * dout + dout) * 4)
+                if not (si == 0 and li == 0):
+                    add("dense_dgrad", 1, 2.0 * M * din * dout, M * (din + dout) * asz + din * dout * asz)
+            elif sp["kind"] == "conv":
+                ho = (sp["h"] + 2 * sp["pad"] - sp["r"]) // sp["stride"] + 1
+                wo = (sp["w"] + 2 * sp["pad"] - sp["s"]) // sp["stride"] + 1
+                kk = sp["r"] * sp["s"] * sp["cin"]
+                P += kk * sp["cout"] + sp["cout"]
+                x_e, y_e = sp["h"] * sp["w"] * sp["cin"], ho * wo * sp["cout"]
+                add("conv_fwd", N, N * 2.0 * mb * ho * wo * kk * sp["cout"], N * (mb * (x_e + y_e) * asz + kk * sp["cout"] * asz))
+                add("conv_wgrad", 1, 2.0 * M * ho * wo * kk * sp["cout"], M * (x_e + y_e) * asz + kk * sp["cout"] * 4)
+                if not (si == 0 and li == 0):
+                    add("conv_dgrad", 1, 2.0 * M * ho * wo * kk * sp["cout"], M * (x_e + y_e) * asz + kk * sp["cout"] * asz)
+            elif sp["kind"] == "maxpool":
+                ho, wo = (sp["h"] - sp["k"]) // sp["stride"] + 1, (sp["w"] - sp["k"]) // sp["stride"] + 1
+                x_e, y_e = sp["h"] * sp["w"] * sp["c"], ho * wo * sp["c"]
+                add("pool_fwd", N, 0.0, N * mb * (x_e + y_e) * asz)
+                add("pool_bwd", 1, 0.0, M * (2 * x_e + y_e) * asz)
+            elif sp["kind"] == "softmax_ce":
+                c = sp["classes"]
+                add("softmax_ce", N, 0.0, N * mb * (c * 4 + c * asz + 8))
+        add("update", 1, 0.0, P * (22 if cfg.dtype == "bf16" else 20))
+    return work
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="mlp4x1024_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=0, help="mini-batches the oracle is timed on (0: about 15 s worth)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the stage-training path on ONE GPU (K stages on K streams of the same "
+              "device); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2410_14312_amd as T
+    from workloads import get_config, init_params, make_batch
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    cfg = get_config(args.workload)
+    params = init_params(cfg)
+    pipe = T.Pipeline(cfg, params)
+    n_distinct = min(32, max(args.steps, args.warmup, 1))
+    distinct = [make_batch(cfg, i) for i in range(n_distinct)]
+
+    def resident(n):
+        x, y = pipe.upload([distinct[i % n_distinct] for i in range(n)])
+        return x, y, torch.zeros(n, dtype=torch.float32, device=pipe.device)
+
+    xw, yw, lw = resident(max(args.warmup, 1))
+    xs, ys, ls = resident(args.steps)
+    torch.cuda.synchronize()
+    if args.warmup > 0:
+        pipe.run_device(xw, yw, args.warmup, lw, want_log=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pipe.run_device(xs, ys, args.steps, ls, want_log=False)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    losses = ls.cpu().numpy()
+    assert np.all(np.isfinite(losses)), "non-finite loss in the timed run"
+    value = cfg.M * args.steps / dt
+
+    # second pass of the same workload with per-kernel event timing on the kernels' streams
+    T.profile_enable(True)
+    pipe.run_device(xs, ys, args.steps, ls, want_log=False)
+    torch.cuda.synchronize()
+    prof = T.profile_read()
+    T.profile_enable(False)
+    work = algorithmic_work(cfg)
+    kernels = []
+    for k, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        per = work.get(k)
+        ent = {"class": k, "launches_per_step": cnt / args.steps, "avg_us": 1e3 * ms / cnt, "ms_per_step": ms / args.steps}
+        if per and per[0]:
+            ent["gflop_per_launch"] = per[1] / per[0] / 1e9
+            ent["mbytes_per_launch"] = per[2] / per[0] / 1e6
+            sec = ms / cnt / 1e3
+            ent["tflops"] = per[1] / per[0] / sec / 1e12
+            ent["gbs"] = per[2] / per[0] / sec / 1e9
+        kernels.append(ent)
+    kernels.sort(key=lambda e: -e["ms_per_step"])
+    dom = kernels[0]
+    if dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce"):
+        roof = {"kernel": dom["class"], "bound": "hbm", "achieved": dom.get("gbs", 0.0), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": dom.get("gbs", 0.0) / HBM_PEAK_GBS, "traffic": None}
+    else:
+        roof = {"kernel": dom["class"], "bound": "mfma", "achieved": dom.get("tflops", 0.0),
+                "peak": MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3, "unit": "TFLOP/s",
+                "frac": dom.get("tflops", 0.0) / (MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3),
+                "traffic": None}
+    roof["avg_launch_us"] = dom["avg_us"]
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pipeline as opipe
+        cores = len(os.sched_getaffinity(0))
+        n_cpu = args.cpu_steps
+        if n_cpu <= 0:
+            t1 = time.perf_counter()
+            opipe.run(cfg, params, distinct[:2])
+            per = (time.perf_counter() - t1) / 2
+            n_cpu = int(max(2, min(n_distinct, 15.0 / max(per, 1e-3))))
+        t1 = time.perf_counter()
+        opipe.run(cfg, params, distinct[:n_cpu])
+        dc = time.perf_counter() - t1
+        cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
+               "sample": "%d mini-batches of the same workload through the numpy fp64 oracle pipeline (%.1f s)" % (n_cpu, dc)}
+
+    flops_step = sum(v[1] for v in work.values())
+    out = {
+        "metric": "training samples/sec (all K stages, nF1B) on 1 MI355X",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "mini_batch": cfg.M, "micro_batches": cfg.N, "stages": cfg.K,
+                   "version_difference": T.version_diff_simulated(cfg.K, cfg.N)},
+        "mfma_frac_of_bf16_peak_end_to_end": flops_step / (dt / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "final_loss": float(losses[-1]),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

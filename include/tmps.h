@@ -1,0 +1,202 @@
+/*
+ * tmps.h -- C ABI of libtmps: the stage-training hot path of TiMePReSt
+ * (arXiv 2410.14312) on AMD MI355X (gfx950).
+ *
+ * The paper trains a DNN as a pipeline of W workers, each holding consecutive
+ * layers (section "Model Architecture").  A mini-batch of M samples is split
+ * into N equal micro-batches; every micro-batch is forwarded on its own, and
+ * once the N forwards of a mini-batch are done ONE backward pass is made over
+ * the whole mini-batch, differentiating at the weights as they are at that
+ * moment (sections "Challenge 1: Staleness of Weights" and "Challenge 2: High
+ * Training Time"); the weights are then updated in place (the update rule for
+ * TiMePReSt).  Workers order their tasks by nF1B (section "Work Scheduling").
+ *
+ * Conventions
+ *   - Every function returns TMPS_OK (0) or a negative TMPS_E* code unless
+ *     stated otherwise; tmps_last_error() gives thread-local text for the last
+ *     failure.  Nothing throws or aborts across this boundary.
+ *   - "device" pointers are HIP device memory, "host" pointers ordinary
+ *     memory.  The caller owns ALL device memory and all streams; the library
+ *     allocates only small host structs, freed by tmps_stage_destroy().
+ *   - Calls that take a stream are asynchronous on it and never synchronise
+ *     the device; tmps_schedule_run() synchronises its streams before it
+ *     returns.  A stream argument is a hipStream_t passed as void*.
+ *   - Activations are row-major [rows, D] (dense) or channels-last
+ *     [rows, H, W, C]; dense weights [Dout, Din]; filters [Cout, R, S, Cin].
+ *   - TMPS_F32: activations, gradients, weights fp32.  TMPS_BF16_F32MASTER:
+ *     activations and back-propagated gradients bfloat16, fp32 accumulation,
+ *     fp32 master weights, momentum and weight gradients, plus a bf16 working
+ *     copy of the weights that the contractions read.
+ */
+#ifndef TMPS_H
+#define TMPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TMPS_OK = 0,
+    TMPS_EINVAL = -1,       /* null pointer, bad enum, non-positive size */
+    TMPS_ESHAPE = -2,       /* layer shapes do not chain / operand layout not accepted */
+    TMPS_EMICRO = -3,       /* micro-batches of a mini-batch are not equal-sized */
+    TMPS_ESLOT = -4,        /* stash slot in use, not filled, or not a whole mini-batch group */
+    TMPS_ESTASH = -5,       /* stash too small for the schedule */
+    TMPS_EHIP = -6,         /* a HIP call failed */
+    TMPS_EUNSUPPORTED = -7, /* layer kind / combination not built */
+    TMPS_ECAP = -8          /* output array too small */
+};
+
+enum { TMPS_F32 = 0, TMPS_BF16_F32MASTER = 1 };
+
+/* Layer kinds and the meaning of tmps_layer_desc.dims */
+enum {
+    TMPS_LINEAR = 1,     /* dims = {Din, Dout}; flags TMPS_FLAG_RELU */
+    TMPS_CONV2D = 2,     /* dims = {H, W, Cin, Cout, R, S, stride, pad}; flags TMPS_FLAG_RELU */
+    TMPS_MAXPOOL = 3,    /* dims = {H, W, C, k, stride} (no padding) */
+    TMPS_SOFTMAX_CE = 4  /* dims = {classes}; only as the last layer of the last stage */
+};
+enum { TMPS_FLAG_RELU = 1 };
+
+typedef struct tmps_stage tmps_stage; /* opaque */
+
+typedef struct {
+    int32_t kind;
+    int32_t dims[8];
+    int32_t flags;
+} tmps_layer_desc;
+
+typedef struct {
+    int32_t dtype;        /* TMPS_F32 | TMPS_BF16_F32MASTER */
+    int32_t micro_batch;  /* M/N samples per forward */
+    int32_t n_micro;      /* N */
+    int32_t max_stash;    /* stash capacity in micro-batches; a positive multiple of n_micro */
+    int32_t is_last;      /* stage ends in TMPS_SOFTMAX_CE */
+    int32_t borrow_input; /* 1: the stage keeps only the pointer x given to tmps_forward_micro,
+                             which must stay valid and unchanged until the slot's backward pass,
+                             and the N inputs of a mini-batch must be consecutive in memory;
+                             0: the input is copied into the stash */
+    float lr;             /* learning rate (eta of the update rule) */
+    float momentum;       /* mu: buf <- mu*buf + g; w <- w - lr*buf (0 gives the paper's plain SGD) */
+} tmps_stage_cfg;
+
+/* ---- stage construction (section "Model Architecture": consecutive layers on one accelerator) ----
+ *
+ * tmps_stage_bytes: sizes in bytes of the four caller-allocated device regions.
+ *   params : [P fp32 master values][P bf16 working copy, TMPS_BF16_F32MASTER only]
+ *   state  : [P fp32 momentum][P fp32 weight gradient]
+ *   stash  : activations of max_stash micro-batches kept for the backward pass
+ *   scratch: gradient ping-pong buffers of one mini-batch and reduction workspace
+ * P = tmps_stage_param_count().  All regions must be 256-byte aligned.  Any out pointer may be
+ * NULL.  Errors: TMPS_EINVAL, TMPS_ESHAPE (layers do not chain), TMPS_EMICRO, TMPS_EUNSUPPORTED. */
+int tmps_stage_bytes(const tmps_layer_desc* layers, int n_layers, const tmps_stage_cfg* cfg,
+                     size_t* param_bytes, size_t* state_bytes, size_t* stash_bytes,
+                     size_t* scratch_bytes);
+
+/* Create a stage over caller-owned device regions of at least the sizes above.  Touches no
+ * device memory: the caller writes the fp32 master parameters (see tmps_stage_param_offset),
+ * zeroes `state`, then calls tmps_stage_sync_params().  *out is a host object. */
+int tmps_stage_create(tmps_stage** out, const tmps_layer_desc* layers, int n_layers,
+                      const tmps_stage_cfg* cfg, void* params, void* state, void* stash,
+                      void* scratch);
+void tmps_stage_destroy(tmps_stage* stage);
+
+/* Number of trainable scalars P of the stage (weights and biases of all its layers). */
+int64_t tmps_stage_param_count(const tmps_stage* stage);
+/* Position of a layer's weight (which = 0) or bias (which = 1) inside the flat arrays of P
+ * elements (master, working copy, momentum, gradient all use the same order).  A layer without
+ * parameters gives count 0. */
+int tmps_stage_param_offset(const tmps_stage* stage, int layer, int which, int64_t* offset,
+                            int64_t* count);
+/* Per-sample element counts of the stage's input and output. */
+int64_t tmps_stage_input_elems(const tmps_stage* stage);
+int64_t tmps_stage_output_elems(const tmps_stage* stage);
+/* Refresh the bf16 working copy from the fp32 master values (no-op for TMPS_F32). */
+int tmps_stage_sync_params(tmps_stage* stage, void* hip_stream);
+/* Device address inside the stash of the stage output of `slot` (micro_batch x output elements,
+ * activation dtype; fp32 logits on the last stage).  Valid until the slot's backward pass; the
+ * outputs of the slots of one mini-batch group are consecutive. */
+void* tmps_stage_output_ptr(const tmps_stage* stage, int slot);
+/* Number of weight updates applied so far (the stage's weight version). */
+long tmps_stage_version(const tmps_stage* stage);
+
+/* ---- the three steps of a stage's training step ----
+ *
+ * Forward pass of one micro-batch (section "Challenge 2", Solution): runs the stage's layers on
+ * x (device, micro_batch rows, activation dtype) with the stage's CURRENT weights and keeps in
+ * stash slot `slot` (0 <= slot < max_stash) what the backward pass needs.  y (device, may be
+ * NULL) receives a copy of the stage output.  On the last stage `labels` (device int32,
+ * micro_batch entries) is required, y receives fp32 logits, and loss_out (device float, may be
+ * NULL) the mean cross-entropy of the micro-batch.  Errors: TMPS_ESLOT if the slot is in use. */
+int tmps_forward_micro(tmps_stage* stage, int slot, const void* x, void* y, const int32_t* labels,
+                       float* loss_out, void* hip_stream);
+
+/* The single backward pass of a mini-batch (section "Challenge 1", Solution): slots must be the
+ * n_micro slots g*N .. g*N+N-1 of one group, all filled.  dy (device, M = N*micro_batch rows of
+ * the stage output shape, gradient dtype; NULL on the last stage, whose error signal is the
+ * gradient of the average of the N micro-batch losses) is propagated through the layers in
+ * reverse using the stashed activations and the weights AS THEY ARE NOW; weight gradients are
+ * summed over the N micro-batches into `state`; dx (device, M rows of the input shape; may be
+ * NULL) receives the gradient w.r.t. the stage input.  Frees the slots. */
+int tmps_backward(tmps_stage* stage, const int* slots, int n_slots, const void* dy, void* dx,
+                  void* hip_stream);
+
+/* In-place update (the update rule for TiMePReSt, with momentum): buf <- mu*buf + g,
+ * w <- w - lr*buf on the fp32 master values, refreshes the bf16 working copy, version += 1. */
+int tmps_update(tmps_stage* stage, void* hip_stream);
+
+/* ---- nF1B schedule (sections "Work Scheduling" and "Multiple Sequence Problem") ----
+ *
+ * Host-only time-point simulation of W workers, N micro-batches per mini-batch.  Each task is
+ * 7 int32: {time-point (from 1), worker (from 0), kind (0 forward, 1 backward+update),
+ * mini-batch (from 1), micro-batch (from 0; -1 for a backward), number of updates the worker
+ * had applied before the task, whole-network version of the pass the task belongs to}.  The
+ * whole-network version counts the mini-batches whose backward pass had left worker 0 before
+ * the time-point at which the pass started.  Tasks come in (time-point, worker) order.
+ * Returns the number of tasks (also when ops_out is NULL), or TMPS_ECAP / TMPS_EINVAL. */
+int tmps_schedule_plan(int W, int N, int n_minibatches, int32_t* ops_out, size_t cap_ops);
+/* Mini-batch groups worker `stage` must be able to stash under this schedule. */
+int tmps_schedule_stash_groups(int W, int N, int stage);
+/* Closed form of the paper for the version difference, floor((W+N-2)/N); TMPS_EINVAL outside
+ * its domain W, N >= 2. */
+int tmps_version_diff_formula(int W, int N);
+/* Steady-state version difference found by simulation. */
+int tmps_version_diff_simulated(int W, int N);
+
+/* Run n_minibatches through K stages on K streams of one GPU in nF1B order.  stages[s] must
+ * have been created with n_micro = N, borrow_input = 1 for s > 0, and enough stash
+ * (tmps_schedule_stash_groups).  inputs: device, n_minibatches*M rows of stage 0's input;
+ * labels: device int32, n_minibatches*M.  losses_out: device float[n_minibatches], the mean
+ * of the N micro-batch losses.  version_log_out: host int32[7 * tasks] as tmps_schedule_plan,
+ * except that field 5 is read from the stage objects as the tasks are issued; may be NULL.
+ * Cross-stage dependencies are HIP events; the call returns after all K streams are idle. */
+int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
+                      const int32_t* labels, void** hip_streams, float* losses_out,
+                      int32_t* version_log_out);
+
+/* ---- measurement aid (not part of the method) ----
+ *
+ * While enabled, every kernel launch made by the calls above is bracketed by two timing events
+ * recorded on the stream it is launched on.  tmps_profile_read() waits for the recorded events,
+ * adds the elapsed milliseconds and launch counts per kernel class into total_ms[] / launches[]
+ * (host arrays of n_classes >= TMPS_KERNEL_CLASSES entries), clears the record and returns
+ * TMPS_KERNEL_CLASSES.  A weight-gradient launch that splits its contraction counts the GEMM and
+ * its slice reduction as one launch.  The event pairs serialise nothing but add host overhead:
+ * time throughput with profiling off. */
+enum {
+    TMPS_KC_DENSE_FWD = 0, TMPS_KC_DENSE_DGRAD, TMPS_KC_DENSE_WGRAD, TMPS_KC_CONV_FWD,
+    TMPS_KC_CONV_DGRAD, TMPS_KC_CONV_WGRAD, TMPS_KC_SOFTMAX_CE, TMPS_KC_UPDATE, TMPS_KC_POOL_FWD,
+    TMPS_KC_POOL_BWD, TMPS_KC_RELU_MASK, TMPS_KC_REDUCE, TMPS_KC_COPY, TMPS_KERNEL_CLASSES
+};
+int tmps_profile_enable(int on);
+int tmps_profile_read(double* total_ms, int64_t* launches, int n_classes);
+
+const char* tmps_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TMPS_H */

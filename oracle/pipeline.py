@@ -13,18 +13,21 @@ from . import schedule as S
 from .stage import Stage
 
 
-def run(cfg, params, batches, trace=None):
+def run(cfg, params, batches, trace=None, precision=None):
     """Train `len(batches)` mini-batches.
 
     cfg: a workloads.Config (shape tables only); params: per stage, per layer dicts of arrays;
-    batches: list of (x [M, ...], labels [M]).  trace: optional dict that receives every task's
+    batches: list of (x [M, ...], labels [M]).  precision: storage policy ("f64" or "bf16", see
+    oracle/precision.py); by default the one the configuration names.  trace: optional dict that receives every task's
     tensors under (kind, b, j, stage) keys.
     Returns dict(losses=[per mini-batch mean of the micro-batch losses], ops=version log,
     stages=[Stage]).
     """
     K, N, M = cfg.K, cfg.N, cfg.M
     micro = M // N
-    stages = [Stage(cfg.stages[s], params[s], cfg.lr, cfg.momentum, M, N) for s in range(K)]
+    if precision is None:
+        precision = "bf16" if cfg.dtype == "bf16" else "f64"
+    stages = [Stage(cfg.stages[s], params[s], cfg.lr, cfg.momentum, M, N, precision) for s in range(K)]
     sim = S.simulate(K, N, len(batches))
     fwd_out = {}
     bwd_out = {}

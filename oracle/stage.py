@@ -8,14 +8,20 @@ with the stage's weights as they are at that moment (no weight version is
 kept from the forward pass); then the weights are updated in place
 (update rule of TiMePReSt with SGD; momentum, which the paper leaves open, is
 buf <- mu*buf + g, w <- w - lr*buf, buf_0 = 0).
+
+precision="bf16" applies the storage policy of oracle/precision.py: the weights the layers read are
+the bfloat16 rounding of the master weights, layer outputs and propagated gradients are rounded
+when stored (the logits, which feed the loss directly, are not); weight gradients, momentum and
+master weights stay unrounded.
 """
 import numpy as np
 
 from . import layers as L
+from .precision import storage_rounding
 
 
 class Stage:
-    def __init__(self, layer_specs, params, lr, momentum, M, N):
+    def __init__(self, layer_specs, params, lr, momentum, M, N, precision="f64"):
         if M % N != 0:
             raise ValueError("mini-batch size must be a multiple of the number of micro-batches")
         self.specs = layer_specs
@@ -26,6 +32,7 @@ class Stage:
         self.is_last = layer_specs[-1]["kind"] == "softmax_ce"
         self.stash = {}
         self.version = 0
+        self.q = storage_rounding(precision)
 
     # -- forward of one micro-batch -------------------------------------------------------
     def forward_micro(self, slot, x, labels=None):
@@ -33,14 +40,19 @@ class Stage:
         if slot in self.stash:
             raise RuntimeError("stash slot %r is in use" % (slot,))
         caches = []
-        a = np.asarray(x, dtype=np.float64)
+        q = self.q
+        a = q(x)
         loss = None
-        for spec, p in zip(self.specs, self.params):
+        for li, (spec, p) in enumerate(zip(self.specs, self.params)):
             k = spec["kind"]
+            feeds_loss = li + 1 < len(self.specs) and self.specs[li + 1]["kind"] == "softmax_ce"
             if k == "linear":
-                a, c = L.linear_forward(a, p["w"], p["b"], spec["relu"])
+                a, c = L.linear_forward(a, q(p["w"]), p["b"], spec["relu"])
+                if not feeds_loss:
+                    a = c["y"] = q(a)
             elif k == "conv":
-                a, c = L.conv_forward(a, p["w"], p["b"], spec["stride"], spec["pad"], spec["relu"])
+                a, c = L.conv_forward(a, q(p["w"]), p["b"], spec["stride"], spec["pad"], spec["relu"])
+                a = c["y"] = q(a)
             elif k == "maxpool":
                 a, c = L.maxpool_forward(a, spec["k"], spec["stride"])
             elif k == "softmax_ce":
@@ -63,19 +75,22 @@ class Stage:
         dxs = []
         for i, slot in enumerate(slots):
             caches = self.stash.pop(slot)
-            g = None if dy is None else np.asarray(dy[i * micro:(i + 1) * micro], dtype=np.float64)
+            q = self.q
+            g = None if dy is None else q(dy[i * micro:(i + 1) * micro])
             for li in range(len(self.specs) - 1, -1, -1):
                 spec, p, c = self.specs[li], self.params[li], caches[li]
                 k = spec["kind"]
                 if k == "softmax_ce":
-                    g = L.softmax_ce_backward(c, self.M)
+                    g = q(L.softmax_ce_backward(c, self.M))
                     continue
                 if k == "linear":
                     g = g.reshape(g.shape[0], -1)
-                    g, dw, db = L.linear_backward(g, c, p["w"], spec["relu"])
+                    g, dw, db = L.linear_backward(g, c, q(p["w"]), spec["relu"])
+                    g = q(g)
                 elif k == "conv":
                     g = g.reshape(c["y"].shape)
-                    g, dw, db = L.conv_backward(g, c, p["w"], spec["stride"], spec["pad"], spec["relu"])
+                    g, dw, db = L.conv_backward(g, c, q(p["w"]), spec["stride"], spec["pad"], spec["relu"])
+                    g = q(g)
                 elif k == "maxpool":
                     g = L.maxpool_backward(g.reshape(c["win"].shape), c, spec["k"], spec["stride"])
                     continue

@@ -1,0 +1,318 @@
+"""ctypes binding of libtmps.so: same names as the C ABI, argument marshalling only."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtmps.so")
+_lib = None
+
+TMPS_F32, TMPS_BF16_F32MASTER = 0, 1
+TMPS_LINEAR, TMPS_CONV2D, TMPS_MAXPOOL, TMPS_SOFTMAX_CE = 1, 2, 3, 4
+TMPS_FLAG_RELU = 1
+
+
+class TmpsError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libtmps error %d: %s" % (code, text))
+        self.code = code
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("dims", C.c_int32 * 8), ("flags", C.c_int32)]
+
+
+class StageCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("micro_batch", C.c_int32), ("n_micro", C.c_int32),
+                ("max_stash", C.c_int32), ("is_last", C.c_int32), ("borrow_input", C.c_int32),
+                ("lr", C.c_float), ("momentum", C.c_float)]
+
+
+EXPORTS = {
+    "tmps_stage_bytes": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(StageCfg), C.POINTER(C.c_size_t),
+                                   C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "tmps_stage_create": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(LayerDesc), C.c_int, C.POINTER(StageCfg),
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tmps_stage_destroy": (None, [C.c_void_p]),
+    "tmps_stage_param_count": (C.c_int64, [C.c_void_p]),
+    "tmps_stage_param_offset": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+    "tmps_stage_input_elems": (C.c_int64, [C.c_void_p]),
+    "tmps_stage_output_elems": (C.c_int64, [C.c_void_p]),
+    "tmps_stage_sync_params": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "tmps_stage_output_ptr": (C.c_void_p, [C.c_void_p, C.c_int]),
+    "tmps_stage_version": (C.c_long, [C.c_void_p]),
+    "tmps_forward_micro": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tmps_backward": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tmps_update": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "tmps_schedule_plan": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32), C.c_size_t]),
+    "tmps_schedule_stash_groups": (C.c_int, [C.c_int, C.c_int, C.c_int]),
+    "tmps_version_diff_formula": (C.c_int, [C.c_int, C.c_int]),
+    "tmps_version_diff_simulated": (C.c_int, [C.c_int, C.c_int]),
+    "tmps_schedule_run": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                    C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_int32)]),
+    "tmps_profile_enable": (C.c_int, [C.c_int]),
+    "tmps_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]),
+    "tmps_last_error": (C.c_char_p, []),
+}
+
+
+def load_library():
+    """Load libtmps.so and declare every exported symbol; raises if the library is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("libtmps.so is not built (%s): run `python __graft_entry__.py`" % _LIB_PATH)
+    lib_ = C.CDLL(_LIB_PATH)
+    for name, (res, args) in EXPORTS.items():
+        fn = getattr(lib_, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib_
+    return _lib
+
+
+def lib():
+    return load_library()
+
+
+def _check(rc):
+    if rc < 0:
+        raise TmpsError(rc, lib().tmps_last_error().decode())
+    return rc
+
+
+# ------------------------------------------------------------------------------- host-only calls
+def schedule_plan(W, N, n_minibatches):
+    n = _check(lib().tmps_schedule_plan(W, N, n_minibatches, None, 0))
+    buf = (C.c_int32 * (7 * n))()
+    _check(lib().tmps_schedule_plan(W, N, n_minibatches, buf, n))
+    return np.frombuffer(buf, dtype=np.int32).reshape(n, 7).copy()
+
+
+def schedule_stash_groups(W, N, stage):
+    return _check(lib().tmps_schedule_stash_groups(W, N, stage))
+
+
+def version_diff_formula(W, N):
+    return _check(lib().tmps_version_diff_formula(W, N))
+
+
+def version_diff_simulated(W, N):
+    return _check(lib().tmps_version_diff_simulated(W, N))
+
+
+KERNEL_CLASSES = ["dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "softmax_ce",
+                  "update", "pool_fwd", "pool_bwd", "relu_mask", "reduce", "copy"]
+
+
+def profile_enable(on):
+    _check(lib().tmps_profile_enable(int(bool(on))))
+
+
+def profile_read():
+    """{class name: (total milliseconds, launches)} since the last read."""
+    n = len(KERNEL_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib().tmps_profile_read(ms, cnt, n))
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def layer_descs(specs):
+    """Neutral layer dicts (workloads.configs) -> array of tmps_layer_desc."""
+    arr = (LayerDesc * len(specs))()
+    for d, sp in zip(arr, specs):
+        k = sp["kind"]
+        dims = [0] * 8
+        if k == "linear":
+            d.kind, dims[:2] = TMPS_LINEAR, [sp["din"], sp["dout"]]
+            d.flags = TMPS_FLAG_RELU if sp["relu"] else 0
+        elif k == "conv":
+            d.kind = TMPS_CONV2D
+            dims[:8] = [sp["h"], sp["w"], sp["cin"], sp["cout"], sp["r"], sp["s"], sp["stride"], sp["pad"]]
+            d.flags = TMPS_FLAG_RELU if sp["relu"] else 0
+        elif k == "maxpool":
+            d.kind, dims[:5] = TMPS_MAXPOOL, [sp["h"], sp["w"], sp["c"], sp["k"], sp["stride"]]
+        elif k == "softmax_ce":
+            d.kind, dims[0] = TMPS_SOFTMAX_CE, sp["classes"]
+        else:
+            raise ValueError("unknown layer kind %r" % k)
+        for i, v in enumerate(dims):
+            d.dims[i] = int(v)
+    return arr
+
+
+def stage_bytes(specs, cfg):
+    out = [C.c_size_t() for _ in range(4)]
+    descs = layer_descs(specs)
+    _check(lib().tmps_stage_bytes(descs, len(specs), C.byref(cfg), *[C.byref(o) for o in out]))
+    return tuple(o.value for o in out)
+
+
+# ------------------------------------------------------------------------------------ device side
+class Stage:
+    """One pipeline worker on a GPU.  Owns the four device regions (torch tensors) the library works in."""
+
+    def __init__(self, specs, dtype, micro_batch, n_micro, max_stash, lr, momentum, borrow_input=False,
+                 device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.specs = list(specs)
+        self.device = torch.device(device)
+        self.is_last = specs[-1]["kind"] == "softmax_ce"
+        self.cfg = StageCfg(TMPS_BF16_F32MASTER if dtype == "bf16" else TMPS_F32, micro_batch, n_micro, max_stash,
+                            int(self.is_last), int(borrow_input), lr, momentum)
+        self.act_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.descs = layer_descs(specs)
+        sizes = stage_bytes(specs, self.cfg)
+        self.regions = [torch.zeros(max(s, 256), dtype=torch.uint8, device=self.device) for s in sizes]
+        h = C.c_void_p()
+        _check(lib().tmps_stage_create(C.byref(h), self.descs, len(specs), C.byref(self.cfg),
+                                       *[C.c_void_p(r.data_ptr()) for r in self.regions]))
+        self.handle = h
+        self.P = lib().tmps_stage_param_count(h)
+        self.in_elems = lib().tmps_stage_input_elems(h)
+        self.out_elems = lib().tmps_stage_output_elems(h)
+        self.micro, self.N = micro_batch, n_micro
+
+    def __del__(self):
+        if getattr(self, "handle", None) is not None and _lib is not None:
+            _lib.tmps_stage_destroy(self.handle)
+            self.handle = None
+
+    # flat fp32 views into the device regions
+    def _flat(self, region, index):
+        t = self.regions[region][index * self.P * 4:(index + 1) * self.P * 4]
+        return t.view(self.torch.float32)
+
+    def param_offset(self, layer, which):
+        off, cnt = C.c_int64(), C.c_int64()
+        _check(lib().tmps_stage_param_offset(self.handle, layer, which, C.byref(off), C.byref(cnt)))
+        return off.value, cnt.value
+
+    def _get(self, flat):
+        host = flat.cpu().numpy()
+        out = []
+        for li, sp in enumerate(self.specs):
+            p = {}
+            for which, key in ((0, "w"), (1, "b")):
+                off, cnt = self.param_offset(li, which)
+                if cnt:
+                    p[key] = host[off:off + cnt].copy()
+            if "w" in p:
+                if sp["kind"] == "linear":
+                    p["w"] = p["w"].reshape(sp["dout"], sp["din"])
+                elif sp["kind"] == "conv":
+                    p["w"] = p["w"].reshape(sp["cout"], sp["r"], sp["s"], sp["cin"])
+            out.append(p)
+        return out
+
+    def set_params(self, params, stream=None):
+        """Write fp32 master parameters (per layer dicts with 'w', 'b'), clear momentum, refresh the working copy."""
+        torch = self.torch
+        host = np.zeros(self.P, dtype=np.float32)
+        for li, p in enumerate(params):
+            for which, key in ((0, "w"), (1, "b")):
+                off, cnt = self.param_offset(li, which)
+                if cnt:
+                    host[off:off + cnt] = np.asarray(p[key], dtype=np.float32).reshape(-1)
+        self._flat(0, 0).copy_(torch.from_numpy(host))
+        self.regions[1].zero_()
+        torch.cuda.synchronize(self.device)
+        _check(lib().tmps_stage_sync_params(self.handle, C.c_void_p(self._stream(stream))))
+        torch.cuda.synchronize(self.device)
+
+    def get_params(self):
+        return self._get(self._flat(0, 0))
+
+    def get_grads(self):
+        return self._get(self._flat(1, 1))
+
+    def get_momentum(self):
+        return self._get(self._flat(1, 0))
+
+    def _stream(self, stream):
+        if stream is None:
+            return self.torch.cuda.current_stream(self.device).cuda_stream
+        return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+    def version(self):
+        return lib().tmps_stage_version(self.handle)
+
+    def output_ptr(self, slot):
+        return lib().tmps_stage_output_ptr(self.handle, slot)
+
+    def forward_micro(self, slot, x, y=None, labels=None, loss_out=None, stream=None):
+        _check(lib().tmps_forward_micro(
+            self.handle, slot, C.c_void_p(x.data_ptr()), C.c_void_p(y.data_ptr()) if y is not None else None,
+            C.c_void_p(labels.data_ptr()) if labels is not None else None,
+            C.c_void_p(loss_out.data_ptr()) if loss_out is not None else None, C.c_void_p(self._stream(stream))))
+
+    def backward(self, slots, dy=None, dx=None, stream=None):
+        arr = (C.c_int * len(slots))(*slots)
+        _check(lib().tmps_backward(self.handle, arr, len(slots),
+                                   C.c_void_p(dy.data_ptr()) if dy is not None else None,
+                                   C.c_void_p(dx.data_ptr()) if dx is not None else None,
+                                   C.c_void_p(self._stream(stream))))
+
+    def update(self, stream=None):
+        _check(lib().tmps_update(self.handle, C.c_void_p(self._stream(stream))))
+
+
+class Pipeline:
+    """K stages of a workloads.Config on K streams of one GPU, run in nF1B order by tmps_schedule_run."""
+
+    def __init__(self, cfg, params, device="cuda:0", extra_groups=0):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        K, N = cfg.K, cfg.N
+        self.stages = []
+        for s in range(K):
+            groups = schedule_stash_groups(K, N, s) + extra_groups
+            st = Stage(cfg.stages[s], cfg.dtype, cfg.micro, N, groups * N, cfg.lr, cfg.momentum,
+                       borrow_input=True, device=device)
+            st.set_params(params[s])
+            self.stages.append(st)
+        self.streams = [torch.cuda.Stream(device=self.device) for _ in range(K)]
+        self.act_dtype = self.stages[0].act_dtype
+
+    def upload(self, batches):
+        """Concatenate mini-batches and place them in HBM (inputs in the activation dtype, labels int32)."""
+        torch = self.torch
+        x = torch.from_numpy(np.concatenate([b[0] for b in batches], axis=0)).to(self.act_dtype)
+        y = torch.from_numpy(np.concatenate([b[1] for b in batches], axis=0).astype(np.int32))
+        return x.to(self.device).contiguous(), y.to(self.device).contiguous()
+
+    def run_device(self, x_dev, y_dev, n_minibatches, losses_dev, want_log=True):
+        """Launch on resident inputs.  Returns the version log (n_tasks x 7 int32) or None."""
+        K, N = self.cfg.K, self.cfg.N
+        handles = (C.c_void_p * K)(*[st.handle for st in self.stages])
+        streams = (C.c_void_p * K)(*[s.cuda_stream for s in self.streams])
+        log = None
+        logp = None
+        if want_log:
+            n_tasks = _check(lib().tmps_schedule_plan(K, N, n_minibatches, None, 0))
+            log = (C.c_int32 * (7 * n_tasks))()
+            logp = log
+        _check(lib().tmps_schedule_run(handles, K, N, n_minibatches, C.c_void_p(x_dev.data_ptr()),
+                                       C.c_void_p(y_dev.data_ptr()), streams,
+                                       C.c_void_p(losses_dev.data_ptr()), logp))
+        if log is None:
+            return None
+        return np.frombuffer(log, dtype=np.int32).reshape(-1, 7).copy()
+
+    def run(self, batches):
+        torch = self.torch
+        x, y = self.upload(batches)
+        losses = torch.zeros(len(batches), dtype=torch.float32, device=self.device)
+        torch.cuda.synchronize(self.device)
+        log = self.run_device(x, y, len(batches), losses)
+        torch.cuda.synchronize(self.device)
+        return losses.cpu().numpy().tolist(), log
+
+    def get_params(self, s):
+        return self.stages[s].get_params()

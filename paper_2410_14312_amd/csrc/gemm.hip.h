@@ -1,0 +1,429 @@
+// Contraction kernels of the stage step for gfx950: one MFMA GEMM skeleton (bf16 in, fp32
+// accumulate) and one plain fp32 GEMM skeleton, both parameterised by operand "views" that map
+// (row, k) of the GEMM to memory.  Dense forward / input-gradient / weight-gradient and the
+// implicit-GEMM forms of convolution are all instances; nothing is materialised (no im2col).
+//
+// GEMM convention: C[m, n] = sum_k A(m, k) * B(n, k).  A view is "k-contiguous" when
+// consecutive k of one row are consecutive in memory (then 8 bf16 are fetched with one 16-byte
+// load), otherwise consecutive rows are (then a wave reads 64 consecutive rows per k and the
+// transposition happens on the way into LDS).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tmps {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+union Pack8 {
+    uint4 u;
+    bf16_t h[8];
+};
+
+// ------------------------------------------------------------------------------------------
+// Operand views
+// ------------------------------------------------------------------------------------------
+
+// Plain matrix.  KC: element(row, k) = p[row*ld + k];  otherwise element(row, k) = p[k*ld + row].
+template <typename T, bool KC> struct DenseView {
+    static constexpr bool kContig = KC;
+    const T* p;
+    int rows, K;
+    int64_t ld;
+    int vec_ok;  // base 16-byte aligned and ld % 8 == 0
+    __device__ __forceinline__ T at(int row, int k) const {
+        if (row >= rows || k >= K) return T(0.0f);
+        return KC ? p[(int64_t)row * ld + k] : p[(int64_t)k * ld + row];
+    }
+    __device__ __forceinline__ uint4 load8(int row, int k) const {
+        if (KC && vec_ok && row < rows && k + 8 <= K)
+            return *reinterpret_cast<const uint4*>(p + (int64_t)row * ld + k);
+        Pack8 r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r.h[i] = (bf16_t)at(row, k + i);
+        return r.u;
+    }
+};
+
+struct ConvGeom {
+    int B, H, W, Cin, Ho, Wo, Cout, R, S, stride, pad;
+};
+
+// Forward A operand: row m = (n, ho, wo), k = (r, s, c) -> x[n, ho*stride+r-pad, wo*stride+s-pad, c].
+template <typename T> struct ConvFwdA {
+    static constexpr bool kContig = true;
+    const T* x;
+    ConvGeom g;
+    int rows, K, vec_ok;  // vec_ok: Cin % 8 == 0 and base aligned
+    __device__ __forceinline__ int64_t addr(int m, int k, bool& ok) const {
+        int hw = g.Ho * g.Wo;
+        int n = m / hw, rem = m - n * hw;
+        int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+        int sc = g.S * g.Cin;
+        int r = k / sc, rem2 = k - r * sc;
+        int s = rem2 / g.Cin, c = rem2 - s * g.Cin;
+        int h = ho * g.stride + r - g.pad, w = wo * g.stride + s - g.pad;
+        ok = (m < rows) && (k < K) && h >= 0 && h < g.H && w >= 0 && w < g.W;
+        return (((int64_t)n * g.H + h) * g.W + w) * g.Cin + c;
+    }
+    __device__ __forceinline__ T at(int m, int k) const {
+        bool ok;
+        int64_t a = addr(m, k, ok);
+        return ok ? x[a] : T(0.0f);
+    }
+    __device__ __forceinline__ uint4 load8(int m, int k) const {
+        if (vec_ok) {
+            bool ok;
+            int64_t a = addr(m, k, ok);
+            return ok ? *reinterpret_cast<const uint4*>(x + a) : make_uint4(0, 0, 0, 0);
+        }
+        Pack8 r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r.h[i] = (bf16_t)at(m, k + i);
+        return r.u;
+    }
+};
+
+// Input-gradient A operand: row m = (n, h, w), k = (r, s, co) -> dy[n, (h+pad-r)/stride, (w+pad-s)/stride, co]
+// where the divisions are exact and in range, else 0.
+template <typename T> struct ConvDgradA {
+    static constexpr bool kContig = true;
+    const T* dy;
+    ConvGeom g;
+    int rows, K, vec_ok;  // vec_ok: Cout % 8 == 0 and base aligned
+    __device__ __forceinline__ int64_t addr(int m, int k, bool& ok) const {
+        int hw = g.H * g.W;
+        int n = m / hw, rem = m - n * hw;
+        int h = rem / g.W, w = rem - h * g.W;
+        int sc = g.S * g.Cout;
+        int r = k / sc, rem2 = k - r * sc;
+        int s = rem2 / g.Cout, co = rem2 - s * g.Cout;
+        int hy = h + g.pad - r, wy = w + g.pad - s;
+        int ho = hy / g.stride, wo = wy / g.stride;
+        ok = (m < rows) && (k < K) && hy >= 0 && wy >= 0 && ho * g.stride == hy &&
+             wo * g.stride == wy && ho < g.Ho && wo < g.Wo;
+        return (((int64_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout + co;
+    }
+    __device__ __forceinline__ T at(int m, int k) const {
+        bool ok;
+        int64_t a = addr(m, k, ok);
+        return ok ? dy[a] : T(0.0f);
+    }
+    __device__ __forceinline__ uint4 load8(int m, int k) const {
+        if (vec_ok) {
+            bool ok;
+            int64_t a = addr(m, k, ok);
+            return ok ? *reinterpret_cast<const uint4*>(dy + a) : make_uint4(0, 0, 0, 0);
+        }
+        Pack8 r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r.h[i] = (bf16_t)at(m, k + i);
+        return r.u;
+    }
+};
+
+// Input-gradient B operand: row n = ci, k = (r, s, co) -> w[co, r, s, ci]  (rows contiguous).
+template <typename T> struct ConvDgradB {
+    static constexpr bool kContig = false;
+    const T* w;
+    ConvGeom g;
+    int rows, K;
+    __device__ __forceinline__ T at(int ci, int k) const {
+        if (ci >= rows || k >= K) return T(0.0f);
+        int sc = g.S * g.Cout;
+        int r = k / sc, rem = k - r * sc;
+        int s = rem / g.Cout, co = rem - s * g.Cout;
+        return w[(((int64_t)co * g.R + r) * g.S + s) * g.Cin + ci];
+    }
+    __device__ __forceinline__ uint4 load8(int ci, int k) const {
+        Pack8 r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r.h[i] = (bf16_t)at(ci, k + i);
+        return r.u;
+    }
+};
+
+// Weight-gradient B operand: row = (r, s, ci), k = m = (n, ho, wo) -> x[n, ho*stride+r-pad, wo*stride+s-pad, ci].
+template <typename T> struct ConvWgradB {
+    static constexpr bool kContig = false;
+    const T* x;
+    ConvGeom g;
+    int rows, K;
+    __device__ __forceinline__ T at(int row, int m) const {
+        if (row >= rows || m >= K) return T(0.0f);
+        int sc = g.S * g.Cin;
+        int r = row / sc, rem = row - r * sc;
+        int s = rem / g.Cin, c = rem - s * g.Cin;
+        int hw = g.Ho * g.Wo;
+        int n = m / hw, rem2 = m - n * hw;
+        int ho = rem2 / g.Wo, wo = rem2 - ho * g.Wo;
+        int h = ho * g.stride + r - g.pad, w = wo * g.stride + s - g.pad;
+        if (h < 0 || h >= g.H || w < 0 || w >= g.W) return T(0.0f);
+        return x[(((int64_t)n * g.H + h) * g.W + w) * g.Cin + c];
+    }
+    __device__ __forceinline__ uint4 load8(int row, int m) const {
+        Pack8 r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r.h[i] = (bf16_t)at(row, m + i);
+        return r.u;
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// Epilogues: called once per output element with the fp32 accumulator.  `z` is the split-K slice.
+// ------------------------------------------------------------------------------------------
+
+// out[m, n] = act(v + bias[n]); optional fp32 second output (logits).
+template <typename TOut> struct EpiBiasAct {
+    TOut* out;
+    const float* bias;  // may be null
+    int64_t ld;
+    int relu;
+    __device__ __forceinline__ void operator()(int m, int n, float v, int) const {
+        if (bias) v += bias[n];
+        if (relu) v = v > 0.0f ? v : 0.0f;
+        out[(int64_t)m * ld + n] = from_f32<TOut>(v);
+    }
+    __device__ __forceinline__ void rowsum(int, float, int) const {}
+};
+
+// out[m, n] = (mask == null || mask[m, n] > 0) ? v : 0   -- gradient through a stored ReLU output.
+template <typename TOut, typename TMask> struct EpiMask {
+    TOut* out;
+    const TMask* mask;  // may be null
+    int64_t ld;
+    __device__ __forceinline__ void operator()(int m, int n, float v, int) const {
+        int64_t i = (int64_t)m * ld + n;
+        if (mask && !(to_f32(mask[i]) > 0.0f)) v = 0.0f;
+        out[i] = from_f32<TOut>(v);
+    }
+    __device__ __forceinline__ void rowsum(int, float, int) const {}
+};
+
+// Weight gradient: fp32 [rows, cols] followed by the bias gradient [rows]; slice z writes its own
+// copy at out + z*slice_stride (reduced afterwards), or the final location when there is one slice.
+struct EpiWgrad {
+    float* out;
+    int64_t ld;            // cols
+    int64_t bias_off;      // rows*cols
+    int64_t slice_stride;  // rows*cols + rows
+    __device__ __forceinline__ void operator()(int m, int n, float v, int z) const {
+        out[z * slice_stride + (int64_t)m * ld + n] = v;
+    }
+    __device__ __forceinline__ void rowsum(int m, float v, int z) const {
+        out[z * slice_stride + bias_off + m] = v;
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA GEMM.  256 threads = 4 waves in a 2x2 arrangement; wave tile (BM/2)x(BN/2) made of
+// 32x32 MFMA tiles; BK = 32; LDS double-buffered; next tile's global loads are in flight while
+// the current one is multiplied.  ROWSUM: blocks of the first column of tiles also sum A over k
+// (the bias gradient of a weight-gradient GEMM, whose A operand is dY transposed).
+// ------------------------------------------------------------------------------------------
+constexpr int kBK = 32;
+constexpr int kLdsLd = kBK + 8;  // bf16 elements per LDS row: 80 bytes, keeps 16-byte reads conflict-free
+
+template <int BM, int BN, bool ROWSUM, class AOp, class BOp, class Epi>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(AOp A, BOp B, Epi epi, int M, int N, int K,
+                                                        int k_per_slice) {
+    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 tiles per wave along m and n
+    __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * kLdsLd];
+    __shared__ __attribute__((aligned(16))) bf16_t sB[2][BN * kLdsLd];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int z = blockIdx.z;
+    const int k_begin = z * k_per_slice;
+    const int k_end = min(K, k_begin + k_per_slice);
+    const int nk = (k_end - k_begin + kBK - 1) / kBK;
+
+    constexpr int A_CH = BM * (kBK / 8) / 256;  // 16-byte chunks per thread
+    constexpr int B_CH = BN * (kBK / 8) / 256;
+    uint4 ra[A_CH], rb[B_CH];
+
+    // The views zero-fill beyond K, but a slice must not read past its own k range.
+    auto gload = [&](int kt) {
+        const int kb = k_begin + kt * kBK;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            int c = tid + i * 256;
+            int row = AOp::kContig ? (c >> 2) : (c % BM);
+            int kc = AOp::kContig ? (c & 3) : (c / BM);
+            int k = kb + kc * 8;
+            if (k + 8 <= k_end) ra[i] = A.load8(m0 + row, k);
+            else {
+                Pack8 t;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t.h[e] = (k + e < k_end) ? (bf16_t)A.at(m0 + row, k + e) : (bf16_t)0.0f;
+                ra[i] = t.u;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            int c = tid + i * 256;
+            int row = BOp::kContig ? (c >> 2) : (c % BN);
+            int kc = BOp::kContig ? (c & 3) : (c / BN);
+            int k = kb + kc * 8;
+            if (k + 8 <= k_end) rb[i] = B.load8(n0 + row, k);
+            else {
+                Pack8 t;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t.h[e] = (k + e < k_end) ? (bf16_t)B.at(n0 + row, k + e) : (bf16_t)0.0f;
+                rb[i] = t.u;
+            }
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            int c = tid + i * 256;
+            int row = AOp::kContig ? (c >> 2) : (c % BM);
+            int kc = AOp::kContig ? (c & 3) : (c / BM);
+            *reinterpret_cast<uint4*>(&sA[buf][row * kLdsLd + kc * 8]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            int c = tid + i * 256;
+            int row = BOp::kContig ? (c >> 2) : (c % BN);
+            int kc = BOp::kContig ? (c & 3) : (c / BN);
+            *reinterpret_cast<uint4*>(&sB[buf][row * kLdsLd + kc * 8]) = rb[i];
+        }
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    float rsum = 0.0f;
+
+    if (nk > 0) {
+        gload(0);
+        lstore(0);
+    }
+    __syncthreads();
+
+    const int frag_row = lane & 31;
+    const int frag_k = (lane >> 5) * 8;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload(kt + 1);
+#pragma unroll
+        for (int kk = 0; kk < kBK / 16; ++kk) {
+            bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8_t*>(
+                    &sA[buf][(wm * (BM / 2) + i * 32 + frag_row) * kLdsLd + kk * 16 + frag_k]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8_t*>(
+                    &sB[buf][(wn * (BN / 2) + j * 32 + frag_row) * kLdsLd + kk * 16 + frag_k]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (ROWSUM && blockIdx.x == 0 && tid < BM) {
+            const bf16_t* rowp = &sA[buf][tid * kLdsLd];
+#pragma unroll
+            for (int e = 0; e < kBK; ++e) rsum += (float)rowp[e];
+        }
+        if (kt + 1 < nk) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // Accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register r holds
+    // row 8*(r/4) + 4*(lane/32) + r%4.
+    const int col_in = lane & 31;
+    const int row_in = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int n = n0 + wn * (BN / 2) + j * 32 + col_in;
+            if (n >= N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int m = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + row_in + (r & 3);
+                if (m < M) epi(m, n, acc[i][j][r], z);
+            }
+        }
+    if (ROWSUM && blockIdx.x == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 GEMM (TMPS_F32 stages): 64x64 tile, BK = 16, 256 threads, 4x4 outputs per thread.
+// ------------------------------------------------------------------------------------------
+template <bool ROWSUM, class AOp, class BOp, class Epi>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(AOp A, BOp B, Epi epi, int M, int N, int K,
+                                                       int k_per_slice) {
+    constexpr int BT = 64, BKF = 16;
+    __shared__ float sA[BKF][BT + 4];
+    __shared__ float sB[BKF][BT + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
+    const int z = blockIdx.z;
+    const int k_begin = z * k_per_slice;
+    const int k_end = min(K, k_begin + k_per_slice);
+    float acc[4][4] = {};
+    float rsum = 0.0f;
+    for (int kb = k_begin; kb < k_end; kb += BKF) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int e = tid + i * 256;
+            int row = AOp::kContig ? (e >> 4) : (e & 63);
+            int k = AOp::kContig ? (e & 15) : (e >> 6);
+            sA[k][row] = (kb + k < k_end) ? to_f32(A.at(m0 + row, kb + k)) : 0.0f;
+            row = BOp::kContig ? (e >> 4) : (e & 63);
+            k = BOp::kContig ? (e & 15) : (e >> 6);
+            sB[k][row] = (kb + k < k_end) ? to_f32(B.at(n0 + row, kb + k)) : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < BKF; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = sA[k][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = sB[k][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        if (ROWSUM && blockIdx.x == 0 && tid < BT) {
+#pragma unroll
+            for (int k = 0; k < BKF; ++k) rsum += sA[k][tid];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int n = n0 + tx * 4 + j;
+            if (n < N) epi(m, n, acc[i][j], z);
+        }
+    }
+    if (ROWSUM && blockIdx.x == 0 && tid < BT && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
+}
+
+}  // namespace tmps

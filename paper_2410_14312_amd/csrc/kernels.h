@@ -1,0 +1,64 @@
+// Host-side launch interface of the HIP kernels (internal to libtmps).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tmps {
+
+// dtype codes match TMPS_F32 / TMPS_BF16_F32MASTER
+constexpr int kF32 = 0;
+constexpr int kBF16 = 1;
+
+inline size_t act_bytes(int dtype) { return dtype == kBF16 ? 2 : 4; }
+
+struct ConvShape {
+    int B, H, W, Cin, Ho, Wo, Cout, R, S, stride, pad;
+};
+
+// Number of split-K slices a weight-gradient GEMM [rows x cols] with contraction length K uses, and
+// the fp32 workspace elements it needs (0 when it writes the gradient directly).
+int wgrad_slices(int rows, int cols, int64_t K);
+size_t wgrad_workspace_elems(int rows, int cols, int64_t K);
+
+// y[B, Dout] = act(x[B, Din] w^T + b).  w is the working copy (bf16 or fp32 per dtype), bias fp32.
+// out_f32: write fp32 regardless of dtype (logits).
+hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B,
+                         int Din, int Dout, int relu, int out_f32, hipStream_t s);
+// dx[B, Din] = dy[B, Dout] w, zeroed where mask[B, Din] <= 0 (mask may be null; activation dtype).
+hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int B,
+                       int Din, int Dout, hipStream_t s);
+// gw[Dout, Din] = dy^T x and gb[Dout] = column sums of dy, with gb stored right after gw.
+hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout,
+                       float* workspace, hipStream_t s);
+
+hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y,
+                        const ConvShape& c, int relu, hipStream_t s);
+hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask,
+                      const ConvShape& c, hipStream_t s);
+hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c,
+                      float* workspace, hipStream_t s);
+
+// 2-D max pooling, channels-last, no padding.  Backward recomputes the winner (first maximum in
+// row-major window order) from the stored input; relu_mask: also zero where the input is <= 0.
+hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int W, int C, int k,
+                           int stride, hipStream_t s);
+hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, int B, int H, int W,
+                            int C, int k, int stride, int relu_mask, hipStream_t s);
+
+// Softmax cross-entropy of `rows` rows of fp32 logits: row_loss[rows] fp32 and
+// dlogits[rows, C] = (softmax - onehot) * inv_M in the gradient dtype.
+hipError_t softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits,
+                      float* row_loss, int rows, int C, float inv_M, hipStream_t s);
+// out[0] = scale * sum(in[0..n))   (deterministic single-block tree)
+hipError_t reduce_scaled_sum(const float* in, int n, float scale, float* out, hipStream_t s);
+
+// dz = y > 0 ? dy : 0
+hipError_t relu_mask(int dtype, const void* dy, const void* y, void* dz, int64_t n, hipStream_t s);
+
+// buf <- mu*buf + g;  w <- w - lr*buf;  wcopy <- bf16(w) when wcopy != null
+hipError_t sgd_momentum(float* w, float* buf, const float* g, void* wcopy_bf16, int64_t n, float lr,
+                        float mu, hipStream_t s);
+hipError_t cast_f32_to_bf16(const float* in, void* out, int64_t n, hipStream_t s);
+
+}  // namespace tmps

@@ -1,0 +1,250 @@
+// Bandwidth-bound kernels of the stage step: softmax cross-entropy, momentum update, max pooling,
+// ReLU gradient mask, casts and small reductions.
+#include "gemm.hip.h"
+#include "kernels.h"
+
+namespace tmps {
+
+static inline int cdiv64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------------- softmax cross-entropy
+// One wave per row; 4 rows per block.  dlogits = (softmax - onehot) * inv_M, loss = lse - z[label].
+template <typename TG>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(const float* __restrict__ logits,
+                                                         const int32_t* __restrict__ labels,
+                                                         TG* __restrict__ dlogits,
+                                                         float* __restrict__ row_loss, int rows, int C,
+                                                         float inv_M) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float* z = logits + (int64_t)row * C;
+    float mx = -INFINITY;
+    for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
+    mx = wave_max(mx);
+    float sum = 0.0f;
+    for (int c = lane; c < C; c += 64) sum += expf(z[c] - mx);
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+    const int label = labels[row];
+    const bool label_ok = label >= 0 && label < C;  // an out-of-range label gives a NaN loss, never a wild read
+    TG* g = dlogits + (int64_t)row * C;
+    for (int c = lane; c < C; c += 64) {
+        float p = expf(z[c] - mx) * inv;
+        g[c] = from_f32<TG>((p - (c == label ? 1.0f : 0.0f)) * inv_M);
+    }
+    if (lane == 0) row_loss[row] = label_ok ? logf(sum) - (z[label] - mx) : NAN;
+}
+
+hipError_t softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
+                      int rows, int C, float inv_M, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    dim3 grid(cdiv64(rows, 4));
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, dim3(256), 0, s, logits, labels, (bf16_t*)dlogits,
+                           row_loss, rows, C, inv_M);
+    else
+        hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, dim3(256), 0, s, logits, labels, (float*)dlogits,
+                           row_loss, rows, C, inv_M);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void reduce_scaled_sum_kernel(const float* __restrict__ in, int n,
+                                                                float scale, float* __restrict__ out) {
+    __shared__ float part[4];
+    float a = 0.0f;
+    for (int i = threadIdx.x; i < n; i += 256) a += in[i];
+    a = wave_sum(a);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = (part[0] + part[1] + part[2] + part[3]) * scale;
+}
+
+hipError_t reduce_scaled_sum(const float* in, int n, float scale, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(reduce_scaled_sum_kernel, dim3(1), dim3(256), 0, s, in, n, scale, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------- ReLU gradient
+template <typename T>
+__global__ void relu_mask_kernel(const T* __restrict__ dy, const T* __restrict__ y, T* __restrict__ dz,
+                                 int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dz[i] = to_f32(y[i]) > 0.0f ? dy[i] : T(0.0f);
+}
+
+hipError_t relu_mask(int dtype, const void* dy, const void* y, void* dz, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    int blocks = cdiv64(n, 256);
+    if (blocks > 4096) blocks = 4096;
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(relu_mask_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t*)dy,
+                           (const bf16_t*)y, (bf16_t*)dz, n);
+    else
+        hipLaunchKernelGGL(relu_mask_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)dy,
+                           (const float*)y, (float*)dz, n);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- momentum update
+// 4 parameters per thread: 16-byte loads of w, buf, g; 16-byte stores of w, buf; 8-byte store of the
+// bf16 working copy.  The tail (n % 4) is handled by the last threads one element at a time.
+__global__ __launch_bounds__(256) void sgd_momentum_kernel(float* __restrict__ w, float* __restrict__ buf,
+                                                           const float* __restrict__ g,
+                                                           bf16_t* __restrict__ wc, int64_t n, float lr,
+                                                           float mu) {
+    const int64_t n4 = n >> 2;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) {
+        float4 wv = reinterpret_cast<const float4*>(w)[i];
+        float4 bv = reinterpret_cast<const float4*>(buf)[i];
+        float4 gv = reinterpret_cast<const float4*>(g)[i];
+        bv.x = mu * bv.x + gv.x; bv.y = mu * bv.y + gv.y; bv.z = mu * bv.z + gv.z; bv.w = mu * bv.w + gv.w;
+        wv.x -= lr * bv.x; wv.y -= lr * bv.y; wv.z -= lr * bv.z; wv.w -= lr * bv.w;
+        reinterpret_cast<float4*>(buf)[i] = bv;
+        reinterpret_cast<float4*>(w)[i] = wv;
+        if (wc) {
+            union { bf16_t h[4]; uint2 u; } pk;
+            pk.h[0] = (bf16_t)wv.x; pk.h[1] = (bf16_t)wv.y; pk.h[2] = (bf16_t)wv.z; pk.h[3] = (bf16_t)wv.w;
+            reinterpret_cast<uint2*>(wc)[i] = pk.u;
+        }
+    }
+    int64_t t = (n4 << 2) + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) {
+        float b = mu * buf[t] + g[t];
+        float x = w[t] - lr * b;
+        buf[t] = b;
+        w[t] = x;
+        if (wc) wc[t] = (bf16_t)x;
+    }
+}
+
+hipError_t sgd_momentum(float* w, float* buf, const float* g, void* wcopy_bf16, int64_t n, float lr, float mu,
+                        hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    int blocks = cdiv64((n >> 2) + 4, 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(sgd_momentum_kernel, dim3(blocks), dim3(256), 0, s, w, buf, g, (bf16_t*)wcopy_bf16, n,
+                       lr, mu);
+    return hipGetLastError();
+}
+
+__global__ void cast_f32_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) out[i] = (bf16_t)in[i];
+}
+
+hipError_t cast_f32_to_bf16(const float* in, void* out, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    int blocks = cdiv64(n, 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(cast_f32_to_bf16_kernel, dim3(blocks), dim3(256), 0, s, in, (bf16_t*)out, n);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------- max pooling
+// One thread per output element (channels fastest, so a wave reads/writes consecutive channels).
+template <typename T>
+__global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int B, int H, int W, int C,
+                                   int Ho, int Wo, int k, int stride) {
+    int64_t total = (int64_t)B * Ho * Wo * C;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int c = (int)(i % C);
+    int64_t t = i / C;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    float best = -INFINITY;
+    for (int r = 0; r < k; ++r)
+        for (int s = 0; s < k; ++s) {
+            float v = to_f32(x[(((int64_t)n * H + ho * stride + r) * W + wo * stride + s) * C + c]);
+            if (v > best) best = v;
+        }
+    y[i] = from_f32<T>(best);
+}
+
+// One thread per window: finds the first maximum and routes dy to it; every input position covered by
+// exactly one window when stride == k, otherwise positions are accumulated with overlapping windows
+// handled by a gather over the windows that contain them (general kernel below).
+template <typename T>
+__global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx,
+                                   int B, int H, int W, int C, int Ho, int Wo, int k, int stride,
+                                   int relu_mask) {
+    // gather form, one thread per INPUT element: sum dy over the windows whose winner it is
+    int64_t total = (int64_t)B * H * W * C;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int c = (int)(i % C);
+    int64_t t = i / C;
+    int w = (int)(t % W); t /= W;
+    int h = (int)(t % H);
+    int n = (int)(t / H);
+    float xv = to_f32(x[i]);
+    float acc = 0.0f;
+    if (!(relu_mask && !(xv > 0.0f))) {
+        // windows (ho, wo) with ho*stride <= h < ho*stride + k
+        int ho_lo = h - k + 1 > 0 ? (h - k + 1 + stride - 1) / stride : 0;
+        int wo_lo = w - k + 1 > 0 ? (w - k + 1 + stride - 1) / stride : 0;
+        for (int ho = ho_lo; ho < Ho && ho * stride <= h; ++ho)
+            for (int wo = wo_lo; wo < Wo && wo * stride <= w; ++wo) {
+                // is (h, w) the first maximum of this window?
+                bool win = true;
+                for (int r = 0; r < k && win; ++r)
+                    for (int s = 0; s < k; ++s) {
+                        int hh = ho * stride + r, ww = wo * stride + s;
+                        float v = to_f32(x[(((int64_t)n * H + hh) * W + ww) * C + c]);
+                        bool before = (hh < h) || (hh == h && ww < w);
+                        if (v > xv || (before && v == xv)) { win = false; break; }
+                    }
+                if (win) acc += to_f32(dy[(((int64_t)n * Ho + ho) * Wo + wo) * C + c]);
+            }
+    }
+    dx[i] = from_f32<T>(acc);
+}
+
+hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int W, int C, int k, int stride,
+                           hipStream_t s) {
+    int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+    int64_t total = (int64_t)B * Ho * Wo * C;
+    if (total <= 0) return hipSuccess;
+    dim3 grid(cdiv64(total, 256));
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, B, H,
+                           W, C, Ho, Wo, k, stride);
+    else
+        hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)y, B, H, W,
+                           C, Ho, Wo, k, stride);
+    return hipGetLastError();
+}
+
+hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, int B, int H, int W, int C,
+                            int k, int stride, int relu_mask, hipStream_t s) {
+    int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+    int64_t total = (int64_t)B * H * W * C;
+    if (total <= 0) return hipSuccess;
+    dim3 grid(cdiv64(total, 256));
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x,
+                           (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, Ho, Wo, k, stride, relu_mask);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (const float*)dy,
+                           (float*)dx, B, H, W, C, Ho, Wo, k, stride, relu_mask);
+    return hipGetLastError();
+}
+
+}  // namespace tmps

@@ -1,0 +1,61 @@
+// One pipeline worker: consecutive layers, activation stash, backward pass, in-place update.
+#pragma once
+#include <vector>
+
+#include "common.h"
+#include "kernels.h"
+
+struct LayerRT {
+    tmps_layer_desc d;
+    int64_t in_elems = 0, out_elems = 0;  // per sample
+    int64_t w_off = 0, w_count = 0, b_off = 0, b_count = 0;  // positions in the flat parameter arrays
+    size_t out_off = 0;    // stash byte offset of this layer's output array (all slots)
+    size_t out_esize = 0;  // bytes per element of that array
+    size_t aux_off = 0;    // softmax-CE: stash byte offset of the per-row losses (fp32)
+    bool relu = false;
+    bool out_f32 = false;  // the logits layer (followed by softmax-CE) writes fp32
+    size_t ws_elems = 0;   // split-K workspace of the weight-gradient GEMM (fp32 elements)
+};
+
+struct tmps_stage {
+    tmps_stage_cfg cfg;
+    std::vector<LayerRT> layers;
+    int64_t P = 0;  // flat parameter count (with alignment gaps)
+    int64_t in_elems = 0, out_elems = 0;
+    size_t asz = 4;  // bytes per activation / gradient element
+    char* params = nullptr;
+    char* state = nullptr;
+    char* stash = nullptr;
+    char* scratch = nullptr;
+    float* master = nullptr;
+    void* wcopy = nullptr;  // bf16 working copy (null for fp32 stages)
+    float* mom = nullptr;
+    float* grad = nullptr;
+    size_t in_off = 0;  // stash offset of the copied inputs (borrow_input == 0)
+    size_t stash_bytes = 0, scratch_bytes = 0;
+    size_t gbuf_off[2] = {0, 0}, gbuf_bytes = 0;  // gradient ping-pong buffers (M rows)
+    size_t dxout_off[2] = {0, 0}, dxout_bytes = 0;  // boundary gradient buffers used by the scheduler
+    size_t ws_off = 0;
+    std::vector<char> slot_used;
+    std::vector<const void*> slot_x;
+    long version = 0;
+
+    int M() const { return cfg.micro_batch * cfg.n_micro; }
+    // weights the contractions read
+    const void* wptr(const LayerRT& L) const {
+        return wcopy ? (const void*)((const char*)wcopy + L.w_off * 2) : (const void*)(master + L.w_off);
+    }
+    const float* bptr(const LayerRT& L) const { return master + L.b_off; }
+    char* out_ptr(const LayerRT& L, int64_t row) const {
+        return stash + L.out_off + (size_t)row * L.out_elems * L.out_esize;
+    }
+};
+
+namespace tmps {
+// Fills `st` from the descriptors: shapes, flat parameter layout, stash and scratch layout.
+int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, const tmps_stage_cfg* cfg);
+// Device address of the boundary-gradient buffer `which` (0/1) of a stage.
+void* stage_dxout(tmps_stage* st, int which);
+// Per-row losses of a slot on the last stage.
+float* stage_row_loss(tmps_stage* st, int slot);
+}  // namespace tmps
