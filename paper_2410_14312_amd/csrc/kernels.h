@@ -16,28 +16,33 @@ struct ConvShape {
     int B, H, W, Cin, Ho, Wo, Cout, R, S, stride, pad;
 };
 
-// Number of split-K slices a weight-gradient GEMM [rows x cols] with contraction length K uses, and
-// the fp32 workspace elements it needs (0 when it writes the gradient directly).
-int wgrad_slices(int rows, int cols, int64_t K);
-size_t wgrad_workspace_elems(int rows, int cols, int64_t K);
+// Tile edge (64 or 128) and number of k-slices chosen for a [M x N x K] contraction, and the fp32
+// workspace elements its partial sums need (0 without a split).  with_rowsum: weight-gradient GEMMs
+// also keep M row sums per slice.  Every launcher below takes that workspace as `ws` (may be null:
+// then nothing is split).
+struct GemmPlan {
+    int tile, slices;
+};
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K);
+size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t K, int with_rowsum);
 
 // y[B, Dout] = act(x[B, Din] w^T + b).  w is the working copy (bf16 or fp32 per dtype), bias fp32.
 // out_f32: write fp32 regardless of dtype (logits).
 hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B,
-                         int Din, int Dout, int relu, int out_f32, hipStream_t s);
+                         int Din, int Dout, int relu, int out_f32, float* ws, hipStream_t s);
 // dx[B, Din] = dy[B, Dout] w, zeroed where mask[B, Din] <= 0 (mask may be null; activation dtype).
 hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int B,
-                       int Din, int Dout, hipStream_t s);
+                       int Din, int Dout, float* ws, hipStream_t s);
 // gw[Dout, Din] = dy^T x and gb[Dout] = column sums of dy, with gb stored right after gw.
 hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout,
-                       float* workspace, hipStream_t s);
+                       float* ws, hipStream_t s);
 
 hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y,
-                        const ConvShape& c, int relu, hipStream_t s);
+                        const ConvShape& c, int relu, float* ws, hipStream_t s);
 hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask,
-                      const ConvShape& c, hipStream_t s);
+                      const ConvShape& c, float* ws, hipStream_t s);
 hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c,
-                      float* workspace, hipStream_t s);
+                      float* ws, hipStream_t s);
 
 // 2-D max pooling, channels-last, no padding.  Backward recomputes the winner (first maximum in
 // row-major window order) from the stored input; relu_mask: also zero where the input is <= 0.

@@ -1,6 +1,9 @@
-// Launchers of the contraction kernels: dense and convolution forward, input gradient and
-// weight gradient, in bf16 (MFMA) and fp32.
-#include "gemm.hip.h"
+// Launchers of the contraction kernels: dense and convolution forward, input gradient and weight
+// gradient.  bf16 stages use the MFMA skeleton of gemm2.hip.h whenever every operand can be fetched
+// with aligned 16-byte loads (channel / feature counts that are multiples of 8), and the
+// element-wise skeleton of gemm.hip.h otherwise (3-channel input layer, 10-way logits layer);
+// fp32 stages use the fp32 skeleton.
+#include "gemm2.hip.h"
 #include "kernels.h"
 
 namespace tmps {
@@ -8,23 +11,36 @@ namespace tmps {
 static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-int wgrad_slices(int rows, int cols, int64_t K) {
-    int64_t tiles = (int64_t)cdiv(rows, 128) * cdiv(cols, 128);
-    if (tiles >= 256 || K <= 512) return 1;
-    int64_t want = (512 + tiles - 1) / tiles;
-    int64_t by_k = K / 256;
-    int64_t by_ws = (int64_t(64) << 20) / (((int64_t)rows * cols + rows) * 4);
-    int64_t s = want;
-    if (s > by_k) s = by_k;
-    if (s > by_ws) s = by_ws;
-    if (s > 128) s = 128;
-    if (s < 1) s = 1;
-    return (int)s;  // upper bound: rounding the slice length up to whole k-tiles can only lower it
+// ------------------------------------------------------------------------------------------
+// Tile size and k-split of a [M x N x K] contraction.  Small outputs are split along k until the grid
+// has a few hundred workgroups, as long as the fp32 partial sums do not outweigh the operands.
+// ------------------------------------------------------------------------------------------
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
+    GemmPlan p;
+    const int64_t t128 = (int64_t)cdiv(M, 128) * cdiv(N, 128);
+    const int64_t t64 = (int64_t)cdiv(M, 64) * cdiv(N, 64);
+    const bool wide = N > 64 && M > 64;
+    p.tile = (wide && t128 >= 64) ? 128 : 64;
+    const int64_t tiles = p.tile == 128 ? t128 : t64;
+    const int64_t target = 384;
+    int64_t s = 1;
+    if (tiles < target) {
+        s = (target + tiles - 1) / tiles;
+        const int64_t by_k = K / 128;
+        const int64_t by_bytes = ((M + N) * K) / (2 * M * N);
+        if (s > by_k) s = by_k;
+        if (s > by_bytes) s = by_bytes;
+        if (s > 64) s = 64;
+        if (s < 1) s = 1;
+    }
+    p.slices = (int)s;
+    return p;
 }
 
-size_t wgrad_workspace_elems(int rows, int cols, int64_t K) {
-    int s = wgrad_slices(rows, cols, K);
-    return s <= 1 ? 0 : (size_t)s * ((size_t)rows * cols + rows);
+size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t K, int with_rowsum) {
+    GemmPlan p = plan_gemm(M, N, K);
+    if (p.slices <= 1) return 0;
+    return (size_t)p.slices * ((size_t)M * N + (with_rowsum ? (size_t)M : 0));
 }
 
 __global__ void slice_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int64_t count,
@@ -36,117 +52,164 @@ __global__ void slice_sum_kernel(const float* __restrict__ part, float* __restri
     out[i] = a;
 }
 
+// slice length (whole k-tiles) and the number of slices really launched
+static void slice_geometry(int64_t K, int want, int ktile, int& per, int& nz) {
+    if (want < 1) want = 1;
+    per = cdiv(cdiv(K, want), ktile) * ktile;
+    if (per < ktile) per = ktile;
+    nz = K > 0 ? cdiv(K, per) : 1;
+}
+
+// ---- MFMA path --------------------------------------------------------------------------------
 template <bool ROWSUM, class AOp, class BOp, class Epi>
-static hipError_t launch_bf16(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int slices,
-                              hipStream_t s) {
-    if (M <= 0 || N <= 0) return hipSuccess;
-    int per = cdiv(cdiv(K, slices), kBK) * kBK;
-    if (per < kBK) per = kBK;
-    int nz = K > 0 ? cdiv(K, per) : 1;
-    int64_t tiles128 = (int64_t)cdiv(M, 128) * cdiv(N, 128) * nz;
-    if (tiles128 >= 192) {
+static hipError_t launch2_tile(int tile, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
+                               int nz, hipStream_t s) {
+    if (tile == 128) {
         dim3 grid(cdiv(N, 128), cdiv(M, 128), nz);
-        hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B,
-                           epi, M, N, K, per);
+        hipLaunchKernelGGL((gemm2_kernel<128, 128, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N,
+                           K, per);
     } else {
         dim3 grid(cdiv(N, 64), cdiv(M, 64), nz);
-        hipLaunchKernelGGL((gemm_bf16_kernel<64, 64, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi,
-                           M, N, K, per);
+        hipLaunchKernelGGL((gemm2_kernel<64, 64, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K,
+                           per);
     }
     return hipGetLastError();
 }
 
-template <bool ROWSUM, class AOp, class BOp, class Epi>
-static hipError_t launch_f32(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int slices,
-                             hipStream_t s) {
+// Forward / input-gradient style GEMM: epilogue `epi` applied once per output element.
+template <class AOp, class BOp, class Epi>
+static hipError_t run2(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, float* ws,
+                       hipStream_t s) {
     if (M <= 0 || N <= 0) return hipSuccess;
-    int per = cdiv(cdiv(K, slices), 16) * 16;
-    if (per < 16) per = 16;
-    int nz = K > 0 ? cdiv(K, per) : 1;
+    GemmPlan p = plan_gemm(M, N, K);
+    int per, nz;
+    slice_geometry(K, ws ? p.slices : 1, kBK2, per, nz);
+    if (nz <= 1) return launch2_tile<false>(p.tile, A, B, epi, M, N, K, per, nz, s);
+    EpiPartial part{ws, N, (int64_t)M * N};
+    hipError_t e = launch2_tile<false>(p.tile, A, B, part, M, N, K, per, nz, s);
+    if (e != hipSuccess) return e;
+    int64_t total = (int64_t)M * N;
+    hipLaunchKernelGGL((splitk_finish_kernel<Epi>), dim3(cdiv(total, 256)), dim3(256), 0, s, ws, epi, M, N, nz);
+    return hipGetLastError();
+}
+
+// Weight-gradient style GEMM: fp32 result [rows x cols] followed by the row sums of A (bias gradient).
+template <class AOp, class BOp>
+static hipError_t run2_wgrad(const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K, float* ws,
+                             hipStream_t s) {
+    GemmPlan p = plan_gemm(rows, cols, K);
+    int per, nz;
+    slice_geometry(K, ws ? p.slices : 1, kBK2, per, nz);
+    int64_t count = (int64_t)rows * cols + rows;
+    EpiWgrad epi{nz > 1 ? ws : gw, cols, (int64_t)rows * cols, count};
+    hipError_t e = launch2_tile<true>(p.tile, A, B, epi, rows, cols, (int)K, per, nz, s);
+    if (e != hipSuccess || nz <= 1) return e;
+    hipLaunchKernelGGL(slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, ws, gw, count, nz);
+    return hipGetLastError();
+}
+
+static int one_slice(int64_t K, int ktile) {
+    int per = cdiv(K, ktile) * ktile;
+    return per < ktile ? ktile : per;
+}
+
+// ---- element-wise fallbacks ------------------------------------------------------------------
+template <bool ROWSUM, class AOp, class BOp, class Epi>
+static hipError_t launch_bf16(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per, int nz,
+                              hipStream_t s) {
+    if (M <= 0 || N <= 0) return hipSuccess;
     dim3 grid(cdiv(N, 64), cdiv(M, 64), nz);
-    hipLaunchKernelGGL((gemm_f32_kernel<ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K,
+    hipLaunchKernelGGL((gemm_bf16_kernel<64, 64, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K,
                        per);
     return hipGetLastError();
 }
 
-// Number of slices the launchers will really use for a requested count (slice length is rounded up
-// to whole k-tiles, which can shrink the count).
-static int real_slices(int64_t K, int slices, int ktile) {
-    int per = cdiv(cdiv(K, slices), ktile) * ktile;
-    if (per < ktile) per = ktile;
-    return K > 0 ? cdiv(K, per) : 1;
+template <bool ROWSUM, class AOp, class BOp, class Epi>
+static hipError_t launch_f32(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per, int nz,
+                             hipStream_t s) {
+    if (M <= 0 || N <= 0) return hipSuccess;
+    dim3 grid(cdiv(N, 64), cdiv(M, 64), nz);
+    hipLaunchKernelGGL((gemm_f32_kernel<ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K, per);
+    return hipGetLastError();
 }
 
 template <typename T, class AOp, class BOp>
-static hipError_t wgrad_common(const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K,
-                               float* workspace, hipStream_t s) {
-    int slices = wgrad_slices(rows, cols, K);
+static hipError_t wgrad_fallback(const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K, float* ws,
+                                 hipStream_t s) {
+    GemmPlan p = plan_gemm(rows, cols, K);
     constexpr int ktile = sizeof(T) == 2 ? kBK : 16;
-    slices = real_slices(K, slices, ktile);
+    int per, nz;
+    slice_geometry(K, ws ? p.slices : 1, ktile, per, nz);
     int64_t count = (int64_t)rows * cols + rows;
-    EpiWgrad epi{slices > 1 ? workspace : gw, cols, (int64_t)rows * cols, count};
-    if (slices > 1 && workspace == nullptr) return hipErrorInvalidValue;
+    EpiWgrad epi{nz > 1 ? ws : gw, cols, (int64_t)rows * cols, count};
     hipError_t e;
     if constexpr (sizeof(T) == 2)
-        e = launch_bf16<true>(A, B, epi, rows, cols, (int)K, slices, s);
+        e = launch_bf16<true>(A, B, epi, rows, cols, (int)K, per, nz, s);
     else
-        e = launch_f32<true>(A, B, epi, rows, cols, (int)K, slices, s);
-    if (e != hipSuccess) return e;
-    if (slices > 1) {
-        hipLaunchKernelGGL(slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, workspace, gw, count,
-                           slices);
-        e = hipGetLastError();
-    }
-    return e;
+        e = launch_f32<true>(A, B, epi, rows, cols, (int)K, per, nz, s);
+    if (e != hipSuccess || nz <= 1) return e;
+    hipLaunchKernelGGL(slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, ws, gw, count, nz);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------- dense
 hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B, int Din,
-                         int Dout, int relu, int out_f32, hipStream_t s) {
+                         int Dout, int relu, int out_f32, float* ws, hipStream_t s) {
     if (dtype == kBF16) {
-        int vec = (Din % 8 == 0) && aligned16(x) && aligned16(w);
-        DenseView<bf16_t, true> A{(const bf16_t*)x, B, Din, Din, vec};
-        DenseView<bf16_t, true> Bv{(const bf16_t*)w, Dout, Din, Din, vec};
-        if (out_f32) {
-            EpiBiasAct<float> epi{(float*)y, bias, Dout, relu};
-            return launch_bf16<false>(A, Bv, epi, B, Dout, Din, 1, s);
+        const bool fast = (Din % 8 == 0) && aligned16(x) && aligned16(w);
+        if (fast) {
+            DenseKC A{(const bf16_t*)x, B, Din, Din};
+            DenseKC Bv{(const bf16_t*)w, Dout, Din, Din};
+            if (out_f32) return run2(A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
+            return run2(A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
         }
-        EpiBiasAct<bf16_t> epi{(bf16_t*)y, bias, Dout, relu};
-        return launch_bf16<false>(A, Bv, epi, B, Dout, Din, 1, s);
+        DenseView<bf16_t, true> A{(const bf16_t*)x, B, Din, Din, 0};
+        DenseView<bf16_t, true> Bv{(const bf16_t*)w, Dout, Din, Din, 0};
+        if (out_f32) return launch_bf16<false>(A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
+        return launch_bf16<false>(A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)x, B, Din, Din, 0};
     DenseView<float, true> Bv{(const float*)w, Dout, Din, Din, 0};
-    EpiBiasAct<float> epi{(float*)y, bias, Dout, relu};
-    return launch_f32<false>(A, Bv, epi, B, Dout, Din, 1, s);
+    return launch_f32<false>(A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, 16), 1, s);
 }
 
 hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int B, int Din,
-                       int Dout, hipStream_t s) {
+                       int Dout, float* ws, hipStream_t s) {
     // dx[m, n] = sum_k dy[m, k] * w[k, n]:  A = dy (k-contiguous), B(n, k) = w[k*Din + n] (row-contiguous)
     if (dtype == kBF16) {
-        int vec = (Dout % 8 == 0) && aligned16(dy);
-        DenseView<bf16_t, true> A{(const bf16_t*)dy, B, Dout, Dout, vec};
-        DenseView<bf16_t, false> Bv{(const bf16_t*)w, Din, Dout, Din, 0};
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din};
-        return launch_bf16<false>(A, Bv, epi, B, Din, Dout, 1, s);
+        const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(w);
+        if (fast) {
+            DenseKC A{(const bf16_t*)dy, B, Dout, Dout};
+            DenseRC Bv{(const bf16_t*)w, Din, Dout, Din};
+            return run2(A, Bv, epi, B, Din, Dout, ws, s);
+        }
+        DenseView<bf16_t, true> A{(const bf16_t*)dy, B, Dout, Dout, 0};
+        DenseView<bf16_t, false> Bv{(const bf16_t*)w, Din, Dout, Din, 0};
+        return launch_bf16<false>(A, Bv, epi, B, Din, Dout, one_slice(Dout, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)dy, B, Dout, Dout, 0};
     DenseView<float, false> Bv{(const float*)w, Din, Dout, Din, 0};
-    EpiMask<float, float> epi{(float*)dx, (const float*)mask, Din};
-    return launch_f32<false>(A, Bv, epi, B, Din, Dout, 1, s);
+    return launch_f32<false>(A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din}, B, Din, Dout, one_slice(Dout, 16), 1, s);
 }
 
-hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout,
-                       float* workspace, hipStream_t s) {
+hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout, float* ws,
+                       hipStream_t s) {
     // gw[m, n] = sum_k dy[k, m] * x[k, n]: both operands row-contiguous, contraction over the batch
     if (dtype == kBF16) {
+        const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(x);
+        if (fast) {
+            DenseRC A{(const bf16_t*)dy, Dout, B, Dout};
+            DenseRC Bv{(const bf16_t*)x, Din, B, Din};
+            return run2_wgrad(A, Bv, gw, Dout, Din, B, ws, s);
+        }
         DenseView<bf16_t, false> A{(const bf16_t*)dy, Dout, B, Dout, 0};
         DenseView<bf16_t, false> Bv{(const bf16_t*)x, Din, B, Din, 0};
-        return wgrad_common<bf16_t>(A, Bv, gw, Dout, Din, B, workspace, s);
+        return wgrad_fallback<bf16_t>(A, Bv, gw, Dout, Din, B, ws, s);
     }
     DenseView<float, false> A{(const float*)dy, Dout, B, Dout, 0};
     DenseView<float, false> Bv{(const float*)x, Din, B, Din, 0};
-    return wgrad_common<float>(A, Bv, gw, Dout, Din, B, workspace, s);
+    return wgrad_fallback<float>(A, Bv, gw, Dout, Din, B, ws, s);
 }
 
 // ---------------------------------------------------------------------------------- convolution
@@ -154,48 +217,73 @@ static ConvGeom geom(const ConvShape& c) {
     return ConvGeom{c.B, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.stride, c.pad};
 }
 
-hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y,
-                        const ConvShape& c, int relu, hipStream_t s) {
+static ConvGeom2 geom2(const ConvShape& c) {
+    ConvGeom2 g;
+    g.B = c.B; g.H = c.H; g.W = c.W; g.Cin = c.Cin; g.Ho = c.Ho; g.Wo = c.Wo; g.Cout = c.Cout;
+    g.R = c.R; g.S = c.S; g.stride = c.stride; g.pad = c.pad;
+    g.d_howo = FastDiv(c.Ho * c.Wo); g.d_wo = FastDiv(c.Wo);
+    g.d_hw = FastDiv(c.H * c.W); g.d_w = FastDiv(c.W);
+    g.d_scin = FastDiv(c.S * c.Cin); g.d_cin = FastDiv(c.Cin);
+    g.d_scout = FastDiv(c.S * c.Cout); g.d_cout = FastDiv(c.Cout);
+    g.d_stride = FastDiv(c.stride);
+    return g;
+}
+
+hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y, const ConvShape& c,
+                        int relu, float* ws, hipStream_t s) {
     int M = c.B * c.Ho * c.Wo, K = c.R * c.S * c.Cin;
     if (dtype == kBF16) {
-        ConvFwdA<bf16_t> A{(const bf16_t*)x, geom(c), M, K, (c.Cin % 8 == 0) && aligned16(x)};
-        DenseView<bf16_t, true> Bv{(const bf16_t*)w, c.Cout, K, K, (K % 8 == 0) && aligned16(w)};
         EpiBiasAct<bf16_t> epi{(bf16_t*)y, bias, c.Cout, relu};
-        return launch_bf16<false>(A, Bv, epi, M, c.Cout, K, 1, s);
+        if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w)) {
+            ConvFwdA2 A{(const bf16_t*)x, geom2(c), M, K};
+            DenseKC Bv{(const bf16_t*)w, c.Cout, K, K};
+            return run2(A, Bv, epi, M, c.Cout, K, ws, s);
+        }
+        ConvFwdA<bf16_t> A{(const bf16_t*)x, geom(c), M, K, 0};
+        DenseView<bf16_t, true> Bv{(const bf16_t*)w, c.Cout, K, K, 0};
+        return launch_bf16<false>(A, Bv, epi, M, c.Cout, K, one_slice(K, kBK), 1, s);
     }
     ConvFwdA<float> A{(const float*)x, geom(c), M, K, 0};
     DenseView<float, true> Bv{(const float*)w, c.Cout, K, K, 0};
-    EpiBiasAct<float> epi{(float*)y, bias, c.Cout, relu};
-    return launch_f32<false>(A, Bv, epi, M, c.Cout, K, 1, s);
+    return launch_f32<false>(A, Bv, EpiBiasAct<float>{(float*)y, bias, c.Cout, relu}, M, c.Cout, K, one_slice(K, 16), 1, s);
 }
 
-hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask,
-                      const ConvShape& c, hipStream_t s) {
+hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const ConvShape& c,
+                      float* ws, hipStream_t s) {
     int M = c.B * c.H * c.W, K = c.R * c.S * c.Cout;
     if (dtype == kBF16) {
-        ConvDgradA<bf16_t> A{(const bf16_t*)dy, geom(c), M, K, (c.Cout % 8 == 0) && aligned16(dy)};
-        ConvDgradB<bf16_t> Bv{(const bf16_t*)w, geom(c), c.Cin, K};
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, c.Cin};
-        return launch_bf16<false>(A, Bv, epi, M, c.Cin, K, 1, s);
+        if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w)) {
+            ConvDgradA2 A{(const bf16_t*)dy, geom2(c), M, K};
+            ConvDgradB2 Bv{(const bf16_t*)w, geom2(c), c.Cin, K};
+            return run2(A, Bv, epi, M, c.Cin, K, ws, s);
+        }
+        ConvDgradA<bf16_t> A{(const bf16_t*)dy, geom(c), M, K, 0};
+        ConvDgradB<bf16_t> Bv{(const bf16_t*)w, geom(c), c.Cin, K};
+        return launch_bf16<false>(A, Bv, epi, M, c.Cin, K, one_slice(K, kBK), 1, s);
     }
     ConvDgradA<float> A{(const float*)dy, geom(c), M, K, 0};
     ConvDgradB<float> Bv{(const float*)w, geom(c), c.Cin, K};
-    EpiMask<float, float> epi{(float*)dx, (const float*)mask, c.Cin};
-    return launch_f32<false>(A, Bv, epi, M, c.Cin, K, 1, s);
+    return launch_f32<false>(A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, c.Cin}, M, c.Cin, K, one_slice(K, 16), 1, s);
 }
 
-hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c,
-                      float* workspace, hipStream_t s) {
+hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c, float* ws,
+                      hipStream_t s) {
     int rows = c.Cout, cols = c.R * c.S * c.Cin;
     int64_t K = (int64_t)c.B * c.Ho * c.Wo;
     if (dtype == kBF16) {
+        if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(x)) {
+            DenseRC A{(const bf16_t*)dy, rows, (int)K, c.Cout};
+            ConvWgradB2 Bv{(const bf16_t*)x, geom2(c), cols, (int)K};
+            return run2_wgrad(A, Bv, gw, rows, cols, K, ws, s);
+        }
         DenseView<bf16_t, false> A{(const bf16_t*)dy, rows, (int)K, c.Cout, 0};
         ConvWgradB<bf16_t> Bv{(const bf16_t*)x, geom(c), cols, (int)K};
-        return wgrad_common<bf16_t>(A, Bv, gw, rows, cols, K, workspace, s);
+        return wgrad_fallback<bf16_t>(A, Bv, gw, rows, cols, K, ws, s);
     }
     DenseView<float, false> A{(const float*)dy, rows, (int)K, c.Cout, 0};
     ConvWgradB<float> Bv{(const float*)x, geom(c), cols, (int)K};
-    return wgrad_common<float>(A, Bv, gw, rows, cols, K, workspace, s);
+    return wgrad_fallback<float>(A, Bv, gw, rows, cols, K, ws, s);
 }
 
 }  // namespace tmps

@@ -75,7 +75,8 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                 if (d[0] < 1 || d[1] < 1) return fail(TMPS_EINVAL, "layer %d: linear dims must be positive", i);
                 L.in_elems = d[0]; L.out_elems = d[1];
                 L.w_count = (int64_t)d[0] * d[1]; L.b_count = d[1];
-                L.ws_elems = wgrad_workspace_elems(d[1], d[0], M);
+                L.ws_elems = std::max({gemm_workspace_elems(cfg->micro_batch, d[1], d[0], 0),
+                                       gemm_workspace_elems(M, d[0], d[1], 0), gemm_workspace_elems(d[1], d[0], M, 1)});
                 break;
             case TMPS_CONV2D: {
                 for (int k = 0; k < 7; ++k)
@@ -86,7 +87,10 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                 L.in_elems = (int64_t)c.H * c.W * c.Cin;
                 L.out_elems = (int64_t)c.Ho * c.Wo * c.Cout;
                 L.w_count = (int64_t)c.Cout * c.R * c.S * c.Cin; L.b_count = c.Cout;
-                L.ws_elems = wgrad_workspace_elems(c.Cout, c.R * c.S * c.Cin, (int64_t)M * c.Ho * c.Wo);
+                const int64_t kf = (int64_t)c.R * c.S * c.Cin, kd = (int64_t)c.R * c.S * c.Cout;
+                L.ws_elems = std::max({gemm_workspace_elems((int64_t)cfg->micro_batch * c.Ho * c.Wo, c.Cout, kf, 0),
+                                       gemm_workspace_elems((int64_t)M * c.H * c.W, c.Cin, kd, 0),
+                                       gemm_workspace_elems(c.Cout, kf, (int64_t)M * c.Ho * c.Wo, 1)});
                 break;
             }
             case TMPS_MAXPOOL: {
@@ -250,6 +254,7 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
     const int dt = st->cfg.dtype;
     const int64_t row0 = (int64_t)slot * mb;
     const void* in = x;
+    float* ws = reinterpret_cast<float*>(st->scratch + st->ws_off);
     if (!st->cfg.borrow_input) {
         char* dst = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->asz;
         TMPS_RUN(kcCopy, s, hipMemcpyAsync(dst, x, (size_t)mb * st->in_elems * st->asz, hipMemcpyDeviceToDevice, s));
@@ -262,10 +267,10 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
         const int32_t* d = L.d.dims;
         switch (L.d.kind) {
             case TMPS_LINEAR:
-                TMPS_RUN(kcDenseFwd, s, dense_forward(dt, in, st->wptr(L), st->bptr(L), out, mb, d[0], d[1], L.relu, L.out_f32, s));
+                TMPS_RUN(kcDenseFwd, s, dense_forward(dt, in, st->wptr(L), st->bptr(L), out, mb, d[0], d[1], L.relu, L.out_f32, ws, s));
                 break;
             case TMPS_CONV2D:
-                TMPS_RUN(kcConvFwd, s, conv_forward(dt, in, st->wptr(L), st->bptr(L), out, conv_shape(L.d, mb), L.relu, s));
+                TMPS_RUN(kcConvFwd, s, conv_forward(dt, in, st->wptr(L), st->bptr(L), out, conv_shape(L.d, mb), L.relu, ws, s));
                 break;
             case TMPS_MAXPOOL:
                 TMPS_RUN(kcPoolFwd, s, maxpool_forward(dt, in, out, mb, d[0], d[1], d[2], d[3], d[4], s));
@@ -348,12 +353,12 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         switch (L.d.kind) {
             case TMPS_LINEAR:
                 TMPS_RUN(kcDenseWgrad, s, dense_wgrad(dt, g, in, gw, M, d[0], d[1], ws, s));
-                if (want_dx) TMPS_RUN(kcDenseDgrad, s, dense_dgrad(dt, g, st->wptr(L), dst, mask, M, d[0], d[1], s));
+                if (want_dx) TMPS_RUN(kcDenseDgrad, s, dense_dgrad(dt, g, st->wptr(L), dst, mask, M, d[0], d[1], ws, s));
                 break;
             case TMPS_CONV2D: {
                 ConvShape c = conv_shape(L.d, M);
                 TMPS_RUN(kcConvWgrad, s, conv_wgrad(dt, g, in, gw, c, ws, s));
-                if (want_dx) TMPS_RUN(kcConvDgrad, s, conv_dgrad(dt, g, st->wptr(L), dst, mask, c, s));
+                if (want_dx) TMPS_RUN(kcConvDgrad, s, conv_dgrad(dt, g, st->wptr(L), dst, mask, c, ws, s));
                 break;
             }
             case TMPS_MAXPOOL:
