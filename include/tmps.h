@@ -172,7 +172,10 @@ int tmps_version_diff_simulated(int W, int N);
  * labels: device int32, n_minibatches*M.  losses_out: device float[n_minibatches], the mean
  * of the N micro-batch losses.  version_log_out: host int32[7 * tasks] as tmps_schedule_plan,
  * except that field 5 is read from the stage objects as the tasks are issued; may be NULL.
- * Cross-stage dependencies are HIP events; the call returns after all K streams are idle. */
+ * Cross-stage dependencies are HIP events.  Each stage's tasks are issued by a host thread of its
+ * own (one per stage, joined before the call returns; set the environment variable
+ * TMPS_ISSUE_THREADS=0 to issue everything from the calling thread).  The call returns after all K
+ * streams are idle. */
 int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
                       const int32_t* labels, void** hip_streams, float* losses_out,
                       int32_t* version_log_out);

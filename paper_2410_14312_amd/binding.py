@@ -159,7 +159,17 @@ class Stage:
                  device="cuda:0"):
         import torch
         self.torch = torch
-        self.specs = list(specs)
+        self.logical_specs = list(specs)
+        # bf16 contractions fetch 8 channels per 16-byte load: a stage that starts with a convolution on
+        # fewer channels (an RGB image) is handed channel-padded inputs and filters (zeros), which leaves
+        # every result unchanged; set_params / get_* / prepare_input / crop_input_grad convert.
+        self.cin, self.cin_pad = None, None
+        specs = list(specs)
+        if dtype == "bf16" and specs[0]["kind"] == "conv" and specs[0]["cin"] % 8 != 0:
+            self.cin = specs[0]["cin"]
+            self.cin_pad = (self.cin + 7) // 8 * 8
+            specs[0] = dict(specs[0], cin=self.cin_pad)
+        self.specs = specs
         self.device = torch.device(device)
         self.is_last = specs[-1]["kind"] == "softmax_ce"
         self.cfg = StageCfg(TMPS_BF16_F32MASTER if dtype == "bf16" else TMPS_F32, micro_batch, n_micro, max_stash,
@@ -206,6 +216,8 @@ class Stage:
                     p["w"] = p["w"].reshape(sp["dout"], sp["din"])
                 elif sp["kind"] == "conv":
                     p["w"] = p["w"].reshape(sp["cout"], sp["r"], sp["s"], sp["cin"])
+                    if li == 0 and self.cin_pad:
+                        p["w"] = np.ascontiguousarray(p["w"][..., :self.cin])
             out.append(p)
         return out
 
@@ -217,12 +229,30 @@ class Stage:
             for which, key in ((0, "w"), (1, "b")):
                 off, cnt = self.param_offset(li, which)
                 if cnt:
-                    host[off:off + cnt] = np.asarray(p[key], dtype=np.float32).reshape(-1)
+                    v = np.asarray(p[key], dtype=np.float32)
+                    if li == 0 and key == "w" and self.cin_pad:
+                        v = np.concatenate([v, np.zeros(v.shape[:-1] + (self.cin_pad - self.cin,), np.float32)], axis=-1)
+                    host[off:off + cnt] = v.reshape(-1)
         self._flat(0, 0).copy_(torch.from_numpy(host))
         self.regions[1].zero_()
         torch.cuda.synchronize(self.device)
         _check(lib().tmps_stage_sync_params(self.handle, C.c_void_p(self._stream(stream))))
         torch.cuda.synchronize(self.device)
+
+    def prepare_input(self, x):
+        """Host array [rows, ...] -> device tensor in the layout and dtype the stage reads."""
+        torch = self.torch
+        x = np.asarray(x, dtype=np.float32)
+        if self.cin_pad:
+            x = np.concatenate([x, np.zeros(x.shape[:-1] + (self.cin_pad - self.cin,), np.float32)], axis=-1)
+        return torch.from_numpy(np.ascontiguousarray(x)).to(self.act_dtype).to(self.device)
+
+    def crop_input_grad(self, dx, rows):
+        """Device gradient w.r.t. the stage input -> host fp32 array with the logical channel count."""
+        a = dx.float().cpu().numpy().reshape(rows, -1)
+        if self.cin_pad:
+            a = a.reshape(-1, self.cin_pad)[:, :self.cin].reshape(rows, -1)
+        return a
 
     def get_params(self):
         return self._get(self._flat(0, 0))
@@ -283,9 +313,9 @@ class Pipeline:
     def upload(self, batches):
         """Concatenate mini-batches and place them in HBM (inputs in the activation dtype, labels int32)."""
         torch = self.torch
-        x = torch.from_numpy(np.concatenate([b[0] for b in batches], axis=0)).to(self.act_dtype)
+        x = self.stages[0].prepare_input(np.concatenate([b[0] for b in batches], axis=0))
         y = torch.from_numpy(np.concatenate([b[1] for b in batches], axis=0).astype(np.int32))
-        return x.to(self.device).contiguous(), y.to(self.device).contiguous()
+        return x.contiguous(), y.to(self.device).contiguous()
 
     def run_device(self, x_dev, y_dev, n_minibatches, losses_dev, want_log=True):
         """Launch on resident inputs.  Returns the version log (n_tasks x 7 int32) or None."""

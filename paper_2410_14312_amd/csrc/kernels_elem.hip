@@ -178,14 +178,12 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, i
     y[i] = from_f32<T>(best);
 }
 
-// One thread per window: finds the first maximum and routes dy to it; every input position covered by
-// exactly one window when stride == k, otherwise positions are accumulated with overlapping windows
-// handled by a gather over the windows that contain them (general kernel below).
+// Gather form, one thread per INPUT element: sum dy over the windows whose winner (first maximum in
+// row-major window order) it is.  Handles overlapping windows and inputs no window covers.
 template <typename T>
 __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx,
                                    int B, int H, int W, int C, int Ho, int Wo, int k, int stride,
                                    int relu_mask) {
-    // gather form, one thread per INPUT element: sum dy over the windows whose winner it is
     int64_t total = (int64_t)B * H * W * C;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -197,12 +195,10 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict_
     float xv = to_f32(x[i]);
     float acc = 0.0f;
     if (!(relu_mask && !(xv > 0.0f))) {
-        // windows (ho, wo) with ho*stride <= h < ho*stride + k
         int ho_lo = h - k + 1 > 0 ? (h - k + 1 + stride - 1) / stride : 0;
         int wo_lo = w - k + 1 > 0 ? (w - k + 1 + stride - 1) / stride : 0;
         for (int ho = ho_lo; ho < Ho && ho * stride <= h; ++ho)
             for (int wo = wo_lo; wo < Wo && wo * stride <= w; ++wo) {
-                // is (h, w) the first maximum of this window?
                 bool win = true;
                 for (int r = 0; r < k && win; ++r)
                     for (int s = 0; s < k; ++s) {
@@ -215,6 +211,44 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict_
             }
     }
     dx[i] = from_f32<T>(acc);
+}
+
+// 2x2 windows with stride 2 on even H, W and C % 8 == 0 (bf16): one thread per window and 8 channels,
+// 16-byte loads of the 4 inputs and of dy, 16-byte stores of the 4 gradients.
+__global__ __launch_bounds__(256) void maxpool2x2_bwd_bf16_kernel(const bf16_t* __restrict__ x,
+                                                                  const bf16_t* __restrict__ dy,
+                                                                  bf16_t* __restrict__ dx, int B, int H, int W,
+                                                                  int C, int relu_mask) {
+    const int Ho = H >> 1, Wo = W >> 1, C8 = C >> 3;
+    int64_t total = (int64_t)B * Ho * Wo * C8;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int c8 = (int)(i % C8);
+    int64_t t = i / C8;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    Pack8 in[4], out[4], g;
+    g.u = *reinterpret_cast<const uint4*>(dy + i * 8);
+    int64_t base = (((int64_t)n * H + 2 * ho) * W + 2 * wo) * C + c8 * 8;
+    const int64_t off[4] = {0, C, (int64_t)W * C, (int64_t)W * C + C};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) in[q].u = *reinterpret_cast<const uint4*>(x + base + off[q]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = (float)in[q].h[e];
+        int best = 0;
+#pragma unroll
+        for (int q = 1; q < 4; ++q)
+            if (v[q] > v[best]) best = q;
+        const bool pass = !(relu_mask && !(v[best] > 0.0f));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[q].h[e] = (q == best && pass) ? g.h[e] : (bf16_t)0.0f;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(dx + base + off[q]) = out[q].u;
 }
 
 hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int W, int C, int k, int stride,
@@ -237,6 +271,14 @@ hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, 
     int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
     int64_t total = (int64_t)B * H * W * C;
     if (total <= 0) return hipSuccess;
+    if (dtype == kBF16 && k == 2 && stride == 2 && H % 2 == 0 && W % 2 == 0 && C % 8 == 0 &&
+        (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(dx) & 15) == 0) {
+        int64_t windows = (int64_t)B * Ho * Wo * (C / 8);
+        hipLaunchKernelGGL(maxpool2x2_bwd_bf16_kernel, dim3(cdiv64(windows, 256)), dim3(256), 0, s, (const bf16_t*)x,
+                           (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, relu_mask);
+        return hipGetLastError();
+    }
     dim3 grid(cdiv64(total, 256));
     if (dtype == kBF16)
         hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x,

@@ -1,11 +1,21 @@
 // One-GPU pipeline emulator: K stages on K HIP streams, tasks issued in nF1B order, cross-stage
 // dependencies as events (sections "Work Scheduling" and "Overlapping of Computation and
 // Communication": what would be a message between workers is an event between streams here).
+//
+// Each stage has its own host thread that issues that stage's tasks in schedule order on the stage's
+// stream, like a worker process would; a thread that needs another stage's result first waits until
+// the producing thread has recorded the event, then makes its stream wait for it.
+#include <stdlib.h>
+#include <string.h>
+
+#include <atomic>
+#include <chrono>
+#include <thread>
 #include <vector>
 
+#include "profile.h"
 #include "schedule.h"
 #include "stage.h"
-#include "profile.h"
 
 using namespace tmps;
 
@@ -25,6 +35,100 @@ struct EventPool {
         return TMPS_OK;
     }
 };
+
+struct RunCtx {
+    tmps_stage** stages;
+    int K, N, M, mb, n_minibatches;
+    const void* inputs;
+    const int32_t* labels;
+    void** streams;
+    float* losses_out;
+    int32_t* log;
+    size_t asz, total_micro, n_fwd_ev;
+    std::vector<int> groups;
+    EventPool pool;
+    std::vector<std::atomic<unsigned char>> recorded;
+    std::atomic<int> err{TMPS_OK};
+    char err_text[512];
+    std::atomic_flag err_lock = ATOMIC_FLAG_INIT;
+
+    size_t fwd_ev(int s, size_t q) const { return (size_t)s * total_micro + q; }
+    size_t bwd_ev(int s, int b0) const { return n_fwd_ev + (size_t)s * n_minibatches + b0; }
+
+    // Block until the producer thread has recorded event e (or a thread failed), then make stream s wait for it.
+    int wait_for(size_t e, hipStream_t s) {
+        while (!recorded[e].load(std::memory_order_acquire)) {
+            if (err.load(std::memory_order_relaxed) != TMPS_OK) return TMPS_EINVAL;
+            std::this_thread::yield();
+        }
+        TMPS_HIP(hipStreamWaitEvent(s, pool.ev[e], 0));
+        return TMPS_OK;
+    }
+    int record(size_t e, hipStream_t s) {
+        TMPS_HIP(hipEventRecord(pool.ev[e], s));
+        recorded[e].store(1, std::memory_order_release);
+        return TMPS_OK;
+    }
+    void set_error(int rc) {
+        while (err_lock.test_and_set(std::memory_order_acquire)) {}
+        if (err.load() == TMPS_OK) {
+            strncpy(err_text, tmps_last_error(), sizeof(err_text) - 1);
+            err_text[sizeof(err_text) - 1] = 0;
+            err.store(rc);
+        }
+        err_lock.clear(std::memory_order_release);
+    }
+};
+
+// Issue one task on its stage's stream.
+int issue(RunCtx& c, const Task& k, size_t ti) {
+    tmps_stage* st = c.stages[k.stage];
+    hipStream_t s = (hipStream_t)c.streams[k.stage];
+    const int b0 = k.b - 1, N = c.N, K = c.K;
+    if (c.log) {
+        int32_t* o = c.log + 7 * ti;
+        o[0] = k.t; o[1] = k.stage; o[2] = k.kind; o[3] = k.b; o[4] = k.j;
+        o[5] = (int32_t)st->version; o[6] = k.net_version;
+    }
+    const int group = b0 % c.groups[k.stage];
+    int rc;
+    if (k.kind == kFwd) {
+        const size_t q = (size_t)b0 * N + k.j;
+        const int slot = group * N + k.j;
+        const void* x;
+        if (k.stage == 0) {
+            x = (const char*)c.inputs + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->in_elems * c.asz;
+        } else {
+            x = tmps_stage_output_ptr(c.stages[k.stage - 1], (b0 % c.groups[k.stage - 1]) * N + k.j);
+            if ((rc = c.wait_for(c.fwd_ev(k.stage - 1, q), s)) != TMPS_OK) return rc;
+        }
+        const int32_t* lab = st->cfg.is_last ? c.labels + (size_t)b0 * c.M + (size_t)k.j * c.mb : nullptr;
+        if ((rc = tmps_forward_micro(st, slot, x, nullptr, lab, nullptr, s)) != TMPS_OK) return rc;
+        if (k.stage < K - 1 && (rc = c.record(c.fwd_ev(k.stage, q), s)) != TMPS_OK) return rc;
+        if (st->cfg.is_last && k.j == N - 1 && c.losses_out) {
+            ProfileScope scope(kcReduce, s);
+            TMPS_HIP(reduce_scaled_sum(stage_row_loss(st, group * N), c.M, 1.0f / (float)c.M, c.losses_out + b0, s));
+        }
+    } else {
+        const void* dy = nullptr;
+        if (k.stage < K - 1) {
+            dy = stage_dxout(c.stages[k.stage + 1], b0 & 1);
+            if ((rc = c.wait_for(c.bwd_ev(k.stage + 1, b0), s)) != TMPS_OK) return rc;
+        }
+        void* dx = nullptr;
+        if (k.stage > 0) {
+            dx = stage_dxout(st, b0 & 1);
+            // the worker below must have consumed what this buffer held two mini-batches ago
+            if (b0 >= 2 && (rc = c.wait_for(c.bwd_ev(k.stage - 1, b0 - 2), s)) != TMPS_OK) return rc;
+        }
+        int slots[64];
+        for (int j = 0; j < N; ++j) slots[j] = group * N + j;
+        if ((rc = tmps_backward(st, slots, N, dy, dx, s)) != TMPS_OK) return rc;
+        if ((rc = c.record(c.bwd_ev(k.stage, b0), s)) != TMPS_OK) return rc;
+        if ((rc = tmps_update(st, s)) != TMPS_OK) return rc;
+    }
+    return TMPS_OK;
+}
 
 }  // namespace
 
@@ -51,75 +155,69 @@ extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_miniba
         for (char u : st->slot_used)
             if (u) return fail(TMPS_ESLOT, "stage %d has a stash slot in use", s);
     }
-    const int M = mb * N;
     const std::vector<Task> tasks = plan_nf1b(K, N, n_minibatches);
-    const size_t total_micro = (size_t)n_minibatches * N;
 
-    // events: forward (stage, micro-batch) for s < K-1, backward (stage, mini-batch) for every stage
-    EventPool pool;
-    const size_t n_fwd_ev = (size_t)(K - 1) * total_micro;
-    int rc = pool.grow(n_fwd_ev + (size_t)K * n_minibatches);
+    RunCtx c;
+    c.stages = stages; c.K = K; c.N = N; c.mb = mb; c.M = mb * N; c.n_minibatches = n_minibatches;
+    c.inputs = inputs; c.labels = labels; c.streams = hip_streams; c.losses_out = losses_out;
+    c.log = version_log_out;
+    c.asz = stages[0]->asz;
+    c.total_micro = (size_t)n_minibatches * N;
+    c.n_fwd_ev = (size_t)(K - 1) * c.total_micro;
+    c.groups.resize(K);
+    for (int s = 0; s < K; ++s) c.groups[s] = stages[s]->cfg.max_stash / N;
+    const size_t n_events = c.n_fwd_ev + (size_t)K * n_minibatches;
+    int rc = c.pool.grow(n_events);
     if (rc != TMPS_OK) return rc;
-    auto fwd_ev = [&](int s, size_t q) { return pool.ev[(size_t)s * total_micro + q]; };
-    auto bwd_ev = [&](int s, int b0) { return pool.ev[n_fwd_ev + (size_t)s * n_minibatches + b0]; };
+    c.recorded = std::vector<std::atomic<unsigned char>>(n_events);
+    for (auto& f : c.recorded) f.store(0, std::memory_order_relaxed);
 
-    std::vector<int> groups(K);
-    for (int s = 0; s < K; ++s) groups[s] = stages[s]->cfg.max_stash / N;
-    const size_t asz = stages[0]->asz;
-    std::vector<int> slots(N);
+    // per-stage task lists (indices into `tasks`, which is also the order of the version log)
+    std::vector<std::vector<size_t>> mine(K);
+    for (size_t i = 0; i < tasks.size(); ++i) mine[tasks[i].stage].push_back(i);
 
-    size_t ti = 0;
-    for (const Task& k : tasks) {
-        tmps_stage* st = stages[k.stage];
-        hipStream_t s = (hipStream_t)hip_streams[k.stage];
-        const int b0 = k.b - 1;
-        if (version_log_out) {
-            int32_t* o = version_log_out + 7 * ti;
-            o[0] = k.t; o[1] = k.stage; o[2] = k.kind; o[3] = k.b; o[4] = k.j;
-            o[5] = (int32_t)st->version; o[6] = k.net_version;
-        }
-        ++ti;
-        const int group = b0 % groups[k.stage];
-        if (k.kind == kFwd) {
-            const size_t q = (size_t)b0 * N + k.j;
-            const int slot = group * N + k.j;
-            const void* x;
-            if (k.stage == 0) {
-                x = (const char*)inputs + ((size_t)b0 * M + (size_t)k.j * mb) * st->in_elems * asz;
-            } else {
-                tmps_stage* prev = stages[k.stage - 1];
-                x = tmps_stage_output_ptr(prev, (b0 % groups[k.stage - 1]) * N + k.j);
-                TMPS_HIP(hipStreamWaitEvent(s, fwd_ev(k.stage - 1, q), 0));
+    const char* env = getenv("TMPS_ISSUE_THREADS");
+    const bool threaded = K > 1 && !(env && env[0] == '0');
+    const bool report = getenv("TMPS_REPORT_ISSUE_TIME") != nullptr;
+    const auto t0 = std::chrono::steady_clock::now();
+    if (threaded) {
+        int dev = 0;
+        TMPS_HIP(hipGetDevice(&dev));
+        std::vector<std::thread> workers;
+        for (int s = 0; s < K; ++s)
+            workers.emplace_back([&, s]() {
+                if (hipSetDevice(dev) != hipSuccess) {
+                    fail(TMPS_EHIP, "hipSetDevice failed in an issue thread");
+                    c.set_error(TMPS_EHIP);
+                    return;
+                }
+                for (size_t i : mine[s]) {
+                    if (c.err.load(std::memory_order_relaxed) != TMPS_OK) return;
+                    int r = issue(c, tasks[i], i);
+                    if (r != TMPS_OK) {
+                        if (c.err.load() == TMPS_OK) c.set_error(r);
+                        return;
+                    }
+                }
+            });
+        for (std::thread& t : workers) t.join();
+    } else {
+        for (size_t i = 0; i < tasks.size(); ++i) {
+            int r = issue(c, tasks[i], i);
+            if (r != TMPS_OK) {
+                c.set_error(r);
+                break;
             }
-            const int32_t* lab = st->cfg.is_last ? labels + (size_t)b0 * M + (size_t)k.j * mb : nullptr;
-            rc = tmps_forward_micro(st, slot, x, nullptr, lab, nullptr, s);
-            if (rc != TMPS_OK) return rc;
-            if (k.stage < K - 1) TMPS_HIP(hipEventRecord(fwd_ev(k.stage, q), s));
-            if (st->cfg.is_last && k.j == N - 1 && losses_out)
-            {
-                ProfileScope scope(kcReduce, s);
-                TMPS_HIP(reduce_scaled_sum(stage_row_loss(st, group * N), M, 1.0f / (float)M, losses_out + b0, s));
-            }
-        } else {
-            const void* dy = nullptr;
-            if (k.stage < K - 1) {
-                dy = stage_dxout(stages[k.stage + 1], b0 & 1);
-                TMPS_HIP(hipStreamWaitEvent(s, bwd_ev(k.stage + 1, b0), 0));
-            }
-            void* dx = nullptr;
-            if (k.stage > 0) {
-                dx = stage_dxout(st, b0 & 1);
-                // the worker below must have consumed what this buffer held two mini-batches ago
-                if (b0 >= 2) TMPS_HIP(hipStreamWaitEvent(s, bwd_ev(k.stage - 1, b0 - 2), 0));
-            }
-            for (int j = 0; j < N; ++j) slots[j] = group * N + j;
-            rc = tmps_backward(st, slots.data(), N, dy, dx, s);
-            if (rc != TMPS_OK) return rc;
-            TMPS_HIP(hipEventRecord(bwd_ev(k.stage, b0), s));
-            rc = tmps_update(st, s);
-            if (rc != TMPS_OK) return rc;
         }
     }
+    const auto t1 = std::chrono::steady_clock::now();
     for (int s = 0; s < K; ++s) TMPS_HIP(hipStreamSynchronize((hipStream_t)hip_streams[s]));
+    if (c.err.load() != TMPS_OK) return fail(c.err.load(), "%s", c.err_text);
+    if (report) {
+        const auto t2 = std::chrono::steady_clock::now();
+        fprintf(stderr, "tmps_schedule_run: %d mini-batches, host issue %.3f ms, until idle %.3f ms\n", n_minibatches,
+                std::chrono::duration<double, std::milli>(t1 - t0).count(),
+                std::chrono::duration<double, std::milli>(t2 - t0).count());
+    }
     return TMPS_OK;
 }
