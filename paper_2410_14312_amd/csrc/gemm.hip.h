@@ -192,6 +192,13 @@ template <typename TOut> struct EpiBiasAct {
         if (relu) v = v > 0.0f ? v : 0.0f;
         out[(int64_t)m * ld + n] = from_f32<TOut>(v);
     }
+    // the same in two steps: column(n) fetches the bias once, at() finishes element idx = m*ld + n
+    __device__ __forceinline__ float column(int n) const { return bias ? bias[n] : 0.0f; }
+    __device__ __forceinline__ void at(float b, int64_t idx, float v, int) const {
+        v += b;
+        if (relu) v = v > 0.0f ? v : 0.0f;
+        out[idx] = from_f32<TOut>(v);
+    }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 
@@ -202,6 +209,11 @@ template <typename TOut, typename TMask> struct EpiMask {
     int64_t ld;
     __device__ __forceinline__ void operator()(int m, int n, float v, int) const {
         int64_t i = (int64_t)m * ld + n;
+        if (mask && !(to_f32(mask[i]) > 0.0f)) v = 0.0f;
+        out[i] = from_f32<TOut>(v);
+    }
+    __device__ __forceinline__ int column(int) const { return 0; }
+    __device__ __forceinline__ void at(int, int64_t i, float v, int) const {
         if (mask && !(to_f32(mask[i]) > 0.0f)) v = 0.0f;
         out[i] = from_f32<TOut>(v);
     }
@@ -217,6 +229,10 @@ struct EpiWgrad {
     int64_t slice_stride;  // rows*cols + rows
     __device__ __forceinline__ void operator()(int m, int n, float v, int z) const {
         out[z * slice_stride + (int64_t)m * ld + n] = v;
+    }
+    __device__ __forceinline__ int column(int) const { return 0; }
+    __device__ __forceinline__ void at(int, int64_t idx, float v, int z) const {
+        out[z * slice_stride + idx] = v;
     }
     __device__ __forceinline__ void rowsum(int m, float v, int z) const {
         out[z * slice_stride + bias_off + m] = v;

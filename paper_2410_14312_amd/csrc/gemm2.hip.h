@@ -13,8 +13,10 @@
 // Dense forward (A, B k-contiguous), dense input gradient (B = W row-contiguous), dense weight
 // gradient (both row-contiguous) and the three implicit-GEMM forms of convolution are instances.
 //
-// 256 threads = 4 waves (2x2), wave tile (BM/2)x(BN/2) of 32x32x16 MFMA tiles, BK = 64.  Global loads
-// of tile t+1 are in flight while tile t is multiplied (register staging, single LDS buffer).
+// 256 threads = 4 waves (2x2), wave tile (BM/2)x(BN/2) of 32x32x16 MFMA tiles, BK = 64.  The global
+// loads of the next D k-tiles are in flight in a register ring while the current tile is multiplied
+// (these contractions are short and few workgroups share a CU, so memory latency has to be hidden
+// inside the workgroup); LDS is double-buffered, one barrier per k-tile.
 // blockIdx.z selects a k-slice; with more than one slice the epilogue stores fp32 partial sums that a
 // finishing kernel reduces.
 #pragma once
@@ -43,28 +45,48 @@ struct FastDiv {
 
 constexpr int kBK2 = 64;
 
+__device__ __forceinline__ uint4 zero16() { return make_uint4(0, 0, 0, 0); }
+__device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+// Load that is ALWAYS issued: lanes whose chunk lies outside the operand read 16 zero bytes from a
+// dummy location instead.  With neither a branch around the load nor a select on its result, the
+// compiler counts the loads in flight exactly and a tile is waited for only when it is copied to LDS,
+// D tiles after it was requested.
+static __device__ __attribute__((aligned(16))) uint4 g_zero_chunk;  // zero-initialised, never written
+__device__ __forceinline__ uint4 ld16_if(const bf16_t* base, int64_t off, bool ok) {
+    const bf16_t* p = ok ? base + off : reinterpret_cast<const bf16_t*>(&g_zero_chunk);
+    return ld16(p);
+}
+// full-rate 24-bit multiply (both factors below 2^24, product below 2^31)
+__device__ __forceinline__ int mul24(int a, int b) { return __mul24(a, b); }
+
 // ------------------------------------------------------------------------------------------
-// Loaders.  KC loaders: init(ctx, row, kc) once per thread-chunk with the global row and the chunk
-// index kc (k offset kc*8 inside a tile); load(ctx, kb, k_end) returns the 16 bytes at k = kb + kc*8
-// (zeros when out of range).  RC (row-contiguous) loaders: init(ctx, row0, kl) with the first of 8
-// consecutive rows and the k offset kl inside a tile; load(ctx, kb, k_end) returns rows row0..row0+7
-// at k = kb + kl.
+// Loaders.  A thread fetches a fixed set of 16-byte chunks of every k-tile; a loader is an iterator
+// over k-tiles, so that the k-loop needs no integer division and no 64-bit multiply:
+//   init_thread(ks, k_begin, col)  per-thread state for the first tile; col = the thread's chunk column
+//                                  (k offset col*8) for k-contiguous loaders, unused otherwise
+//   init(ctx, row, col, k_begin)   per-chunk state.  k-contiguous: row = global row.  row-contiguous:
+//                                  row = first of 8 consecutive rows, col = k offset inside a tile.
+//   load(ctx, ks, k_end)           the chunk of the current tile (zeros outside the operand); called once
+//                                  per tile and chunk, in order; may step per-chunk state
+//   next(ks)                       step the per-thread state to the next tile (k += 64)
+// Element offsets are 32-bit: every tensor here has fewer than 2^31 elements.
 // ------------------------------------------------------------------------------------------
 struct DenseKC {
     static constexpr bool kContig = true;
     const bf16_t* p;
     int rows, K;
     int64_t ld;
-    struct Ctx { const bf16_t* q; int koff; bool ok; };
-    __device__ __forceinline__ void init(Ctx& c, int row, int kc) const {
+    struct KS { int k; };
+    struct Ctx { int64_t roff; bool ok; };
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int col) const { ks.k = k_begin + col * 8; }
+    __device__ __forceinline__ void init(Ctx& c, int row, int, int) const {
         c.ok = row < rows;
-        c.koff = kc * 8;
-        c.q = p + (int64_t)(c.ok ? row : 0) * ld + c.koff;
+        c.roff = (int64_t)(c.ok ? row : 0) * ld;
     }
-    __device__ __forceinline__ uint4 load(const Ctx& c, int kb, int k_end) const {
-        if (c.ok && kb + c.koff + 8 <= k_end) return *reinterpret_cast<const uint4*>(c.q + kb);
-        return make_uint4(0, 0, 0, 0);
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        return ld16_if(p, c.roff + ks.k, c.ok && ks.k + 8 <= k_end);
     }
+    __device__ __forceinline__ void next(KS& ks) const { ks.k += kBK2; }
 };
 
 struct DenseRC {
@@ -72,16 +94,20 @@ struct DenseRC {
     const bf16_t* p;  // element(row, k) = p[k*ld + row]
     int rows, K;
     int64_t ld;
-    struct Ctx { const bf16_t* q; int kl; bool ok; };
-    __device__ __forceinline__ void init(Ctx& c, int row0, int kl) const {
+    struct KS { int kb; };
+    struct Ctx { int64_t off; int kl; bool ok; };
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int) const { ks.kb = k_begin; }
+    __device__ __forceinline__ void init(Ctx& c, int row0, int kl, int k_begin) const {
         c.ok = row0 + 8 <= rows;
         c.kl = kl;
-        c.q = p + (c.ok ? row0 : 0) + (int64_t)kl * ld;
+        c.off = (c.ok ? row0 : 0) + (int64_t)(k_begin + kl) * ld;
     }
-    __device__ __forceinline__ uint4 load(const Ctx& c, int kb, int k_end) const {
-        if (c.ok && kb + c.kl < k_end) return *reinterpret_cast<const uint4*>(c.q + (int64_t)kb * ld);
-        return make_uint4(0, 0, 0, 0);
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        uint4 v = ld16_if(p, c.off, c.ok && ks.kb + c.kl < k_end);
+        c.off += kBK2 * ld;
+        return v;
     }
+    __device__ __forceinline__ void next(KS& ks) const { ks.kb += kBK2; }
 };
 
 struct ConvGeom2 {
@@ -90,31 +116,44 @@ struct ConvGeom2 {
 };
 
 // Forward A: row m = (n, ho, wo), k = (r, s, c) -> x[n, ho*stride + r - pad, wo*stride + s - pad, c].
+// Per thread: (r, s, c) of its chunk column, stepped by 64 channels per tile.
 struct ConvFwdA2 {
     static constexpr bool kContig = true;
     const bf16_t* x;
     ConvGeom2 g;
     int rows, K;
-    struct Ctx { int64_t base; int h0, w0, koff; bool ok; };
-    __device__ __forceinline__ void init(Ctx& c, int m, int kc) const {
+    struct KS { int k, r, s, ch, koff; };
+    struct Ctx { int base, h0, w0; bool ok; };
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int col) const {
+        ks.k = k_begin + col * 8;
+        uint32_t r, rem, s, ch;
+        g.d_scin.divmod(ks.k, r, rem);
+        g.d_cin.divmod(rem, s, ch);
+        ks.r = (int)r; ks.s = (int)s; ks.ch = (int)ch;
+        ks.koff = mul24(mul24(ks.r, g.W) + ks.s, g.Cin) + ks.ch;
+    }
+    __device__ __forceinline__ void init(Ctx& c, int m, int, int) const {
         c.ok = m < rows;
         uint32_t n, rem, ho, wo;
         g.d_howo.divmod(c.ok ? m : 0, n, rem);
         g.d_wo.divmod(rem, ho, wo);
         c.h0 = (int)ho * g.stride - g.pad;
         c.w0 = (int)wo * g.stride - g.pad;
-        c.base = (((int64_t)n * g.H + c.h0) * g.W + c.w0) * g.Cin;
-        c.koff = kc * 8;
+        c.base = (((int)n * g.H + c.h0) * g.W + c.w0) * g.Cin;
     }
-    __device__ __forceinline__ uint4 load(const Ctx& c, int kb, int k_end) const {
-        int k = kb + c.koff;
-        if (!c.ok || k + 8 > k_end) return make_uint4(0, 0, 0, 0);
-        uint32_t r, rem, s, ch;
-        g.d_scin.divmod(k, r, rem);
-        g.d_cin.divmod(rem, s, ch);
-        int h = c.h0 + (int)r, w = c.w0 + (int)s;
-        if ((unsigned)h >= (unsigned)g.H || (unsigned)w >= (unsigned)g.W) return make_uint4(0, 0, 0, 0);
-        return *reinterpret_cast<const uint4*>(x + c.base + ((int64_t)r * g.W + s) * g.Cin + ch);
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        const int h = c.h0 + ks.r, w = c.w0 + ks.s;
+        const bool ok = c.ok && ks.k + 8 <= k_end && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+        return ld16_if(x, c.base + ks.koff, ok);
+    }
+    __device__ __forceinline__ void next(KS& ks) const {
+        ks.k += kBK2;
+        ks.ch += kBK2;
+        while (ks.ch >= g.Cin) {
+            ks.ch -= g.Cin;
+            if (++ks.s == g.S) { ks.s = 0; ++ks.r; }
+        }
+        ks.koff = mul24(mul24(ks.r, g.W) + ks.s, g.Cin) + ks.ch;
     }
 };
 
@@ -125,64 +164,106 @@ struct ConvDgradA2 {
     const bf16_t* dy;
     ConvGeom2 g;
     int rows, K;
-    struct Ctx { int n, hp, wp, koff; bool ok; };
-    __device__ __forceinline__ void init(Ctx& c, int m, int kc) const {
+    struct KS { int k, r, s, co, kterm; };
+    struct Ctx { int c0, hp, wp, nbase; bool ok; };
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int col) const {
+        ks.k = k_begin + col * 8;
+        uint32_t r, rem, s, co;
+        g.d_scout.divmod(ks.k, r, rem);
+        g.d_cout.divmod(rem, s, co);
+        ks.r = (int)r; ks.s = (int)s; ks.co = (int)co;
+        ks.kterm = ks.co - mul24(mul24(ks.r, g.Wo) + ks.s, g.Cout);
+    }
+    __device__ __forceinline__ void init(Ctx& c, int m, int, int) const {
         c.ok = m < rows;
         uint32_t n, rem, h, w;
         g.d_hw.divmod(c.ok ? m : 0, n, rem);
         g.d_w.divmod(rem, h, w);
-        c.n = (int)n;
         c.hp = (int)h + g.pad;
         c.wp = (int)w + g.pad;
-        c.koff = kc * 8;
+        c.nbase = (int)n * g.Ho * g.Wo * g.Cout;
+        c.c0 = c.nbase + (c.hp * g.Wo + c.wp) * g.Cout;  // stride 1: offset = c0 + kterm
     }
-    __device__ __forceinline__ uint4 load(const Ctx& c, int kb, int k_end) const {
-        int k = kb + c.koff;
-        if (!c.ok || k + 8 > k_end) return make_uint4(0, 0, 0, 0);
-        uint32_t r, rem, s, co;
-        g.d_scout.divmod(k, r, rem);
-        g.d_cout.divmod(rem, s, co);
-        int hy = c.hp - (int)r, wy = c.wp - (int)s;
-        if (hy < 0 || wy < 0) return make_uint4(0, 0, 0, 0);
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        const bool in_k = c.ok && ks.k + 8 <= k_end;
+        const int hy = c.hp - ks.r, wy = c.wp - ks.s;
+        if (g.stride == 1) {
+            const bool ok = in_k && (unsigned)hy < (unsigned)g.Ho && (unsigned)wy < (unsigned)g.Wo;
+            return ld16_if(dy, c.c0 + ks.kterm, ok);
+        }
         uint32_t ho, hr, wo, wr;
-        g.d_stride.divmod(hy, ho, hr);
-        g.d_stride.divmod(wy, wo, wr);
-        if (hr != 0 || wr != 0 || (int)ho >= g.Ho || (int)wo >= g.Wo) return make_uint4(0, 0, 0, 0);
-        return *reinterpret_cast<const uint4*>(dy + (((int64_t)c.n * g.Ho + ho) * g.Wo + wo) * g.Cout + co);
+        g.d_stride.divmod(hy < 0 ? 0 : hy, ho, hr);
+        g.d_stride.divmod(wy < 0 ? 0 : wy, wo, wr);
+        const bool ok = in_k && hy >= 0 && wy >= 0 && hr == 0 && wr == 0 && (int)ho < g.Ho && (int)wo < g.Wo;
+        return ld16_if(dy, c.nbase + ((int)ho * g.Wo + (int)wo) * g.Cout + ks.co, ok);
+    }
+    __device__ __forceinline__ void next(KS& ks) const {
+        ks.k += kBK2;
+        ks.co += kBK2;
+        while (ks.co >= g.Cout) {
+            ks.co -= g.Cout;
+            if (++ks.s == g.S) { ks.s = 0; ++ks.r; }
+        }
+        ks.kterm = ks.co - mul24(mul24(ks.r, g.Wo) + ks.s, g.Cout);
     }
 };
 
 // Input-gradient B: row n = ci (8 consecutive), k = (r, s, co) -> w[co, r, s, ci].
+// Per thread: (r, s, co) of the tile's first k; a chunk adds its k offset (with carry when the tile
+// crosses a filter tap).
 struct ConvDgradB2 {
     static constexpr bool kContig = false;
     const bf16_t* w;
     ConvGeom2 g;
     int rows, K;
+    struct KS { int kb, r, s, co; };
     struct Ctx { int ci0, kl; bool ok; };
-    __device__ __forceinline__ void init(Ctx& c, int row0, int kl) const {
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int) const {
+        ks.kb = k_begin;
+        uint32_t r, rem, s, co;
+        g.d_scout.divmod(k_begin, r, rem);
+        g.d_cout.divmod(rem, s, co);
+        ks.r = (int)r; ks.s = (int)s; ks.co = (int)co;
+    }
+    __device__ __forceinline__ void init(Ctx& c, int row0, int kl, int) const {
         c.ok = row0 + 8 <= rows;
         c.ci0 = row0;
         c.kl = kl;
     }
-    __device__ __forceinline__ uint4 load(const Ctx& c, int kb, int k_end) const {
-        int k = kb + c.kl;
-        if (!c.ok || k >= k_end) return make_uint4(0, 0, 0, 0);
-        uint32_t r, rem, s, co;
-        g.d_scout.divmod(k, r, rem);
-        g.d_cout.divmod(rem, s, co);
-        return *reinterpret_cast<const uint4*>(w + ((((int64_t)co * g.R + r) * g.S + s) * g.Cin + c.ci0));
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        const bool ok = c.ok && ks.kb + c.kl < k_end;
+        int co = ks.co + c.kl, s = ks.s, r = ks.r;
+        while (co >= g.Cout) {
+            co -= g.Cout;
+            if (++s == g.S) { s = 0; ++r; }
+        }
+        const int off = mul24(mul24(mul24(co, g.R) + r, g.S) + s, g.Cin) + c.ci0;
+        return ld16_if(w, off, ok);
+    }
+    __device__ __forceinline__ void next(KS& ks) const {
+        ks.kb += kBK2;
+        ks.co += kBK2;
+        while (ks.co >= g.Cout) {
+            ks.co -= g.Cout;
+            if (++ks.s == g.S) { ks.s = 0; ++ks.r; }
+        }
     }
 };
 
 // Weight-gradient B: row = (r, s, ci) (8 consecutive ci), k = m = (n, ho, wo)
 // -> x[n, ho*stride + r - pad, wo*stride + s - pad, ci].
+// Per chunk: (ho, wo) of its position and the element offset of that position, stepped by 64
+// positions per tile with precomputed carries.
 struct ConvWgradB2 {
     static constexpr bool kContig = false;
     const bf16_t* x;
     ConvGeom2 g;
     int rows, K;
-    struct Ctx { int dr, ds, ci0, kl; bool ok; };
-    __device__ __forceinline__ void init(Ctx& c, int row0, int kl) const {
+    int step_wo, step_ho, step_n;  // 64 positions = step_n images + step_ho rows + step_wo columns
+    struct KS { int kb; };
+    struct Ctx { int dr, ds, ci0, kl, ho, wo, n; bool ok; };
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int) const { ks.kb = k_begin; }
+    __device__ __forceinline__ void init(Ctx& c, int row0, int kl, int k_begin) const {
         c.ok = row0 + 8 <= rows;
         uint32_t r, rem, s, ci;
         g.d_scin.divmod(c.ok ? row0 : 0, r, rem);
@@ -191,17 +272,24 @@ struct ConvWgradB2 {
         c.ds = (int)s - g.pad;
         c.ci0 = (int)ci;
         c.kl = kl;
+        uint32_t n, rem2, ho, wo;
+        g.d_howo.divmod(k_begin + kl, n, rem2);
+        g.d_wo.divmod(rem2, ho, wo);
+        c.n = (int)n; c.ho = (int)ho; c.wo = (int)wo;
     }
-    __device__ __forceinline__ uint4 load(const Ctx& c, int kb, int k_end) const {
-        int m = kb + c.kl;
-        if (!c.ok || m >= k_end) return make_uint4(0, 0, 0, 0);
-        uint32_t n, rem, ho, wo;
-        g.d_howo.divmod(m, n, rem);
-        g.d_wo.divmod(rem, ho, wo);
-        int h = (int)ho * g.stride + c.dr, w = (int)wo * g.stride + c.ds;
-        if ((unsigned)h >= (unsigned)g.H || (unsigned)w >= (unsigned)g.W) return make_uint4(0, 0, 0, 0);
-        return *reinterpret_cast<const uint4*>(x + (((int64_t)n * g.H + h) * g.W + w) * g.Cin + c.ci0);
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        const int h = c.ho * g.stride + c.dr, w = c.wo * g.stride + c.ds;
+        const bool ok = c.ok && ks.kb + c.kl < k_end && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+        uint4 v = ld16_if(x, mul24(mul24(mul24(c.n, g.H) + h, g.W) + w, g.Cin) + c.ci0, ok);
+        // advance this chunk's position by 64
+        c.wo += step_wo;
+        c.ho += step_ho;
+        c.n += step_n;
+        if (c.wo >= g.Wo) { c.wo -= g.Wo; ++c.ho; }
+        if (c.ho >= g.Ho) { c.ho -= g.Ho; ++c.n; }
+        return v;
     }
+    __device__ __forceinline__ void next(KS& ks) const { ks.kb += kBK2; }
 };
 
 // ------------------------------------------------------------------------------------------
@@ -219,6 +307,8 @@ template <int ROWS, bool KC> __device__ __forceinline__ bf16x8_t read_frag(const
         const bf16_t* p = tile + (row_base + (lane & 31)) * TileShape<ROWS, true>::pitch + kk * 16 + (lane >> 5) * 8;
         return *reinterpret_cast<const bf16x8_t*>(p);
     } else {
+        // Transpose read: within 16 lanes, lane j supplies the address of 4 consecutive rows at
+        // k = k0 + j/4, rows c0 + 4*(j%4); lane i receives k0..k0+3 of row c0 + i.
         constexpr int pitch = TileShape<ROWS, false>::pitch;
         const int k = kk * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
         const int col = row_base + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
@@ -234,13 +324,21 @@ template <int ROWS, bool KC> __device__ __forceinline__ bf16x8_t read_frag(const
     }
 }
 
-template <int BM, int BN, bool ROWSUM, class AOp, class BOp, class Epi>
+// LDS bytes of one launch: two buffers of an A tile and a B tile.
+template <int BM, int BN, class AOp, class BOp> constexpr int gemm2_lds_bytes() {
+    return 2 * (TileShape<BM, AOp::kContig>::elems + TileShape<BN, BOp::kContig>::elems) * (int)sizeof(bf16_t);
+}
+
+// D = number of k-tiles whose global loads are in flight per thread (register ring).
+template <int BM, int BN, int D, bool ROWSUM, class AOp, class BOp, class Epi>
 __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M, int N, int K, int k_per_slice) {
     constexpr bool AKC = AOp::kContig, BKC = BOp::kContig;
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int A_CH = BM * (kBK2 / 8) / 256, B_CH = BN * (kBK2 / 8) / 256;
-    __shared__ __attribute__((aligned(16))) bf16_t sA[TileShape<BM, AKC>::elems];
-    __shared__ __attribute__((aligned(16))) bf16_t sB[TileShape<BN, BKC>::elems];
+    constexpr int A_ELEMS = TileShape<BM, AKC>::elems, B_ELEMS = TileShape<BN, BKC>::elems;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t* const sA = reinterpret_cast<bf16_t*>(smem_raw);  // [2][A_ELEMS]
+    bf16_t* const sB = sA + 2 * A_ELEMS;                      // [2][B_ELEMS]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -249,19 +347,23 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
     const int k_end = min(K, k_begin + k_per_slice);
     const int nk = (k_end - k_begin + kBK2 - 1) / kBK2;
 
+    typename AOp::KS ksa;
+    typename BOp::KS ksb;
     typename AOp::Ctx ca[A_CH];
     typename BOp::Ctx cb[B_CH];
     int sa_off[A_CH], sb_off[B_CH];
+    A.init_thread(ksa, k_begin, tid & 7);
+    B.init_thread(ksb, k_begin, tid & 7);
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
         int c = tid + i * 256;
         if constexpr (AKC) {
             int row = c >> 3, kc = c & 7;
-            A.init(ca[i], m0 + row, kc);
+            A.init(ca[i], m0 + row, kc, k_begin);
             sa_off[i] = row * TileShape<BM, true>::pitch + kc * 8;
         } else {
             int rc = c % (BM / 8), kl = c / (BM / 8);
-            A.init(ca[i], m0 + rc * 8, kl);
+            A.init(ca[i], m0 + rc * 8, kl, k_begin);
             sa_off[i] = kl * TileShape<BM, false>::pitch + rc * 8;
         }
     }
@@ -270,11 +372,11 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
         int c = tid + i * 256;
         if constexpr (BKC) {
             int row = c >> 3, kc = c & 7;
-            B.init(cb[i], n0 + row, kc);
+            B.init(cb[i], n0 + row, kc, k_begin);
             sb_off[i] = row * TileShape<BN, true>::pitch + kc * 8;
         } else {
             int rc = c % (BN / 8), kl = c / (BN / 8);
-            B.init(cb[i], n0 + rc * 8, kl);
+            B.init(cb[i], n0 + rc * 8, kl, k_begin);
             sb_off[i] = kl * TileShape<BN, false>::pitch + rc * 8;
         }
     }
@@ -288,34 +390,42 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     float rsum = 0.0f;
 
-    uint4 ra[A_CH], rb[B_CH];
-    if (nk > 0) {
+    // Register ring: tile t is fetched into slot t % D.
+    uint4 ra[D][A_CH], rb[D][B_CH];
+    auto fetch = [&](uint4 (&a)[A_CH], uint4 (&b)[B_CH]) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[i] = A.load(ca[i], k_begin, k_end);
+        for (int i = 0; i < A_CH; ++i) a[i] = A.load(ca[i], ksa, k_end);
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) rb[i] = B.load(cb[i], k_begin, k_end);
-    }
-    for (int kt = 0; kt < nk; ++kt) {
-        __syncthreads();  // everyone is done reading the previous tile
+        for (int i = 0; i < B_CH; ++i) b[i] = B.load(cb[i], ksb, k_end);
+        A.next(ksa);
+        B.next(ksb);
+    };
+    auto stash = [&](const uint4 (&a)[A_CH], const uint4 (&b)[B_CH], int buf) {
+        bf16_t* da = sA + buf * A_ELEMS;
+        bf16_t* db = sB + buf * B_ELEMS;
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(&sA[sa_off[i]]) = ra[i];
+        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(da + sa_off[i]) = a[i];
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(&sB[sb_off[i]]) = rb[i];
-        __syncthreads();
-        if (kt + 1 < nk) {
-            const int kb = k_begin + (kt + 1) * kBK2;
+        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(db + sb_off[i]) = b[i];
+    };
+    // Fetches beyond the slice return zeros (the loaders clamp), so the ring is always kept full and the
+    // steady-state loop has no branch around a load or a store.
 #pragma unroll
-            for (int i = 0; i < A_CH; ++i) ra[i] = A.load(ca[i], kb, k_end);
-#pragma unroll
-            for (int i = 0; i < B_CH; ++i) rb[i] = B.load(cb[i], kb, k_end);
-        }
+    for (int d = 0; d < D; ++d) fetch(ra[d], rb[d]);
+    stash(ra[0], rb[0], 0);
+    fetch(ra[0], rb[0]);
+    __syncthreads();
+
+    auto multiply = [&](int buf) {
+        const bf16_t* tA = sA + buf * A_ELEMS;
+        const bf16_t* tB = sB + buf * B_ELEMS;
 #pragma unroll
         for (int kk = 0; kk < kBK2 / 16; ++kk) {
             bf16x8_t af[TM], bfr[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = read_frag<BM, AKC>(sA, wm * (BM / 2) + i * 32, kk, lane);
+            for (int i = 0; i < TM; ++i) af[i] = read_frag<BM, AKC>(tA, wm * (BM / 2) + i * 32, kk, lane);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = read_frag<BN, BKC>(sB, wn * (BN / 2) + j * 32, kk, lane);
+            for (int j = 0; j < TN; ++j) bfr[j] = read_frag<BN, BKC>(tB, wn * (BN / 2) + j * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -324,29 +434,67 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
         }
         if (ROWSUM && blockIdx.x == 0 && tid < BM) {
             if constexpr (AKC) {
-                const bf16_t* rowp = &sA[tid * TileShape<BM, true>::pitch];
+                const bf16_t* rowp = tA + tid * TileShape<BM, true>::pitch;
 #pragma unroll 8
                 for (int e = 0; e < kBK2; ++e) rsum += (float)rowp[e];
             } else {
 #pragma unroll 8
-                for (int e = 0; e < kBK2; ++e) rsum += (float)sA[e * TileShape<BM, false>::pitch + tid];
+                for (int e = 0; e < kBK2; ++e) rsum += (float)tA[e * TileShape<BM, false>::pitch + tid];
             }
+        }
+    };
+
+    // Rounds of D tiles; the last round may multiply up to D-1 all-zero tiles.
+    const int rounds = (nk + D - 1) / D;
+    for (int round = 0; round < rounds; ++round) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int kt = round * D + d;
+            const int dn = (d + 1) % D;  // compile-time after unrolling
+            // LDS buffer (kt+1)&1 was last read in iteration kt-1, which ended with a barrier
+            stash(ra[dn], rb[dn], (kt + 1) & 1);
+            fetch(ra[dn], rb[dn]);
+            multiply(kt & 1);
+            __syncthreads();
         }
     }
 
+    // Accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register r holds
+    // row 8*(r/4) + 4*(lane/32) + r%4.  Output offsets advance by additions only.
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+    const int64_t ld = epi.ld;
+    if (m0 + BM <= M && n0 + BN <= N) {
+        // Interior block: no bounds tests, hence no branch between the stores (a branch makes the
+        // compiler wait for every earlier store before the next one).
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int n = n0 + wn * (BN / 2) + j * 32 + col_in;
-            if (n >= N) continue;
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + col_in;
+                const int mb = m0 + wm * (BM / 2) + i * 32 + row_in;
+                const int64_t idx = (int64_t)mb * ld + n;
+                const auto col = epi.column(n);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int m = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + row_in + (r & 3);
-                if (m < M) epi(m, n, acc[i][j][r], z);
+                for (int r = 0; r < 16; ++r)
+                    epi.at(col, idx + (int64_t)(8 * (r >> 2) + (r & 3)) * ld, acc[i][j][r], z);
             }
-        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + col_in;
+                if (n >= N) continue;
+                const int mb = m0 + wm * (BM / 2) + i * 32 + row_in;
+                const int64_t idx = (int64_t)mb * ld + n;
+                const auto col = epi.column(n);  // whatever depends on the column only (bias), fetched once
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = mb + 8 * (r >> 2) + (r & 3);
+                    if (m < M) epi.at(col, idx + (int64_t)(8 * (r >> 2) + (r & 3)) * ld, acc[i][j][r], z);
+                }
+            }
+    }
     if (ROWSUM && blockIdx.x == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
 }
 
@@ -354,8 +502,9 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
 struct EpiPartial {
     float* part;
     int64_t ld, slice_stride;
-    __device__ __forceinline__ void operator()(int m, int n, float v, int z) const {
-        part[z * slice_stride + (int64_t)m * ld + n] = v;
+    __device__ __forceinline__ int column(int) const { return 0; }
+    __device__ __forceinline__ void at(int, int64_t idx, float v, int z) const {
+        part[z * slice_stride + idx] = v;
     }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
@@ -366,10 +515,17 @@ __global__ void splitk_finish_kernel(const float* __restrict__ part, Epi epi, in
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = (int64_t)M * N;
     if (i >= total) return;
-    float a = 0.0f;
-    for (int z = 0; z < slices; ++z) a += part[z * total + i];
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    int z = 0;
+    for (; z + 4 <= slices; z += 4) {
+        a0 += part[(z + 0) * total + i];
+        a1 += part[(z + 1) * total + i];
+        a2 += part[(z + 2) * total + i];
+        a3 += part[(z + 3) * total + i];
+    }
+    for (; z < slices; ++z) a0 += part[z * total + i];
     int m = (int)(i / N), n = (int)(i - (int64_t)m * N);
-    epi(m, n, a, 0);
+    epi.at(epi.column(n), (int64_t)m * epi.ld + n, (a0 + a1) + (a2 + a3), 0);
 }
 
 }  // namespace tmps

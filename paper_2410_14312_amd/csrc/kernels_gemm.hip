@@ -22,7 +22,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const bool wide = N > 64 && M > 64;
     p.tile = (wide && t128 >= 64) ? 128 : 64;
     const int64_t tiles = p.tile == 128 ? t128 : t64;
-    const int64_t target = 384;
+    const int64_t target = 384;  // swept 32..2048 on the VGG workload: flat optimum around 384-512
     int64_t s = 1;
     if (tiles < target) {
         s = (target + tiles - 1) / tiles;
@@ -61,19 +61,27 @@ static void slice_geometry(int64_t K, int want, int ktile, int& per, int& nz) {
 }
 
 // ---- MFMA path --------------------------------------------------------------------------------
+template <int BM, int BN, int D, bool ROWSUM, class AOp, class BOp, class Epi>
+static hipError_t launch2_inst(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per, int nz,
+                               hipStream_t s) {
+    constexpr int lds = gemm2_lds_bytes<BM, BN, AOp, BOp>();
+    auto kern = gemm2_kernel<BM, BN, D, ROWSUM, AOp, BOp, Epi>;
+    if (lds > 64 * 1024) {
+        // more LDS than the default per-workgroup limit: raise it once per kernel instance
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (attr != hipSuccess) return attr;
+    }
+    dim3 grid(cdiv(N, BN), cdiv(M, BM), nz);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per);
+    return hipGetLastError();
+}
+
 template <bool ROWSUM, class AOp, class BOp, class Epi>
 static hipError_t launch2_tile(int tile, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
                                int nz, hipStream_t s) {
-    if (tile == 128) {
-        dim3 grid(cdiv(N, 128), cdiv(M, 128), nz);
-        hipLaunchKernelGGL((gemm2_kernel<128, 128, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N,
-                           K, per);
-    } else {
-        dim3 grid(cdiv(N, 64), cdiv(M, 64), nz);
-        hipLaunchKernelGGL((gemm2_kernel<64, 64, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K,
-                           per);
-    }
-    return hipGetLastError();
+    if (tile == 128) return launch2_inst<128, 128, 2, ROWSUM>(A, B, epi, M, N, K, per, nz, s);
+    return launch2_inst<64, 64, 4, ROWSUM>(A, B, epi, M, N, K, per, nz, s);
 }
 
 // Forward / input-gradient style GEMM: epilogue `epi` applied once per output element.
@@ -217,6 +225,14 @@ static ConvGeom geom(const ConvShape& c) {
     return ConvGeom{c.B, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.stride, c.pad};
 }
 
+// The MFMA loaders index positions with 24-bit multiplies and tensors with 32-bit element offsets.
+static bool small_enough(const ConvShape& c) {
+    const int64_t pin = (int64_t)c.B * c.H * c.W, pout = (int64_t)c.B * c.Ho * c.Wo;
+    const int64_t wel = (int64_t)c.Cout * c.R * c.S * c.Cin;
+    return pin < (1 << 24) && pout < (1 << 24) && pin * c.Cin < (int64_t(1) << 31) &&
+           pout * c.Cout < (int64_t(1) << 31) && wel < (int64_t(1) << 31) && c.Cin < (1 << 20) && c.Cout < (1 << 20);
+}
+
 static ConvGeom2 geom2(const ConvShape& c) {
     ConvGeom2 g;
     g.B = c.B; g.H = c.H; g.W = c.W; g.Cin = c.Cin; g.Ho = c.Ho; g.Wo = c.Wo; g.Cout = c.Cout;
@@ -234,7 +250,7 @@ hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bi
     int M = c.B * c.Ho * c.Wo, K = c.R * c.S * c.Cin;
     if (dtype == kBF16) {
         EpiBiasAct<bf16_t> epi{(bf16_t*)y, bias, c.Cout, relu};
-        if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w)) {
+        if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w) && small_enough(c)) {
             ConvFwdA2 A{(const bf16_t*)x, geom2(c), M, K};
             DenseKC Bv{(const bf16_t*)w, c.Cout, K, K};
             return run2(A, Bv, epi, M, c.Cout, K, ws, s);
@@ -253,7 +269,7 @@ hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const 
     int M = c.B * c.H * c.W, K = c.R * c.S * c.Cout;
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, c.Cin};
-        if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w)) {
+        if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w) && small_enough(c)) {
             ConvDgradA2 A{(const bf16_t*)dy, geom2(c), M, K};
             ConvDgradB2 Bv{(const bf16_t*)w, geom2(c), c.Cin, K};
             return run2(A, Bv, epi, M, c.Cin, K, ws, s);
@@ -272,9 +288,10 @@ hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const
     int rows = c.Cout, cols = c.R * c.S * c.Cin;
     int64_t K = (int64_t)c.B * c.Ho * c.Wo;
     if (dtype == kBF16) {
-        if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(x)) {
+        if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(x) && small_enough(c)) {
             DenseRC A{(const bf16_t*)dy, rows, (int)K, c.Cout};
-            ConvWgradB2 Bv{(const bf16_t*)x, geom2(c), cols, (int)K};
+            const int rows64 = kBK2 / c.Wo;
+            ConvWgradB2 Bv{(const bf16_t*)x, geom2(c), cols, (int)K, kBK2 % c.Wo, rows64 % c.Ho, rows64 / c.Ho};
             return run2_wgrad(A, Bv, gw, rows, cols, K, ws, s);
         }
         DenseView<bf16_t, false> A{(const bf16_t*)dy, rows, (int)K, c.Cout, 0};
