@@ -71,6 +71,25 @@ def algorithmic_work(cfg):
     return work
 
 
+# classes whose kernels carry their own start/stop timestamps (no bracket overhead)
+KERNEL_STAMPED = ("dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "splitk_finish",
+                  "slice_sum")
+
+
+def measured_traffic(workload, kernel_class):
+    """HBM bytes per launch of a kernel class from the committed counter summary
+    profiles/hbm_traffic_<workload>.txt (lines `<class> <fetch bytes/launch> <write bytes/launch>`,
+    already scaled by the copy-kernel factor), or None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 3 and f[0] == kernel_class:
+            return float(f[1]) + float(f[2])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +98,8 @@ def main():
     ap.add_argument("--workload", default="vgg16_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="mini-batches the oracle is timed on (0: about 15 s worth)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy kernel (reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the stage-training path on ONE GPU (K stages on K streams of the same "
@@ -93,6 +114,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     cfg = get_config(args.workload)
     params = init_params(cfg)
     pipe = T.Pipeline(cfg, params)
@@ -125,10 +152,15 @@ def main():
     T.profile_enable(False)
     work = algorithmic_work(cfg)
     kernels = []
+    # what an empty pair of timing events measures on these streams; subtracted from every bracket
+    pair_ms, pair_cnt = prof.pop("event_pair", (0.0, 0))
+    pair_us = 1e3 * pair_ms / pair_cnt if pair_cnt else 0.0
     for k, (ms, cnt) in prof.items():
         if cnt == 0:
             continue
         per = work.get(k)
+        if k not in KERNEL_STAMPED:      # bracketed classes also contain the cost of the event pair
+            ms = max(ms - cnt * pair_us / 1e3, 0.05 * ms)
         ent = {"class": k, "launches_per_step": cnt / args.steps, "avg_us": 1e3 * ms / cnt, "ms_per_step": ms / args.steps}
         if per and per[0]:
             ent["gflop_per_launch"] = per[1] / per[0] / 1e9
@@ -148,6 +180,8 @@ def main():
                 "frac": dom.get("tflops", 0.0) / (MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3),
                 "traffic": None}
     roof["avg_launch_us"] = dom["avg_us"]
+    roof["event_pair_us_subtracted"] = pair_us
+    roof["traffic"] = measured_traffic(cfg.name, dom["class"])
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -182,17 +182,21 @@ int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, cons
 
 /* ---- measurement aid (not part of the method) ----
  *
- * While enabled, every kernel launch made by the calls above is bracketed by two timing events
- * recorded on the stream it is launched on.  tmps_profile_read() waits for the recorded events,
- * adds the elapsed milliseconds and launch counts per kernel class into total_ms[] / launches[]
- * (host arrays of n_classes >= TMPS_KERNEL_CLASSES entries), clears the record and returns
- * TMPS_KERNEL_CLASSES.  A weight-gradient launch that splits its contraction counts the GEMM and
- * its slice reduction as one launch.  The event pairs serialise nothing but add host overhead:
- * time throughput with profiling off. */
+ * While enabled, every kernel launch made by the calls above is timed with HIP events on the stream
+ * it is launched on.  The contraction kernels (the six *_FWD / *_DGRAD / *_WGRAD classes) and the
+ * reductions of their k-split (TMPS_KC_SPLIT_FINISH, TMPS_KC_SLICE_SUM) are launched with a start and
+ * a stop event of their own, which the runtime stamps with the start and end of that kernel's
+ * execution.  The other classes are bracketed by two events recorded around the launch, which also
+ * measures dispatch latency; TMPS_KC_EVENT_PAIR is an empty bracket recorded before every update, the
+ * cost of such a pair by itself.  tmps_profile_read() waits for the recorded events, adds the elapsed
+ * milliseconds and launch counts per class into total_ms[] / launches[] (host arrays of n_classes >=
+ * TMPS_KERNEL_CLASSES entries), clears the record and returns TMPS_KERNEL_CLASSES.  Timing adds host
+ * overhead: measure throughput with profiling off. */
 enum {
     TMPS_KC_DENSE_FWD = 0, TMPS_KC_DENSE_DGRAD, TMPS_KC_DENSE_WGRAD, TMPS_KC_CONV_FWD,
     TMPS_KC_CONV_DGRAD, TMPS_KC_CONV_WGRAD, TMPS_KC_SOFTMAX_CE, TMPS_KC_UPDATE, TMPS_KC_POOL_FWD,
-    TMPS_KC_POOL_BWD, TMPS_KC_RELU_MASK, TMPS_KC_REDUCE, TMPS_KC_COPY, TMPS_KERNEL_CLASSES
+    TMPS_KC_POOL_BWD, TMPS_KC_RELU_MASK, TMPS_KC_REDUCE, TMPS_KC_COPY, TMPS_KC_EVENT_PAIR,
+    TMPS_KC_SPLIT_FINISH, TMPS_KC_SLICE_SUM, TMPS_KERNEL_CLASSES
 };
 int tmps_profile_enable(int on);
 int tmps_profile_read(double* total_ms, int64_t* launches, int n_classes);

@@ -104,7 +104,7 @@ def version_diff_simulated(W, N):
 
 
 KERNEL_CLASSES = ["dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "softmax_ce",
-                  "update", "pool_fwd", "pool_bwd", "relu_mask", "reduce", "copy"]
+                  "update", "pool_fwd", "pool_bwd", "relu_mask", "reduce", "copy", "event_pair", "splitk_finish", "slice_sum"]
 
 
 def profile_enable(on):

@@ -3,8 +3,11 @@
 // with aligned 16-byte loads (channel / feature counts that are multiples of 8), and the
 // element-wise skeleton of gemm.hip.h otherwise (3-channel input layer, 10-way logits layer);
 // fp32 stages use the fp32 skeleton.
+#include <hip/hip_ext.h>
+
 #include "gemm2.hip.h"
 #include "kernels.h"
+#include "profile.h"
 
 namespace tmps {
 
@@ -52,6 +55,19 @@ __global__ void slice_sum_kernel(const float* __restrict__ part, float* __restri
     out[i] = a;
 }
 
+// Launch; while profiling is enabled the kernel is stamped with its own start/stop timestamps.
+template <class Kern, class... Args>
+static hipError_t launch_timed(int kc, Kern kern, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
+    KernelEvents ev;
+    if (profile_kernel_begin(ev)) {
+        hipExtLaunchKernelGGL(kern, grid, block, lds, s, ev.start, ev.stop, 0, args...);
+        profile_kernel_end(kc, ev);
+    } else {
+        hipLaunchKernelGGL(kern, grid, block, lds, s, args...);
+    }
+    return hipGetLastError();
+}
+
 // slice length (whole k-tiles) and the number of slices really launched
 static void slice_geometry(int64_t K, int want, int ktile, int& per, int& nz) {
     if (want < 1) want = 1;
@@ -62,8 +78,8 @@ static void slice_geometry(int64_t K, int want, int ktile, int& per, int& nz) {
 
 // ---- MFMA path --------------------------------------------------------------------------------
 template <int BM, int BN, int D, bool ROWSUM, class AOp, class BOp, class Epi>
-static hipError_t launch2_inst(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per, int nz,
-                               hipStream_t s) {
+static hipError_t launch2_inst(int kc, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
+                               int nz, hipStream_t s) {
     constexpr int lds = gemm2_lds_bytes<BM, BN, AOp, BOp>();
     auto kern = gemm2_kernel<BM, BN, D, ROWSUM, AOp, BOp, Epi>;
     if (lds > 64 * 1024) {
@@ -73,47 +89,46 @@ static hipError_t launch2_inst(const AOp& A, const BOp& B, const Epi& epi, int M
         if (attr != hipSuccess) return attr;
     }
     dim3 grid(cdiv(N, BN), cdiv(M, BM), nz);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per);
-    return hipGetLastError();
+    return launch_timed(kc, kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per);
 }
 
 template <bool ROWSUM, class AOp, class BOp, class Epi>
-static hipError_t launch2_tile(int tile, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
-                               int nz, hipStream_t s) {
-    if (tile == 128) return launch2_inst<128, 128, 2, ROWSUM>(A, B, epi, M, N, K, per, nz, s);
-    return launch2_inst<64, 64, 4, ROWSUM>(A, B, epi, M, N, K, per, nz, s);
+static hipError_t launch2_tile(int kc, int tile, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K,
+                               int per, int nz, hipStream_t s) {
+    if (tile == 128) return launch2_inst<128, 128, 2, ROWSUM>(kc, A, B, epi, M, N, K, per, nz, s);
+    return launch2_inst<64, 64, 4, ROWSUM>(kc, A, B, epi, M, N, K, per, nz, s);
 }
 
 // Forward / input-gradient style GEMM: epilogue `epi` applied once per output element.
 template <class AOp, class BOp, class Epi>
-static hipError_t run2(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, float* ws,
+static hipError_t run2(int kc, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, float* ws,
                        hipStream_t s) {
     if (M <= 0 || N <= 0) return hipSuccess;
     GemmPlan p = plan_gemm(M, N, K);
     int per, nz;
     slice_geometry(K, ws ? p.slices : 1, kBK2, per, nz);
-    if (nz <= 1) return launch2_tile<false>(p.tile, A, B, epi, M, N, K, per, nz, s);
+    if (nz <= 1) return launch2_tile<false>(kc, p.tile, A, B, epi, M, N, K, per, nz, s);
     EpiPartial part{ws, N, (int64_t)M * N};
-    hipError_t e = launch2_tile<false>(p.tile, A, B, part, M, N, K, per, nz, s);
+    hipError_t e = launch2_tile<false>(kc, p.tile, A, B, part, M, N, K, per, nz, s);
     if (e != hipSuccess) return e;
     int64_t total = (int64_t)M * N;
-    hipLaunchKernelGGL((splitk_finish_kernel<Epi>), dim3(cdiv(total, 256)), dim3(256), 0, s, ws, epi, M, N, nz);
-    return hipGetLastError();
+    return launch_timed(kcSplitFinish, splitk_finish_kernel<Epi>, dim3(cdiv(total, 256)), dim3(256), 0, s,
+                        (const float*)ws, epi, M, N, nz);
 }
 
 // Weight-gradient style GEMM: fp32 result [rows x cols] followed by the row sums of A (bias gradient).
 template <class AOp, class BOp>
-static hipError_t run2_wgrad(const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K, float* ws,
-                             hipStream_t s) {
+static hipError_t run2_wgrad(int kc, const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K,
+                             float* ws, hipStream_t s) {
     GemmPlan p = plan_gemm(rows, cols, K);
     int per, nz;
     slice_geometry(K, ws ? p.slices : 1, kBK2, per, nz);
     int64_t count = (int64_t)rows * cols + rows;
     EpiWgrad epi{nz > 1 ? ws : gw, cols, (int64_t)rows * cols, count};
-    hipError_t e = launch2_tile<true>(p.tile, A, B, epi, rows, cols, (int)K, per, nz, s);
+    hipError_t e = launch2_tile<true>(kc, p.tile, A, B, epi, rows, cols, (int)K, per, nz, s);
     if (e != hipSuccess || nz <= 1) return e;
-    hipLaunchKernelGGL(slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, ws, gw, count, nz);
-    return hipGetLastError();
+    return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw,
+                        count, nz);
 }
 
 static int one_slice(int64_t K, int ktile) {
@@ -123,26 +138,24 @@ static int one_slice(int64_t K, int ktile) {
 
 // ---- element-wise fallbacks ------------------------------------------------------------------
 template <bool ROWSUM, class AOp, class BOp, class Epi>
-static hipError_t launch_bf16(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per, int nz,
-                              hipStream_t s) {
+static hipError_t launch_bf16(int kc, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
+                              int nz, hipStream_t s) {
     if (M <= 0 || N <= 0) return hipSuccess;
     dim3 grid(cdiv(N, 64), cdiv(M, 64), nz);
-    hipLaunchKernelGGL((gemm_bf16_kernel<64, 64, ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K,
-                       per);
-    return hipGetLastError();
+    return launch_timed(kc, gemm_bf16_kernel<64, 64, ROWSUM, AOp, BOp, Epi>, grid, dim3(256), 0, s, A, B, epi, M, N,
+                        K, per);
 }
 
 template <bool ROWSUM, class AOp, class BOp, class Epi>
-static hipError_t launch_f32(const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per, int nz,
-                             hipStream_t s) {
+static hipError_t launch_f32(int kc, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
+                             int nz, hipStream_t s) {
     if (M <= 0 || N <= 0) return hipSuccess;
     dim3 grid(cdiv(N, 64), cdiv(M, 64), nz);
-    hipLaunchKernelGGL((gemm_f32_kernel<ROWSUM, AOp, BOp, Epi>), grid, dim3(256), 0, s, A, B, epi, M, N, K, per);
-    return hipGetLastError();
+    return launch_timed(kc, gemm_f32_kernel<ROWSUM, AOp, BOp, Epi>, grid, dim3(256), 0, s, A, B, epi, M, N, K, per);
 }
 
 template <typename T, class AOp, class BOp>
-static hipError_t wgrad_fallback(const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K, float* ws,
+static hipError_t wgrad_fallback(int kc, const AOp& A, const BOp& B, float* gw, int rows, int cols, int64_t K, float* ws,
                                  hipStream_t s) {
     GemmPlan p = plan_gemm(rows, cols, K);
     constexpr int ktile = sizeof(T) == 2 ? kBK : 16;
@@ -152,12 +165,12 @@ static hipError_t wgrad_fallback(const AOp& A, const BOp& B, float* gw, int rows
     EpiWgrad epi{nz > 1 ? ws : gw, cols, (int64_t)rows * cols, count};
     hipError_t e;
     if constexpr (sizeof(T) == 2)
-        e = launch_bf16<true>(A, B, epi, rows, cols, (int)K, per, nz, s);
+        e = launch_bf16<true>(kc, A, B, epi, rows, cols, (int)K, per, nz, s);
     else
-        e = launch_f32<true>(A, B, epi, rows, cols, (int)K, per, nz, s);
+        e = launch_f32<true>(kc, A, B, epi, rows, cols, (int)K, per, nz, s);
     if (e != hipSuccess || nz <= 1) return e;
-    hipLaunchKernelGGL(slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, ws, gw, count, nz);
-    return hipGetLastError();
+    return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw,
+                        count, nz);
 }
 
 // ---------------------------------------------------------------------------------------- dense
@@ -168,17 +181,17 @@ hipError_t dense_forward(int dtype, const void* x, const void* w, const float* b
         if (fast) {
             DenseKC A{(const bf16_t*)x, B, Din, Din};
             DenseKC Bv{(const bf16_t*)w, Dout, Din, Din};
-            if (out_f32) return run2(A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
-            return run2(A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
+            if (out_f32) return run2(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
+            return run2(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
         }
         DenseView<bf16_t, true> A{(const bf16_t*)x, B, Din, Din, 0};
         DenseView<bf16_t, true> Bv{(const bf16_t*)w, Dout, Din, Din, 0};
-        if (out_f32) return launch_bf16<false>(A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
-        return launch_bf16<false>(A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
+        if (out_f32) return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
+        return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)x, B, Din, Din, 0};
     DenseView<float, true> Bv{(const float*)w, Dout, Din, Din, 0};
-    return launch_f32<false>(A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, 16), 1, s);
+    return launch_f32<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, 16), 1, s);
 }
 
 hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int B, int Din,
@@ -190,15 +203,15 @@ hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const
         if (fast) {
             DenseKC A{(const bf16_t*)dy, B, Dout, Dout};
             DenseRC Bv{(const bf16_t*)w, Din, Dout, Din};
-            return run2(A, Bv, epi, B, Din, Dout, ws, s);
+            return run2(kcDenseDgrad, A, Bv, epi, B, Din, Dout, ws, s);
         }
         DenseView<bf16_t, true> A{(const bf16_t*)dy, B, Dout, Dout, 0};
         DenseView<bf16_t, false> Bv{(const bf16_t*)w, Din, Dout, Din, 0};
-        return launch_bf16<false>(A, Bv, epi, B, Din, Dout, one_slice(Dout, kBK), 1, s);
+        return launch_bf16<false>(kcDenseDgrad, A, Bv, epi, B, Din, Dout, one_slice(Dout, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)dy, B, Dout, Dout, 0};
     DenseView<float, false> Bv{(const float*)w, Din, Dout, Din, 0};
-    return launch_f32<false>(A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din}, B, Din, Dout, one_slice(Dout, 16), 1, s);
+    return launch_f32<false>(kcDenseDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din}, B, Din, Dout, one_slice(Dout, 16), 1, s);
 }
 
 hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout, float* ws,
@@ -209,15 +222,15 @@ hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int 
         if (fast) {
             DenseRC A{(const bf16_t*)dy, Dout, B, Dout};
             DenseRC Bv{(const bf16_t*)x, Din, B, Din};
-            return run2_wgrad(A, Bv, gw, Dout, Din, B, ws, s);
+            return run2_wgrad(kcDenseWgrad, A, Bv, gw, Dout, Din, B, ws, s);
         }
         DenseView<bf16_t, false> A{(const bf16_t*)dy, Dout, B, Dout, 0};
         DenseView<bf16_t, false> Bv{(const bf16_t*)x, Din, B, Din, 0};
-        return wgrad_fallback<bf16_t>(A, Bv, gw, Dout, Din, B, ws, s);
+        return wgrad_fallback<bf16_t>(kcDenseWgrad, A, Bv, gw, Dout, Din, B, ws, s);
     }
     DenseView<float, false> A{(const float*)dy, Dout, B, Dout, 0};
     DenseView<float, false> Bv{(const float*)x, Din, B, Din, 0};
-    return wgrad_fallback<float>(A, Bv, gw, Dout, Din, B, ws, s);
+    return wgrad_fallback<float>(kcDenseWgrad, A, Bv, gw, Dout, Din, B, ws, s);
 }
 
 // ---------------------------------------------------------------------------------- convolution
@@ -253,15 +266,15 @@ hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bi
         if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w) && small_enough(c)) {
             ConvFwdA2 A{(const bf16_t*)x, geom2(c), M, K};
             DenseKC Bv{(const bf16_t*)w, c.Cout, K, K};
-            return run2(A, Bv, epi, M, c.Cout, K, ws, s);
+            return run2(kcConvFwd, A, Bv, epi, M, c.Cout, K, ws, s);
         }
         ConvFwdA<bf16_t> A{(const bf16_t*)x, geom(c), M, K, 0};
         DenseView<bf16_t, true> Bv{(const bf16_t*)w, c.Cout, K, K, 0};
-        return launch_bf16<false>(A, Bv, epi, M, c.Cout, K, one_slice(K, kBK), 1, s);
+        return launch_bf16<false>(kcConvFwd, A, Bv, epi, M, c.Cout, K, one_slice(K, kBK), 1, s);
     }
     ConvFwdA<float> A{(const float*)x, geom(c), M, K, 0};
     DenseView<float, true> Bv{(const float*)w, c.Cout, K, K, 0};
-    return launch_f32<false>(A, Bv, EpiBiasAct<float>{(float*)y, bias, c.Cout, relu}, M, c.Cout, K, one_slice(K, 16), 1, s);
+    return launch_f32<false>(kcConvFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, c.Cout, relu}, M, c.Cout, K, one_slice(K, 16), 1, s);
 }
 
 hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const ConvShape& c,
@@ -272,15 +285,15 @@ hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const 
         if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w) && small_enough(c)) {
             ConvDgradA2 A{(const bf16_t*)dy, geom2(c), M, K};
             ConvDgradB2 Bv{(const bf16_t*)w, geom2(c), c.Cin, K};
-            return run2(A, Bv, epi, M, c.Cin, K, ws, s);
+            return run2(kcConvDgrad, A, Bv, epi, M, c.Cin, K, ws, s);
         }
         ConvDgradA<bf16_t> A{(const bf16_t*)dy, geom(c), M, K, 0};
         ConvDgradB<bf16_t> Bv{(const bf16_t*)w, geom(c), c.Cin, K};
-        return launch_bf16<false>(A, Bv, epi, M, c.Cin, K, one_slice(K, kBK), 1, s);
+        return launch_bf16<false>(kcConvDgrad, A, Bv, epi, M, c.Cin, K, one_slice(K, kBK), 1, s);
     }
     ConvDgradA<float> A{(const float*)dy, geom(c), M, K, 0};
     ConvDgradB<float> Bv{(const float*)w, geom(c), c.Cin, K};
-    return launch_f32<false>(A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, c.Cin}, M, c.Cin, K, one_slice(K, 16), 1, s);
+    return launch_f32<false>(kcConvDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, c.Cin}, M, c.Cin, K, one_slice(K, 16), 1, s);
 }
 
 hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c, float* ws,
@@ -292,15 +305,15 @@ hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const
             DenseRC A{(const bf16_t*)dy, rows, (int)K, c.Cout};
             const int rows64 = kBK2 / c.Wo;
             ConvWgradB2 Bv{(const bf16_t*)x, geom2(c), cols, (int)K, kBK2 % c.Wo, rows64 % c.Ho, rows64 / c.Ho};
-            return run2_wgrad(A, Bv, gw, rows, cols, K, ws, s);
+            return run2_wgrad(kcConvWgrad, A, Bv, gw, rows, cols, K, ws, s);
         }
         DenseView<bf16_t, false> A{(const bf16_t*)dy, rows, (int)K, c.Cout, 0};
         ConvWgradB<bf16_t> Bv{(const bf16_t*)x, geom(c), cols, (int)K};
-        return wgrad_fallback<bf16_t>(A, Bv, gw, rows, cols, K, ws, s);
+        return wgrad_fallback<bf16_t>(kcConvWgrad, A, Bv, gw, rows, cols, K, ws, s);
     }
     DenseView<float, false> A{(const float*)dy, rows, (int)K, c.Cout, 0};
     ConvWgradB<float> Bv{(const float*)x, geom(c), cols, (int)K};
-    return wgrad_fallback<float>(A, Bv, gw, rows, cols, K, ws, s);
+    return wgrad_fallback<float>(kcConvWgrad, A, Bv, gw, rows, cols, K, ws, s);
 }
 
 }  // namespace tmps

@@ -48,6 +48,19 @@ void profile_end(int kc, hipStream_t s) {
     t_open = nullptr;
 }
 
+bool profile_kernel_begin(KernelEvents& ev) {
+    if (!g_on) return false;
+    std::lock_guard<std::mutex> lk(g_mu);
+    ev.start = get_event();
+    ev.stop = get_event();
+    return ev.start && ev.stop;
+}
+
+void profile_kernel_end(int kc, const KernelEvents& ev) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_spans.push_back(Span{kc, ev.start, ev.stop});
+}
+
 }  // namespace tmps
 
 using namespace tmps;

@@ -6,13 +6,21 @@ namespace tmps {
 
 enum KernelClass {
     kcDenseFwd = 0, kcDenseDgrad, kcDenseWgrad, kcConvFwd, kcConvDgrad, kcConvWgrad, kcSoftmaxCE,
-    kcUpdate, kcPoolFwd, kcPoolBwd, kcReluMask, kcReduce, kcCopy, kcCount
+    kcUpdate, kcPoolFwd, kcPoolBwd, kcReluMask, kcReduce, kcCopy, kcEventPair, kcSplitFinish, kcSliceSum, kcCount
 };
 
 bool profile_on();
 // Record a start/stop event pair around a launch of class `kc` on stream `s`.
 void profile_begin(int kc, hipStream_t s);
 void profile_end(int kc, hipStream_t s);
+
+// Timing of ONE kernel by its own dispatch timestamps: the two events are handed to
+// hipExtLaunchKernelGGL, which stamps them with the start and the end of that kernel's execution.
+struct KernelEvents {
+    hipEvent_t start, stop;
+};
+bool profile_kernel_begin(KernelEvents& ev);          // false when profiling is off (or no event could be made)
+void profile_kernel_end(int kc, const KernelEvents& ev);
 
 struct ProfileScope {
     int kc;
