@@ -41,13 +41,17 @@ class Stage:
             raise RuntimeError("stash slot %r is in use" % (slot,))
         caches = []
         q = self.q
-        a = q(x)
+        a = x if self.specs[0]["kind"] == "embedding" else q(x)
         loss = None
+        inputs = []   # inputs[li] = what layer li read (a residual connection adds one of these)
         for li, (spec, p) in enumerate(zip(self.specs, self.params)):
             k = spec["kind"]
+            inputs.append(a)
             feeds_loss = li + 1 < len(self.specs) and self.specs[li + 1]["kind"] == "softmax_ce"
             if k == "linear":
-                a, c = L.linear_forward(a, q(p["w"]), p["b"], spec["relu"])
+                skip = inputs[li - spec["skip"]] if spec.get("skip") else None
+                a, c = L.linear_forward(a, q(p["w"]), p["b"], spec["relu"], spec.get("act"), spec.get("rows", 1),
+                                        skip, round_z=q)
                 if not feeds_loss:
                     a = c["y"] = q(a)
             elif k == "conv":
@@ -55,8 +59,18 @@ class Stage:
                 a = c["y"] = q(a)
             elif k == "maxpool":
                 a, c = L.maxpool_forward(a, spec["k"], spec["stride"])
+            elif k == "layernorm":
+                a, c = L.layernorm_forward(a, p["w"], p["b"], spec["d"], spec["eps"])
+                a = q(a)
+            elif k == "attention":
+                a, c = L.attention_forward(a, spec["s"], spec["d"], spec["heads"])
+                a = q(a)
+            elif k == "embedding":
+                a, c = L.embedding_forward(a, q(p["w"]), q(p["b"]))
+                a = q(a)
             elif k == "softmax_ce":
-                loss, c = L.softmax_ce_forward(a, np.asarray(labels))
+                rows = spec.get("rows", 1)
+                loss, c = L.softmax_ce_forward(a.reshape(a.shape[0] * rows, -1), np.asarray(labels).reshape(-1))
             else:
                 raise ValueError(k)
             caches.append(c)
@@ -77,22 +91,34 @@ class Stage:
             caches = self.stash.pop(slot)
             q = self.q
             g = None if dy is None else q(dy[i * micro:(i + 1) * micro])
+            held = {}   # layer index -> gradient of a residual connection that joins that layer's input
             for li in range(len(self.specs) - 1, -1, -1):
                 spec, p, c = self.specs[li], self.params[li], caches[li]
                 k = spec["kind"]
+                dw = db = None
                 if k == "softmax_ce":
-                    g = q(L.softmax_ce_backward(c, self.M))
-                    continue
-                if k == "linear":
-                    g = g.reshape(g.shape[0], -1)
-                    g, dw, db = L.linear_backward(g, c, q(p["w"]), spec["relu"])
-                    g = q(g)
+                    g = L.softmax_ce_backward(c, self.M * spec.get("rows", 1))
+                elif k == "linear":
+                    if spec.get("skip"):
+                        held[li - spec["skip"]] = g
+                    g, dw, db = L.linear_backward(g, c, q(p["w"]), spec["relu"], spec.get("act"))
                 elif k == "conv":
                     g = g.reshape(c["y"].shape)
                     g, dw, db = L.conv_backward(g, c, q(p["w"]), spec["stride"], spec["pad"], spec["relu"])
-                    g = q(g)
                 elif k == "maxpool":
                     g = L.maxpool_backward(g.reshape(c["win"].shape), c, spec["k"], spec["stride"])
+                elif k == "layernorm":
+                    g, dw, db = L.layernorm_backward(g, c, p["w"])
+                elif k == "attention":
+                    g = L.attention_backward(g, c)
+                elif k == "embedding":
+                    dw, db = L.embedding_backward(g, c, spec["vocab"], spec["d"])
+                    g = None
+                if li in held:
+                    g = g.reshape(g.shape[0], -1) + held.pop(li).reshape(g.shape[0], -1)
+                if g is not None and k != "maxpool":
+                    g = q(g).reshape(g.shape[0], -1)
+                if dw is None:
                     continue
                 if acc[li] is None:
                     acc[li] = {"w": dw, "b": db}
@@ -101,7 +127,7 @@ class Stage:
                     acc[li]["b"] = acc[li]["b"] + db
             dxs.append(g)
         self.grads = acc
-        return np.concatenate(dxs, axis=0)
+        return None if dxs[0] is None else np.concatenate(dxs, axis=0)
 
     # -- in-place update -------------------------------------------------------------------
     def update(self):

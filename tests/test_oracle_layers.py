@@ -184,3 +184,123 @@ def test_maxpool_gradient_goes_to_one_winner_per_window():
     y, c = L.maxpool_forward(np.zeros((1, 2, 2, 1)), 2, 2)
     dx = L.maxpool_backward(np.ones_like(y), c, 2, 2)
     assert dx.sum() == 1.0 and dx[0, 0, 0, 0] == 1.0
+
+
+# ------------------------------------------------------------------ GELU, residual linear
+def test_gelu_closed_forms_and_library():
+    z = np.linspace(-6, 6, 97)
+    g = L.gelu(z)
+    assert L.gelu(np.zeros(1))[0] == 0.0
+    assert np.allclose(g - L.gelu(-z), z, atol=1e-15)             # z Phi(z) - (-z) Phi(-z) = z
+    assert abs(L.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15   # Phi(1)
+    zt = torch.tensor(z, requires_grad=True)
+    yt = F.gelu(zt)
+    yt.sum().backward()
+    assert _rel(g, yt.detach().numpy()) < 1e-14
+    assert _rel(L.gelu_derivative(z), zt.grad.numpy()) < 1e-13
+
+
+def test_linear_gelu_rows_and_residual_against_library_and_fd():
+    rng = np.random.default_rng(20)
+    B, rows, din, dout = 2, 3, 5, 5
+    x = rng.standard_normal((B, rows * din)); w = rng.standard_normal((dout, din)); b = rng.standard_normal(dout)
+    skip = rng.standard_normal((B, rows * dout)); r = rng.standard_normal((B, rows * dout))
+    y, c = L.linear_forward(x, w, b, False, "gelu", rows, None)
+    dx, dw, db = L.linear_backward(r, c, w, False, "gelu")
+    xt, wt, bt = (torch.tensor(a, requires_grad=True) for a in (x, w, b))
+    yt = F.gelu(F.linear(xt.reshape(B * rows, din), wt, bt)).reshape(B, -1)
+    yt.backward(torch.tensor(r))
+    assert _rel(y, yt.detach().numpy()) < 1e-13
+    assert _rel(dx, xt.grad.numpy()) < 1e-12 and _rel(dw, wt.grad.numpy()) < 1e-12 and _rel(db, bt.grad.numpy()) < 1e-12
+    f = lambda: float((L.linear_forward(x, w, b, False, "gelu", rows, None)[0] * r).sum())
+    assert _rel(dx, _fd(f, x)) < 1e-6
+    # residual: the result is the plain layer plus the skipped tensor
+    y2, _ = L.linear_forward(x, w, b, False, None, rows, skip)
+    y1, _ = L.linear_forward(x, w, b, False, None, rows, None)
+    assert np.allclose(y2, y1 + skip)
+
+
+# ------------------------------------------------------------------ layer normalisation
+def test_layernorm_invariants_library_and_fd():
+    rng = np.random.default_rng(21)
+    B, rows, d = 2, 3, 7
+    x = rng.standard_normal((B, rows * d)) * 3 + 1
+    gam = rng.standard_normal(d); bet = rng.standard_normal(d); r = rng.standard_normal((B, rows * d))
+    y1, c1 = L.layernorm_forward(x, np.ones(d), np.zeros(d), d, eps=0.0)
+    y1 = y1.reshape(-1, d)
+    assert np.allclose(y1.mean(axis=1), 0, atol=1e-14) and np.allclose((y1 ** 2).mean(axis=1), 1, atol=1e-12)
+    y, c = L.layernorm_forward(x, gam, bet, d, 1e-5)
+    dx, dg, db = L.layernorm_backward(r, c, gam)
+    xt, gt, bt = (torch.tensor(a, requires_grad=True) for a in (x, gam, bet))
+    yt = F.layer_norm(xt.reshape(-1, d), (d,), gt, bt, 1e-5).reshape(B, -1)
+    yt.backward(torch.tensor(r))
+    assert _rel(y, yt.detach().numpy()) < 1e-13
+    assert _rel(dx, xt.grad.numpy()) < 1e-11 and _rel(dg, gt.grad.numpy()) < 1e-12 and _rel(db, bt.grad.numpy()) < 1e-12
+    f = lambda: float((L.layernorm_forward(x, gam, bet, d, 1e-5)[0] * r).sum())
+    assert _rel(dx, _fd(f, x)) < 1e-6
+    assert _rel(dg, _fd(f, gam)) < 1e-7
+    # dx comes from the gain passed to backward, the statistics from the forward pass
+    gam2 = rng.standard_normal(d)
+    dx2, _, _ = L.layernorm_backward(r, c, gam2)
+    dxr, _, _ = L.layernorm_backward((r.reshape(-1, d) * gam2 / gam).reshape(r.shape), c, gam)
+    assert np.allclose(dx2, dxr)
+
+
+# ------------------------------------------------------------------ attention
+def _attention_loops(qkv, s, d, heads):
+    """Definition written out with loops (tiny sizes only)."""
+    B = qkv.shape[0]
+    dh = d // heads
+    t = qkv.reshape(B, s, 3, heads, dh)
+    out = np.zeros((B, s, heads, dh))
+    for b in range(B):
+        for h in range(heads):
+            for i in range(s):
+                sc = np.array([t[b, i, 0, h] @ t[b, j, 1, h] / np.sqrt(dh) for j in range(i + 1)])
+                p = np.exp(sc - sc.max())
+                p /= p.sum()
+                for j in range(i + 1):
+                    out[b, i, h] += p[j] * t[b, j, 2, h]
+    return out.reshape(B, s * d)
+
+
+def test_attention_definition_causality_library_and_fd():
+    rng = np.random.default_rng(22)
+    B, s, d, heads = 2, 5, 6, 2
+    qkv = rng.standard_normal((B, s * 3 * d)); r = rng.standard_normal((B, s * d))
+    y, c = L.attention_forward(qkv, s, d, heads)
+    assert np.allclose(y, _attention_loops(qkv, s, d, heads), atol=1e-13)
+    assert np.allclose(c["p"].sum(axis=-1), 1.0) and np.all(np.triu(c["p"], 1) == 0.0)
+    # position i depends on positions <= i only
+    q2 = qkv.reshape(B, s, 3 * d).copy()
+    q2[:, 3:] += rng.standard_normal((B, s - 3, 3 * d))
+    y2, _ = L.attention_forward(q2.reshape(B, -1), s, d, heads)
+    assert np.allclose(y.reshape(B, s, d)[:, :3], y2.reshape(B, s, d)[:, :3])
+    # first position attends to itself only: output = its own value vector
+    assert np.allclose(y.reshape(B, s, d)[:, 0], qkv.reshape(B, s, 3, d)[:, 0, 2])
+    dx = L.attention_backward(r, c)
+    dh = d // heads
+    tt = torch.tensor(qkv.reshape(B, s, 3, heads, dh), requires_grad=True)
+    qh, kh, vh = (tt[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    yt = F.scaled_dot_product_attention(qh, kh, vh, is_causal=True).permute(0, 2, 1, 3).reshape(B, s * d)
+    yt.backward(torch.tensor(r))
+    assert _rel(y, yt.detach().numpy()) < 1e-12
+    assert _rel(dx, tt.grad.numpy().reshape(B, -1)) < 1e-11
+    f = lambda: float((L.attention_forward(qkv, s, d, heads)[0] * r).sum())
+    assert _rel(dx, _fd(f, qkv)) < 1e-6
+
+
+# ------------------------------------------------------------------ embedding
+def test_embedding_definition_and_gradients():
+    rng = np.random.default_rng(23)
+    B, s, d, vocab = 3, 4, 5, 6
+    tok = rng.integers(0, vocab, (B, s)); tok[0, 0] = tok[1, 2] = tok[2, 3] = 1     # repeated token
+    wte = rng.standard_normal((vocab, d)); wpe = rng.standard_normal((s, d)); r = rng.standard_normal((B, s * d))
+    y, c = L.embedding_forward(tok, wte, wpe)
+    for b in range(B):
+        for i in range(s):
+            assert np.array_equal(y.reshape(B, s, d)[b, i], wte[tok[b, i]] + wpe[i])
+    dwte, dwpe = L.embedding_backward(r, c, vocab, d)
+    f = lambda: float((L.embedding_forward(tok, wte, wpe)[0] * r).sum())
+    assert _rel(dwte, _fd(f, wte)) < 1e-8 and _rel(dwpe, _fd(f, wpe)) < 1e-8
+    assert np.allclose(dwte[1], sum(r.reshape(B, s, d)[b, i] for b in range(B) for i in range(s) if tok[b, i] == 1))

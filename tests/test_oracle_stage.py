@@ -31,12 +31,35 @@ def _torch_net_loss(cfg, params, x, labels):
     """Whole-network mean cross-entropy written with library ops (independent of the oracle)."""
     a = torch.tensor(np.asarray(x, dtype=np.float64))
     for st, ps in zip(cfg.stages, params):
+        ins = []      # inputs of this stage's layers (sources of residual connections)
         for spec, p in zip(st, ps):
             k = spec["kind"]
+            if k == "linear" and spec.get("rows", 1) > 1:
+                src = ins[len(ins) - spec["skip"]] if spec.get("skip") else None
+                ins.append(a)
+                a = F.linear(a.reshape(a.shape[0], spec["rows"], -1), p["w"], p["b"])
+                if spec.get("act") == "gelu":
+                    a = F.gelu(a)
+                a = a.reshape(a.shape[0], -1)
+                if src is not None:
+                    a = a + src
+                continue
+            ins.append(a)
             if k == "linear":
                 a = F.linear(a.reshape(a.shape[0], -1), p["w"], p["b"])
                 if spec["relu"]:
                     a = F.relu(a)
+            elif k == "layernorm":
+                a = F.layer_norm(a.reshape(a.shape[0], spec["rows"], spec["d"]), (spec["d"],), p["w"], p["b"],
+                                 spec["eps"]).reshape(a.shape[0], -1)
+            elif k == "attention":
+                B, s, d, h = a.shape[0], spec["s"], spec["d"], spec["heads"]
+                t = a.reshape(B, s, 3, h, d // h)
+                q_, k_, v_ = (t[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+                a = F.scaled_dot_product_attention(q_, k_, v_, is_causal=True).permute(0, 2, 1, 3).reshape(B, s * d)
+            elif k == "embedding":
+                tok = torch.tensor(np.asarray(x, dtype=np.int64))
+                a = (p["w"][tok] + p["b"][None]).reshape(tok.shape[0], -1)
             elif k == "conv":
                 a = F.conv2d(a.permute(0, 3, 1, 2), p["w"].permute(0, 3, 1, 2), p["b"],
                              stride=spec["stride"], padding=spec["pad"]).permute(0, 2, 3, 1)
@@ -45,7 +68,8 @@ def _torch_net_loss(cfg, params, x, labels):
             elif k == "maxpool":
                 a = F.max_pool2d(a.permute(0, 3, 1, 2), spec["k"], spec["stride"]).permute(0, 2, 3, 1)
             elif k == "softmax_ce":
-                return F.cross_entropy(a, torch.tensor(np.asarray(labels, dtype=np.int64)))
+                return F.cross_entropy(a.reshape(-1, spec["classes"]),
+                                       torch.tensor(np.asarray(labels, dtype=np.int64)).reshape(-1))
     raise AssertionError
 
 
@@ -54,7 +78,8 @@ def _torch_params(params):
              for p in ps] for ps in params]
 
 
-@pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=2, N=2)])
+@pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=2, N=2),
+                                    lambda: get_config("tiny_transformer_f32")])
 def test_micro_batched_forward_and_gradients_equal_full_batch(cfg_fn):
     cfg = cfg_fn()
     params = init_params(cfg, bias_std=0.1)
@@ -88,7 +113,8 @@ def test_micro_batched_forward_and_gradients_equal_full_batch(cfg_fn):
                 assert np.max(np.abs(g_o[k] - ref)) <= 1e-12 * (1 + np.max(np.abs(ref))), k
 
 
-@pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=1, N=2)])
+@pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=1, N=2),
+                                    lambda: get_config("tiny_transformer_f32")])
 def test_single_worker_equals_textbook_sgd_momentum(cfg_fn):
     cfg = cfg_fn()
     flat_layers = [l for st in cfg.stages for l in st]

@@ -10,8 +10,32 @@ from dataclasses import dataclass, field
 from typing import List, Tuple
 
 
-def linear(din, dout, relu):
-    return {"kind": "linear", "din": int(din), "dout": int(dout), "relu": bool(relu)}
+def linear(din, dout, relu, act=None, rows=1, skip=0):
+    """rows: rows per sample (the layer acts on each row of [rows, din]); act: None or "gelu" (relu=True is
+    the ReLU); skip: k > 0 adds the input of the layer k positions before this one (residual connection)."""
+    return {"kind": "linear", "din": int(din), "dout": int(dout), "relu": bool(relu), "act": act,
+            "rows": int(rows), "skip": int(skip)}
+
+
+def layernorm(d, rows=1, eps=1e-5):
+    return {"kind": "layernorm", "d": int(d), "rows": int(rows), "eps": float(eps)}
+
+
+def attention(s, d, heads):
+    """Causal multi-head self-attention on packed [s, 3d] = (q | k | v) rows; output [s, d]."""
+    return {"kind": "attention", "s": int(s), "d": int(d), "heads": int(heads)}
+
+
+def embedding(vocab, s, d):
+    """Token + learned positional embedding: int tokens [s] -> [s, d]."""
+    return {"kind": "embedding", "vocab": int(vocab), "s": int(s), "d": int(d)}
+
+
+def transformer_block(s, d, heads, ffn):
+    """Pre-LayerNorm block: x + proj(attn(qkv(LN(x)))), then x + fc2(gelu(fc1(LN(x))))."""
+    return [layernorm(d, s), linear(d, 3 * d, False, rows=s), attention(s, d, heads),
+            linear(d, d, False, rows=s, skip=3),
+            layernorm(d, s), linear(d, ffn, False, act="gelu", rows=s), linear(ffn, d, False, rows=s, skip=2)]
 
 
 def conv(h, w, cin, cout, r=3, stride=1, pad=1, relu=True):
@@ -24,8 +48,9 @@ def maxpool(h, w, c, k=2, stride=2):
             "stride": int(stride)}
 
 
-def softmax_ce(classes):
-    return {"kind": "softmax_ce", "classes": int(classes)}
+def softmax_ce(classes, rows=1):
+    """rows: labelled rows per sample (sequence positions); the loss is the mean over all rows."""
+    return {"kind": "softmax_ce", "classes": int(classes), "rows": int(rows)}
 
 
 @dataclass
@@ -42,6 +67,7 @@ class Config:
     momentum: float = 0.9
     steps: int = 20
     notes: str = ""
+    vocab: int = 0             # > 0: inputs are int token ids [S] uniform over the vocabulary, labels the next tokens
 
     @property
     def K(self):
@@ -93,10 +119,37 @@ def _vgg16(fc_width=4096):
         notes="FC widths 512-4096-4096-10 (the 1x1x512 feature map of a 32x32 input)")
 
 
+def _transformer(name, dtype, layers, d, heads, ffn, s, vocab, M, N, K, seed):
+    per = layers // K
+    stages = []
+    for k in range(K):
+        st = [embedding(vocab, s, d)] if k == 0 else []
+        for _ in range(per):
+            st += transformer_block(s, d, heads, ffn)
+        if k == K - 1:
+            st += [layernorm(d, s), linear(d, vocab, False, rows=s), softmax_ce(vocab, rows=s)]
+        stages.append(st)
+    return Config(name=name, dtype=dtype, M=M, N=N, seed=seed, steps=2, in_shape=(s,), classes=vocab, vocab=vocab,
+                  stages=stages,
+                  notes="pre-LayerNorm, causal attention, exact-erf GELU, learned positions, untied output layer, "
+                        "eps 1e-5; S+1 tokens are drawn per sample: the first S are the input, the last S the targets")
+
+
+def _gpt2_small():
+    return _transformer("gpt2_small_bf16", "bf16", 12, 768, 12, 3072, 512, 32000, M=16, N=8, K=4, seed=4)
+
+
+def _tiny_transformer(dtype):
+    return lambda: _transformer("tiny_transformer_" + dtype, dtype, 2, 64, 2, 128, 32, 96, M=8, N=4, K=2, seed=5)
+
+
 CONFIGS = {
     "tiny_mlp_f32": _tiny_mlp,
     "mlp4x1024_bf16": _mlp_bf16,
     "vgg16_bf16": _vgg16,
+    "gpt2_small_bf16": _gpt2_small,
+    "tiny_transformer_f32": _tiny_transformer("f32"),
+    "tiny_transformer_bf16": _tiny_transformer("bf16"),
 }
 
 
@@ -108,7 +161,13 @@ def layer_out_shape(layer, in_shape):
     """Per-sample output shape of one layer given its per-sample input shape."""
     k = layer["kind"]
     if k == "linear":
-        return (layer["dout"],)
+        return (layer["dout"],) if layer.get("rows", 1) == 1 else (layer["rows"], layer["dout"])
+    if k == "layernorm":
+        return tuple(in_shape)
+    if k == "attention":
+        return (layer["s"], layer["d"])
+    if k == "embedding":
+        return (layer["s"], layer["d"])
     if k == "conv":
         ho = (layer["h"] + 2 * layer["pad"] - layer["r"]) // layer["stride"] + 1
         wo = (layer["w"] + 2 * layer["pad"] - layer["s"]) // layer["stride"] + 1
@@ -118,7 +177,7 @@ def layer_out_shape(layer, in_shape):
         wo = (layer["w"] - layer["k"]) // layer["stride"] + 1
         return (ho, wo, layer["c"])
     if k == "softmax_ce":
-        return (layer["classes"],)
+        return (layer["classes"],) if layer.get("rows", 1) == 1 else (layer["rows"], layer["classes"])
     raise ValueError(k)
 
 

@@ -2,7 +2,9 @@
 
 Inputs follow the recipe of the benchmark configurations: standard-normal
 inputs, labels uniform over the classes, He-normal weights ``N(0, 2/fan_in)``
-and zero biases.  Everything is drawn with numpy's PCG64 generator keyed by
+and zero biases; layer-normalisation gains 1 and shifts 0; embedding tables
+``N(0, 0.02^2)``; token inputs uniform over the vocabulary, S+1 per sample
+(the first S are the input, the last S the next-token targets).  Everything is drawn with numpy's PCG64 generator keyed by
 ``(seed, stream, index)`` so that a batch can be regenerated independently.
 The only numeric helper is ``to_bf16_grid``, which snaps fp32 *input data* to
 values exactly representable in bfloat16 so that both implementations start
@@ -37,6 +39,10 @@ def param_shapes(layer):
         return {"w": (layer["dout"], layer["din"]), "b": (layer["dout"],)}
     if layer["kind"] == "conv":
         return {"w": (layer["cout"], layer["r"], layer["s"], layer["cin"]), "b": (layer["cout"],)}
+    if layer["kind"] == "layernorm":      # w = gain, b = shift
+        return {"w": (layer["d"],), "b": (layer["d"],)}
+    if layer["kind"] == "embedding":      # w = token table, b = position table
+        return {"w": (layer["vocab"], layer["d"]), "b": (layer["s"], layer["d"])}
     return {}
 
 
@@ -49,7 +55,18 @@ def init_params(cfg, bias_std=0.0):
         for layer in st:
             shp = param_shapes(layer)
             p = {}
-            if shp:
+            if shp and layer["kind"] == "layernorm":
+                g = _rng(cfg.seed, 1, idx)
+                p["w"] = np.ones(shp["w"], dtype=np.float32)
+                p["b"] = np.zeros(shp["b"], dtype=np.float32)
+                if bias_std > 0.0:
+                    p["w"] += (g.standard_normal(shp["w"]) * bias_std).astype(np.float32)
+                    p["b"] += (g.standard_normal(shp["b"]) * bias_std).astype(np.float32)
+            elif shp and layer["kind"] == "embedding":
+                g = _rng(cfg.seed, 1, idx)
+                p["w"] = (g.standard_normal(shp["w"]) * 0.02).astype(np.float32)
+                p["b"] = (g.standard_normal(shp["b"]) * 0.02).astype(np.float32)
+            elif shp:
                 g = _rng(cfg.seed, 1, idx)
                 std = np.sqrt(2.0 / fan_in(layer))
                 p["w"] = (g.standard_normal(shp["w"]) * std).astype(np.float32)
@@ -67,6 +84,10 @@ def make_batch(cfg, step, M=None):
     """One mini-batch: (x fp32 [M, *in_shape], labels int32 [M]); bf16 configs get bf16-grid inputs."""
     M = cfg.M if M is None else M
     g = _rng(cfg.seed, 2, step)
+    if getattr(cfg, "vocab", 0):
+        s = cfg.in_shape[0]
+        t = g.integers(0, cfg.vocab, size=(M, s + 1), dtype=np.int64).astype(np.int32)
+        return np.ascontiguousarray(t[:, :s]), np.ascontiguousarray(t[:, 1:])
     x = g.standard_normal((M,) + tuple(cfg.in_shape)).astype(np.float32)
     if cfg.dtype == "bf16":
         x = to_bf16_grid(x)
