@@ -54,12 +54,23 @@ enum { TMPS_F32 = 0, TMPS_BF16_F32MASTER = 1 };
 
 /* Layer kinds and the meaning of tmps_layer_desc.dims */
 enum {
-    TMPS_LINEAR = 1,     /* dims = {Din, Dout}; flags TMPS_FLAG_RELU */
+    TMPS_LINEAR = 1,     /* dims = {Din, Dout, skip, rows}; flags TMPS_FLAG_RELU or TMPS_FLAG_GELU.  rows (0 = 1):
+                            rows per sample, the layer maps every row [Din] -> [Dout].  skip > 0: the input of the
+                            layer `skip` positions before this one (which must be a TMPS_LAYERNORM) is added to the
+                            result: a residual connection around the layers in between */
     TMPS_CONV2D = 2,     /* dims = {H, W, Cin, Cout, R, S, stride, pad}; flags TMPS_FLAG_RELU */
     TMPS_MAXPOOL = 3,    /* dims = {H, W, C, k, stride} (no padding) */
-    TMPS_SOFTMAX_CE = 4  /* dims = {classes}; only as the last layer of the last stage */
+    TMPS_SOFTMAX_CE = 4, /* dims = {classes, rows}; only as the last layer of the last stage, after a plain
+                            TMPS_LINEAR with the same rows; labels are int32 [samples, rows]; the loss is the
+                            mean over all rows */
+    TMPS_LAYERNORM = 5,  /* dims = {D, rows}; per row of D features, eps 1e-5; parameters gain (w) and shift (b) */
+    TMPS_ATTENTION = 6,  /* dims = {S, D, heads}; causal multi-head self-attention; input rows [q | k | v] of 3*D
+                            features, output [S, D]; scores scaled by 1/sqrt(D/heads) */
+    TMPS_EMBEDDING = 7   /* dims = {vocab, S, D}; first layer of a stage only; the stage input is int32 tokens
+                            [samples, S]; output [S, D] = token table row + position table row; parameters
+                            token table (w, [vocab, D]) and position table (b, [S, D]) */
 };
-enum { TMPS_FLAG_RELU = 1 };
+enum { TMPS_FLAG_RELU = 1, TMPS_FLAG_GELU = 2 /* exact: z * Phi(z) */ };
 
 typedef struct tmps_stage tmps_stage; /* opaque */
 
@@ -168,8 +179,9 @@ int tmps_version_diff_simulated(int W, int N);
 
 /* Run n_minibatches through K stages on K streams of one GPU in nF1B order.  stages[s] must
  * have been created with n_micro = N, borrow_input = 1 for s > 0, and enough stash
- * (tmps_schedule_stash_groups).  inputs: device, n_minibatches*M rows of stage 0's input;
- * labels: device int32, n_minibatches*M.  losses_out: device float[n_minibatches], the mean
+ * (tmps_schedule_stash_groups).  inputs: device, n_minibatches*M rows of stage 0's input
+ * (int32 tokens when it starts with an embedding); labels: device int32, n_minibatches*M times the rows
+ * per sample of the loss layer.  losses_out: device float[n_minibatches], the mean
  * of the N micro-batch losses.  version_log_out: host int32[7 * tasks] as tmps_schedule_plan,
  * except that field 5 is read from the stage objects as the tasks are issued; may be NULL.
  * Cross-stage dependencies are HIP events.  Each stage's tasks are issued by a host thread of its
@@ -196,7 +208,8 @@ enum {
     TMPS_KC_DENSE_FWD = 0, TMPS_KC_DENSE_DGRAD, TMPS_KC_DENSE_WGRAD, TMPS_KC_CONV_FWD,
     TMPS_KC_CONV_DGRAD, TMPS_KC_CONV_WGRAD, TMPS_KC_SOFTMAX_CE, TMPS_KC_UPDATE, TMPS_KC_POOL_FWD,
     TMPS_KC_POOL_BWD, TMPS_KC_RELU_MASK, TMPS_KC_REDUCE, TMPS_KC_COPY, TMPS_KC_EVENT_PAIR,
-    TMPS_KC_SPLIT_FINISH, TMPS_KC_SLICE_SUM, TMPS_KERNEL_CLASSES
+    TMPS_KC_SPLIT_FINISH, TMPS_KC_SLICE_SUM, TMPS_KC_LAYERNORM,
+    TMPS_KC_ATTN_FWD, TMPS_KC_ATTN_BWD, TMPS_KC_EMBEDDING, TMPS_KERNEL_CLASSES
 };
 int tmps_profile_enable(int on);
 int tmps_profile_read(double* total_ms, int64_t* launches, int n_classes);

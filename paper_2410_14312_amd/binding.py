@@ -9,8 +9,8 @@ _LIB_PATH = os.path.join(_HERE, "libtmps.so")
 _lib = None
 
 TMPS_F32, TMPS_BF16_F32MASTER = 0, 1
-TMPS_LINEAR, TMPS_CONV2D, TMPS_MAXPOOL, TMPS_SOFTMAX_CE = 1, 2, 3, 4
-TMPS_FLAG_RELU = 1
+TMPS_LINEAR, TMPS_CONV2D, TMPS_MAXPOOL, TMPS_SOFTMAX_CE, TMPS_LAYERNORM, TMPS_ATTENTION, TMPS_EMBEDDING = 1, 2, 3, 4, 5, 6, 7
+TMPS_FLAG_RELU, TMPS_FLAG_GELU = 1, 2
 
 
 class TmpsError(RuntimeError):
@@ -104,7 +104,8 @@ def version_diff_simulated(W, N):
 
 
 KERNEL_CLASSES = ["dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "softmax_ce",
-                  "update", "pool_fwd", "pool_bwd", "relu_mask", "reduce", "copy", "event_pair", "splitk_finish", "slice_sum"]
+                  "update", "pool_fwd", "pool_bwd", "relu_mask", "reduce", "copy", "event_pair", "splitk_finish", "slice_sum",
+                  "layernorm", "attn_fwd", "attn_bwd", "embedding"]
 
 
 def profile_enable(on):
@@ -127,8 +128,16 @@ def layer_descs(specs):
         k = sp["kind"]
         dims = [0] * 8
         if k == "linear":
-            d.kind, dims[:2] = TMPS_LINEAR, [sp["din"], sp["dout"]]
-            d.flags = TMPS_FLAG_RELU if sp["relu"] else 0
+            d.kind, dims[:4] = TMPS_LINEAR, [sp["din"], sp["dout"], sp.get("skip", 0), sp.get("rows", 1)]
+            d.flags = TMPS_FLAG_RELU if sp["relu"] else (TMPS_FLAG_GELU if sp.get("act") == "gelu" else 0)
+        elif k == "layernorm":
+            if abs(sp["eps"] - 1e-5) > 1e-12:
+                raise ValueError("the library's layer normalisation uses eps = 1e-5")
+            d.kind, dims[:2] = TMPS_LAYERNORM, [sp["d"], sp["rows"]]
+        elif k == "attention":
+            d.kind, dims[:3] = TMPS_ATTENTION, [sp["s"], sp["d"], sp["heads"]]
+        elif k == "embedding":
+            d.kind, dims[:3] = TMPS_EMBEDDING, [sp["vocab"], sp["s"], sp["d"]]
         elif k == "conv":
             d.kind = TMPS_CONV2D
             dims[:8] = [sp["h"], sp["w"], sp["cin"], sp["cout"], sp["r"], sp["s"], sp["stride"], sp["pad"]]
@@ -136,7 +145,7 @@ def layer_descs(specs):
         elif k == "maxpool":
             d.kind, dims[:5] = TMPS_MAXPOOL, [sp["h"], sp["w"], sp["c"], sp["k"], sp["stride"]]
         elif k == "softmax_ce":
-            d.kind, dims[0] = TMPS_SOFTMAX_CE, sp["classes"]
+            d.kind, dims[:2] = TMPS_SOFTMAX_CE, [sp["classes"], sp.get("rows", 1)]
         else:
             raise ValueError("unknown layer kind %r" % k)
         for i, v in enumerate(dims):
@@ -218,6 +227,9 @@ class Stage:
                     p["w"] = p["w"].reshape(sp["cout"], sp["r"], sp["s"], sp["cin"])
                     if li == 0 and self.cin_pad:
                         p["w"] = np.ascontiguousarray(p["w"][..., :self.cin])
+                elif sp["kind"] == "embedding":
+                    p["w"] = p["w"].reshape(sp["vocab"], sp["d"])
+                    p["b"] = p["b"].reshape(sp["s"], sp["d"])
             out.append(p)
         return out
 
@@ -242,6 +254,8 @@ class Stage:
     def prepare_input(self, x):
         """Host array [rows, ...] -> device tensor in the layout and dtype the stage reads."""
         torch = self.torch
+        if self.specs[0]["kind"] == "embedding":
+            return torch.from_numpy(np.ascontiguousarray(np.asarray(x, dtype=np.int32))).to(self.device)
         x = np.asarray(x, dtype=np.float32)
         if self.cin_pad:
             x = np.concatenate([x, np.zeros(x.shape[:-1] + (self.cin_pad - self.cin,), np.float32)], axis=-1)

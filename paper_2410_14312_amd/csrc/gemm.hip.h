@@ -181,42 +181,60 @@ template <typename T> struct ConvWgradB {
 // Epilogues: called once per output element with the fp32 accumulator.  `z` is the split-K slice.
 // ------------------------------------------------------------------------------------------
 
-// out[m, n] = act(v + bias[n]); optional fp32 second output (logits).
+// Exact GELU z * Phi(z) and its derivative Phi(z) + z * phi(z).
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+    return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
+}
+
+enum { kActNone = 0, kActRelu = 1, kActGelu = 2 };
+
+// out[m, n] = act(v + bias[n]) + res[m, n].  With GELU the pre-activation is also stored (zout), for the
+// derivative in the backward pass.  res: a residual connection's source, same shape as out.
 template <typename TOut> struct EpiBiasAct {
     TOut* out;
     const float* bias;  // may be null
     int64_t ld;
-    int relu;
+    int relu;           // kActNone / kActRelu / kActGelu
+    const TOut* res = nullptr;
+    TOut* zout = nullptr;
+    __device__ __forceinline__ void finish(int64_t idx, float v) const {
+        if (relu == kActRelu) v = v > 0.0f ? v : 0.0f;
+        else if (relu == kActGelu) {
+            if (zout) zout[idx] = from_f32<TOut>(v);
+            v = gelu_f(v);
+        }
+        if (res) v += to_f32(res[idx]);
+        out[idx] = from_f32<TOut>(v);
+    }
     __device__ __forceinline__ void operator()(int m, int n, float v, int) const {
         if (bias) v += bias[n];
-        if (relu) v = v > 0.0f ? v : 0.0f;
-        out[(int64_t)m * ld + n] = from_f32<TOut>(v);
+        finish((int64_t)m * ld + n, v);
     }
     // the same in two steps: column(n) fetches the bias once, at() finishes element idx = m*ld + n
     __device__ __forceinline__ float column(int n) const { return bias ? bias[n] : 0.0f; }
-    __device__ __forceinline__ void at(float b, int64_t idx, float v, int) const {
-        v += b;
-        if (relu) v = v > 0.0f ? v : 0.0f;
-        out[idx] = from_f32<TOut>(v);
-    }
+    __device__ __forceinline__ void at(float b, int64_t idx, float v, int) const { finish(idx, v + b); }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 
-// out[m, n] = (mask == null || mask[m, n] > 0) ? v : 0   -- gradient through a stored ReLU output.
+// Gradient through the stored activation of the layer below: mode kActRelu: v where mask[m, n] > 0 else 0
+// (mask = that layer's output); mode kActGelu: v * gelu'(mask[m, n]) (mask = that layer's pre-activation).
 template <typename TOut, typename TMask> struct EpiMask {
     TOut* out;
     const TMask* mask;  // may be null
     int64_t ld;
-    __device__ __forceinline__ void operator()(int m, int n, float v, int) const {
-        int64_t i = (int64_t)m * ld + n;
-        if (mask && !(to_f32(mask[i]) > 0.0f)) v = 0.0f;
+    int mode = kActRelu;
+    __device__ __forceinline__ void finish(int64_t i, float v) const {
+        if (mask) {
+            const float t = to_f32(mask[i]);
+            if (mode == kActGelu) v *= gelu_grad_f(t);
+            else if (!(t > 0.0f)) v = 0.0f;
+        }
         out[i] = from_f32<TOut>(v);
     }
+    __device__ __forceinline__ void operator()(int m, int n, float v, int) const { finish((int64_t)m * ld + n, v); }
     __device__ __forceinline__ int column(int) const { return 0; }
-    __device__ __forceinline__ void at(int, int64_t i, float v, int) const {
-        if (mask && !(to_f32(mask[i]) > 0.0f)) v = 0.0f;
-        out[i] = from_f32<TOut>(v);
-    }
+    __device__ __forceinline__ void at(int, int64_t i, float v, int) const { finish(i, v); }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 

@@ -28,11 +28,16 @@ size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t K, int with_rowsum);
 
 // y[B, Dout] = act(x[B, Din] w^T + b).  w is the working copy (bf16 or fp32 per dtype), bias fp32.
 // out_f32: write fp32 regardless of dtype (logits).
+// act: 0 none, 1 ReLU, 2 exact GELU (then zout, if not null, receives the pre-activation).  res (may be
+// null): tensor of y's shape and dtype added after the activation (residual connection).
 hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B,
-                         int Din, int Dout, int relu, int out_f32, float* ws, hipStream_t s);
-// dx[B, Din] = dy[B, Dout] w, zeroed where mask[B, Din] <= 0 (mask may be null; activation dtype).
-hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int B,
-                       int Din, int Dout, float* ws, hipStream_t s);
+                         int Din, int Dout, int act, int out_f32, const void* res, void* zout, float* ws,
+                         hipStream_t s);
+// dx[B, Din] = dy[B, Dout] w, passed through the activation of the layer below: mask_mode 1: zeroed
+// where mask[B, Din] <= 0 (mask = that layer's output); mask_mode 2: times gelu'(mask) (mask = that
+// layer's pre-activation).  mask may be null; activation dtype.
+hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode,
+                       int B, int Din, int Dout, float* ws, hipStream_t s);
 // gw[Dout, Din] = dy^T x and gb[Dout] = column sums of dy, with gb stored right after gw.
 hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout,
                        float* ws, hipStream_t s);
@@ -50,6 +55,32 @@ hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int 
                            int stride, hipStream_t s);
 hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, int B, int H, int W,
                             int C, int k, int stride, int relu_mask, hipStream_t s);
+
+// Layer normalisation over rows of D features.  stats[rows][2] = (mean, 1/std) of the forward pass.
+hipError_t layernorm_forward(int dtype, const void* x, const float* gamma, const float* beta, void* y,
+                             float* stats, int64_t rows, int D, float eps, hipStream_t s);
+// dx (may be null) = gradient w.r.t. x, plus `add` (may be null: gradient of a residual connection that
+// joins x); dgamma_dbeta: D gain gradients followed by D shift gradients; ws: layernorm_workspace_elems.
+hipError_t layernorm_backward(int dtype, const void* dy, const void* x, const float* stats, const float* gamma,
+                              const void* add, void* dx, float* dgamma_dbeta, float* ws, int64_t rows, int D,
+                              hipStream_t s);
+size_t layernorm_workspace_elems(int64_t rows, int D);
+
+// Causal multi-head self-attention on packed rows [q | k | v] (3*D features, head h owns features
+// h*D/H.. of each part).  o[B*S, D]; lse[B, H, S] = log-sum-exp of the scaled scores of each query.
+hipError_t attention_forward(int dtype, const void* qkv, void* o, float* lse, int B, int S, int D, int H,
+                             hipStream_t s);
+// dqkv[B*S, 3*D] from the gradient dout[B*S, D] of the output; delta: workspace of B*H*S floats.
+hipError_t attention_backward(int dtype, const void* qkv, const void* o, const void* dout, const float* lse,
+                              float* delta, void* dqkv, int B, int S, int D, int H, hipStream_t s);
+size_t attention_workspace_elems(int B, int S, int H);
+
+// y[row] = wte[tok[row]] + wpe[row % S] (tables in the contraction dtype), and the table gradients
+// (fp32; dwte by atomic adds after clearing it, dwpe summed over the batch).
+hipError_t embedding_forward(int dtype, const int32_t* tok, const void* wte, const void* wpe, void* y,
+                             int64_t rows, int S, int D, int vocab, hipStream_t s);
+hipError_t embedding_backward(int dtype, const int32_t* tok, const void* dy, float* dwte, float* dwpe,
+                              int64_t B, int S, int D, int vocab, hipStream_t s);
 
 // Softmax cross-entropy of `rows` rows of fp32 logits: row_loss[rows] fp32 and
 // dlogits[rows, C] = (softmax - onehot) * inv_M in the gradient dtype.

@@ -47,9 +47,61 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float* __restrict
     if (lane == 0) row_loss[row] = label_ok ? logf(sum) - (z[label] - mx) : NAN;
 }
 
+// Wide rows (a vocabulary): one 256-thread block per row.  First pass keeps a running (max, sum) per thread
+// (online softmax), combined across the block; second pass writes the gradient.
+template <typename TG>
+__global__ __launch_bounds__(256) void softmax_ce_wide_kernel(const float* __restrict__ logits,
+                                                              const int32_t* __restrict__ labels,
+                                                              TG* __restrict__ dlogits, float* __restrict__ row_loss,
+                                                              int C, float inv_M) {
+    __shared__ float sm[4], ss[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const float* z = logits + row * C;
+    float mx = -INFINITY, sum = 0.0f;
+    for (int c = tid; c < C; c += 256) {
+        const float v = z[c];
+        if (v > mx) {
+            sum = sum * expf(mx - v) + 1.0f;
+            mx = v;
+        } else {
+            sum += expf(v - mx);
+        }
+    }
+    const float wm = wave_max(mx);
+    sum = wave_sum(sum * expf(mx - wm));   // a thread that saw nothing has sum 0 and mx -inf: 0 * exp(-inf) = 0
+    if (lane == 0) {
+        sm[wave] = wm;
+        ss[wave] = sum;
+    }
+    __syncthreads();
+    const float bm = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    float bs = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) bs += ss[w] * expf(sm[w] - bm);
+    const float inv = 1.0f / bs;
+    const int label = labels[row];
+    const bool label_ok = label >= 0 && label < C;
+    TG* g = dlogits + row * C;
+    for (int c = tid; c < C; c += 256) {
+        const float p = expf(z[c] - bm) * inv;
+        g[c] = from_f32<TG>((p - (c == label ? 1.0f : 0.0f)) * inv_M);
+    }
+    if (tid == 0) row_loss[row] = label_ok ? logf(bs) - (z[label] - bm) : NAN;
+}
+
 hipError_t softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
                       int rows, int C, float inv_M, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
+    if (C > 2048) {
+        if (dtype == kBF16)
+            hipLaunchKernelGGL(softmax_ce_wide_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, logits, labels,
+                               (bf16_t*)dlogits, row_loss, C, inv_M);
+        else
+            hipLaunchKernelGGL(softmax_ce_wide_kernel<float>, dim3(rows), dim3(256), 0, s, logits, labels,
+                               (float*)dlogits, row_loss, C, inv_M);
+        return hipGetLastError();
+    }
     dim3 grid(cdiv64(rows, 4));
     if (dtype == kBF16)
         hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, dim3(256), 0, s, logits, labels, (bf16_t*)dlogits,

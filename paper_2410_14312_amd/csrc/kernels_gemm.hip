@@ -7,6 +7,7 @@
 
 #include "gemm2.hip.h"
 #include "kernels.h"
+#include "launch.h"
 #include "profile.h"
 
 namespace tmps {
@@ -53,19 +54,6 @@ __global__ void slice_sum_kernel(const float* __restrict__ part, float* __restri
     float a = 0.0f;
     for (int z = 0; z < slices; ++z) a += part[(int64_t)z * count + i];
     out[i] = a;
-}
-
-// Launch; while profiling is enabled the kernel is stamped with its own start/stop timestamps.
-template <class Kern, class... Args>
-static hipError_t launch_timed(int kc, Kern kern, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
-    KernelEvents ev;
-    if (profile_kernel_begin(ev)) {
-        hipExtLaunchKernelGGL(kern, grid, block, lds, s, ev.start, ev.stop, 0, args...);
-        profile_kernel_end(kc, ev);
-    } else {
-        hipLaunchKernelGGL(kern, grid, block, lds, s, args...);
-    }
-    return hipGetLastError();
 }
 
 // slice length (whole k-tiles) and the number of slices really launched
@@ -175,30 +163,30 @@ static hipError_t wgrad_fallback(int kc, const AOp& A, const BOp& B, float* gw, 
 
 // ---------------------------------------------------------------------------------------- dense
 hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B, int Din,
-                         int Dout, int relu, int out_f32, float* ws, hipStream_t s) {
+                         int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
     if (dtype == kBF16) {
         const bool fast = (Din % 8 == 0) && aligned16(x) && aligned16(w);
         if (fast) {
             DenseKC A{(const bf16_t*)x, B, Din, Din};
             DenseKC Bv{(const bf16_t*)w, Dout, Din, Din};
             if (out_f32) return run2(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
-            return run2(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
+            return run2(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, ws, s);
         }
         DenseView<bf16_t, true> A{(const bf16_t*)x, B, Din, Din, 0};
         DenseView<bf16_t, true> Bv{(const bf16_t*)w, Dout, Din, Din, 0};
         if (out_f32) return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
-        return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
+        return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, one_slice(Din, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)x, B, Din, Din, 0};
     DenseView<float, true> Bv{(const float*)w, Dout, Din, Din, 0};
-    return launch_f32<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, 16), 1, s);
+    return launch_f32<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu, (const float*)res, (float*)zout}, B, Dout, Din, one_slice(Din, 16), 1, s);
 }
 
-hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int B, int Din,
-                       int Dout, float* ws, hipStream_t s) {
+hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode, int B,
+                       int Din, int Dout, float* ws, hipStream_t s) {
     // dx[m, n] = sum_k dy[m, k] * w[k, n]:  A = dy (k-contiguous), B(n, k) = w[k*Din + n] (row-contiguous)
     if (dtype == kBF16) {
-        EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din};
+        EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode};
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(w);
         if (fast) {
             DenseKC A{(const bf16_t*)dy, B, Dout, Dout};
@@ -211,7 +199,7 @@ hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const
     }
     DenseView<float, true> A{(const float*)dy, B, Dout, Dout, 0};
     DenseView<float, false> Bv{(const float*)w, Din, Dout, Din, 0};
-    return launch_f32<false>(kcDenseDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din}, B, Din, Dout, one_slice(Dout, 16), 1, s);
+    return launch_f32<false>(kcDenseDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din, mask_mode}, B, Din, Dout, one_slice(Dout, 16), 1, s);
 }
 
 hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout, float* ws,

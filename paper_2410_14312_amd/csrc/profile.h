@@ -6,7 +6,8 @@ namespace tmps {
 
 enum KernelClass {
     kcDenseFwd = 0, kcDenseDgrad, kcDenseWgrad, kcConvFwd, kcConvDgrad, kcConvWgrad, kcSoftmaxCE,
-    kcUpdate, kcPoolFwd, kcPoolBwd, kcReluMask, kcReduce, kcCopy, kcEventPair, kcSplitFinish, kcSliceSum, kcCount
+    kcUpdate, kcPoolFwd, kcPoolBwd, kcReluMask, kcReduce, kcCopy, kcEventPair, kcSplitFinish, kcSliceSum, kcLayerNorm,
+    kcAttnFwd, kcAttnBwd, kcEmbedding, kcCount
 };
 
 bool profile_on();

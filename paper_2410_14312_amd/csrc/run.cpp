@@ -97,17 +97,18 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
         const int slot = group * N + k.j;
         const void* x;
         if (k.stage == 0) {
-            x = (const char*)c.inputs + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->in_elems * c.asz;
+            x = (const char*)c.inputs + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->in_elems * st->in_esize;
         } else {
             x = tmps_stage_output_ptr(c.stages[k.stage - 1], (b0 % c.groups[k.stage - 1]) * N + k.j);
             if ((rc = c.wait_for(c.fwd_ev(k.stage - 1, q), s)) != TMPS_OK) return rc;
         }
-        const int32_t* lab = st->cfg.is_last ? c.labels + (size_t)b0 * c.M + (size_t)k.j * c.mb : nullptr;
+        const int32_t* lab = st->cfg.is_last ? c.labels + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->label_rps : nullptr;
         if ((rc = tmps_forward_micro(st, slot, x, nullptr, lab, nullptr, s)) != TMPS_OK) return rc;
         if (k.stage < K - 1 && (rc = c.record(c.fwd_ev(k.stage, q), s)) != TMPS_OK) return rc;
         if (st->cfg.is_last && k.j == N - 1 && c.losses_out) {
             ProfileScope scope(kcReduce, s);
-            TMPS_HIP(reduce_scaled_sum(stage_row_loss(st, group * N), c.M, 1.0f / (float)c.M, c.losses_out + b0, s));
+            const int rows = c.M * st->label_rps;
+            TMPS_HIP(reduce_scaled_sum(stage_row_loss(st, group * N), rows, 1.0f / (float)rows, c.losses_out + b0, s));
         }
     } else {
         const void* dy = nullptr;

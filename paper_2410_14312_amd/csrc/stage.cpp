@@ -19,6 +19,7 @@
 #include <initializer_list>
 
 #include <new>
+#include <vector>
 
 namespace tmps {
 
@@ -63,35 +64,60 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                     cfg->max_stash, cfg->n_micro);
     st.cfg = *cfg;
     st.asz = act_bytes(cfg->dtype);
+    st.in_esize = st.asz;
     st.layers.clear();
-    const int M = cfg->micro_batch * cfg->n_micro;
-    const int64_t rows_all = (int64_t)cfg->max_stash * cfg->micro_batch;
-    int64_t cur = -1, poff = 0, max_elems = 0;
+    const int mb = cfg->micro_batch;
+    const int M = mb * cfg->n_micro;
+    const int64_t rows_all = (int64_t)cfg->max_stash * mb;
+    int64_t cur = -1, poff = 0, gmax = 0;
     size_t soff = 0, ws = 0;
+    bool any_skip = false;
     for (int i = 0; i < n_layers; ++i) {
         LayerRT L;
         L.d = layers[i];
         const int32_t* d = L.d.dims;
         L.relu = (L.d.flags & TMPS_FLAG_RELU) != 0;
+        L.act = L.relu ? 1 : ((L.d.flags & TMPS_FLAG_GELU) ? 2 : 0);
         switch (L.d.kind) {
-            case TMPS_LINEAR:
+            case TMPS_LINEAR: {
                 if (d[0] < 1 || d[1] < 1) return fail(TMPS_EINVAL, "layer %d: linear dims must be positive", i);
-                L.in_elems = d[0]; L.out_elems = d[1];
+                if ((L.d.flags & TMPS_FLAG_RELU) && (L.d.flags & TMPS_FLAG_GELU))
+                    return fail(TMPS_EINVAL, "layer %d: ReLU and GELU are exclusive", i);
+                if (d[2] < 0 || d[3] < 0) return fail(TMPS_EINVAL, "layer %d: negative skip or row count", i);
+                L.rps = d[3] > 0 ? d[3] : 1;
+                L.skip = d[2];
+                L.in_elems = (int64_t)L.rps * d[0]; L.out_elems = (int64_t)L.rps * d[1];
                 L.w_count = (int64_t)d[0] * d[1]; L.b_count = d[1];
-                L.ws_elems = std::max({gemm_workspace_elems(cfg->micro_batch, d[1], d[0], 0),
-                                       gemm_workspace_elems(M, d[0], d[1], 0), gemm_workspace_elems(d[1], d[0], M, 1)});
+                if (L.skip) {
+                    const int src = i - L.skip;
+                    if (src < 0) return fail(TMPS_ESHAPE, "layer %d: residual source lies before the stage", i);
+                    if (st.layers[src].d.kind != TMPS_LAYERNORM)
+                        return fail(TMPS_EUNSUPPORTED, "layer %d: a residual connection must start at the input of a layer-normalisation layer", i);
+                    if (st.layers[src].in_elems != L.out_elems)
+                        return fail(TMPS_ESHAPE, "layer %d: residual source has %lld elements per sample, the layer output %lld", i,
+                                    (long long)st.layers[src].in_elems, (long long)L.out_elems);
+                    for (int j = src + 1; j < i; ++j)
+                        if (st.layers[j].skip && j - st.layers[j].skip == src)
+                            return fail(TMPS_EUNSUPPORTED, "layer %d: two residual connections start at the same layer", i);
+                    any_skip = true;
+                }
+                const int64_t rf = (int64_t)mb * L.rps, rb = (int64_t)M * L.rps;
+                L.ws_elems = std::max({gemm_workspace_elems(rf, d[1], d[0], 0), gemm_workspace_elems(rb, d[0], d[1], 0),
+                                       gemm_workspace_elems(d[1], d[0], rb, 1)});
                 break;
+            }
             case TMPS_CONV2D: {
                 for (int k = 0; k < 7; ++k)
                     if (d[k] < 1) return fail(TMPS_EINVAL, "layer %d: conv dims must be positive", i);
                 if (d[7] < 0) return fail(TMPS_EINVAL, "layer %d: negative padding", i);
+                if (L.act == 2) return fail(TMPS_EUNSUPPORTED, "layer %d: GELU on a convolution is not built", i);
                 ConvShape c = conv_shape(L.d, M);
                 if (c.Ho < 1 || c.Wo < 1) return fail(TMPS_ESHAPE, "layer %d: empty convolution output", i);
                 L.in_elems = (int64_t)c.H * c.W * c.Cin;
                 L.out_elems = (int64_t)c.Ho * c.Wo * c.Cout;
                 L.w_count = (int64_t)c.Cout * c.R * c.S * c.Cin; L.b_count = c.Cout;
                 const int64_t kf = (int64_t)c.R * c.S * c.Cin, kd = (int64_t)c.R * c.S * c.Cout;
-                L.ws_elems = std::max({gemm_workspace_elems((int64_t)cfg->micro_batch * c.Ho * c.Wo, c.Cout, kf, 0),
+                L.ws_elems = std::max({gemm_workspace_elems((int64_t)mb * c.Ho * c.Wo, c.Cout, kf, 0),
                                        gemm_workspace_elems((int64_t)M * c.H * c.W, c.Cin, kd, 0),
                                        gemm_workspace_elems(c.Cout, kf, (int64_t)M * c.Ho * c.Wo, 1)});
                 break;
@@ -102,17 +128,48 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                 int Ho = (d[0] - d[3]) / d[4] + 1, Wo = (d[1] - d[3]) / d[4] + 1;
                 L.in_elems = (int64_t)d[0] * d[1] * d[2];
                 L.out_elems = (int64_t)Ho * Wo * d[2];
-                L.relu = false;
+                L.relu = false; L.act = 0;
                 break;
             }
+            case TMPS_LAYERNORM:
+                if (d[0] < 1 || d[1] < 0) return fail(TMPS_EINVAL, "layer %d: bad layer-normalisation dims", i);
+                L.rps = d[1] > 0 ? d[1] : 1;
+                L.in_elems = L.out_elems = (int64_t)L.rps * d[0];
+                L.w_count = d[0]; L.b_count = d[0];
+                L.relu = false; L.act = 0;
+                L.ws_elems = layernorm_workspace_elems((int64_t)M * L.rps, d[0]);
+                break;
+            case TMPS_ATTENTION:
+                if (d[0] < 1 || d[1] < 1 || d[2] < 1 || d[1] % d[2] != 0)
+                    return fail(TMPS_EINVAL, "layer %d: attention needs S, D, heads positive and D a multiple of heads", i);
+                L.rps = d[0];
+                L.in_elems = (int64_t)d[0] * 3 * d[1];
+                L.out_elems = (int64_t)d[0] * d[1];
+                L.relu = false; L.act = 0;
+                L.ws_elems = attention_workspace_elems(M, d[0], d[2]);
+                break;
+            case TMPS_EMBEDDING:
+                if (i != 0) return fail(TMPS_ESHAPE, "an embedding can only be the first layer of a stage");
+                if (d[0] < 1 || d[1] < 1 || d[2] < 1) return fail(TMPS_EINVAL, "layer %d: embedding dims must be positive", i);
+                L.rps = d[1];
+                L.in_elems = d[1];
+                L.out_elems = (int64_t)d[1] * d[2];
+                L.w_count = (int64_t)d[0] * d[2]; L.b_count = (int64_t)d[1] * d[2];
+                L.relu = false; L.act = 0;
+                st.in_esize = 4;
+                break;
             case TMPS_SOFTMAX_CE:
                 if (i != n_layers - 1 || !cfg->is_last || i == 0)
                     return fail(TMPS_ESHAPE, "softmax-CE must be the last layer of the last stage, after another layer");
-                if (d[0] < 1) return fail(TMPS_EINVAL, "layer %d: classes must be positive", i);
-                if (st.layers.back().d.kind != TMPS_LINEAR || st.layers.back().relu)
-                    return fail(TMPS_EUNSUPPORTED, "softmax-CE must follow a linear layer without ReLU");
-                L.in_elems = L.out_elems = d[0];
-                L.relu = false;
+                if (d[0] < 1 || d[1] < 0) return fail(TMPS_EINVAL, "layer %d: classes must be positive", i);
+                if (st.layers.back().d.kind != TMPS_LINEAR || st.layers.back().act != 0 || st.layers.back().skip)
+                    return fail(TMPS_EUNSUPPORTED, "softmax-CE must follow a plain linear layer");
+                L.rps = d[1] > 0 ? d[1] : 1;
+                if (st.layers.back().rps != L.rps)
+                    return fail(TMPS_ESHAPE, "softmax-CE has %d rows per sample, the layer before it %d", L.rps, st.layers.back().rps);
+                L.in_elems = L.out_elems = (int64_t)L.rps * d[0];
+                L.relu = false; L.act = 0;
+                st.label_rps = L.rps;
                 break;
             default:
                 return fail(TMPS_EUNSUPPORTED, "layer %d: kind %d not built", i, L.d.kind);
@@ -126,36 +183,49 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
             L.b_off = poff + L.w_count;
             poff = (int64_t)align_up((size_t)(L.b_off + L.b_count), 64);
         }
-        max_elems = std::max(max_elems, std::max(L.in_elems, L.out_elems));
+        // the gradient w.r.t. this layer's input lives in a gradient buffer (the loss layer's is kept in the stash)
+        if (i > 0 && L.d.kind != TMPS_SOFTMAX_CE) gmax = std::max(gmax, L.in_elems);
         ws = std::max(ws, L.ws_elems);
         st.layers.push_back(L);
     }
     if (cfg->is_last && st.layers.back().d.kind != TMPS_SOFTMAX_CE)
         return fail(TMPS_ESHAPE, "the last stage must end in softmax-CE");
     if (cfg->is_last) st.layers[n_layers - 2].out_f32 = true;
+    if (!cfg->is_last) {
+        if (st.layers.back().act == 2) return fail(TMPS_EUNSUPPORTED, "a stage cannot end in a GELU layer");
+        if (st.layers.back().relu) gmax = std::max(gmax, st.layers.back().out_elems);
+    }
     st.P = poff;
     st.in_elems = st.layers.front().in_elems;
     st.out_elems = cfg->is_last ? st.layers[n_layers - 2].out_elems : st.layers.back().out_elems;
 
-    // stash: [copied inputs] then every layer's output array over all slots
+    // stash: [copied inputs] then every layer's output array over all slots, and what else the backward pass needs
     st.in_off = 0;
-    if (!cfg->borrow_input) soff = align_up((size_t)rows_all * st.in_elems * st.asz, 256);
+    if (!cfg->borrow_input) soff = align_up((size_t)rows_all * st.in_elems * st.in_esize, 256);
     for (LayerRT& L : st.layers) {
         L.out_off = soff;
         L.out_esize = L.out_f32 ? 4 : st.asz;
         soff = align_up(soff + (size_t)rows_all * L.out_elems * L.out_esize, 256);
-        if (L.d.kind == TMPS_SOFTMAX_CE) {
+        size_t aux = 0;
+        if (L.d.kind == TMPS_SOFTMAX_CE) aux = (size_t)rows_all * L.rps * 4;                  // per-row losses
+        if (L.d.kind == TMPS_LAYERNORM) aux = (size_t)rows_all * L.rps * 8;                   // (mean, 1/std) per row
+        if (L.d.kind == TMPS_ATTENTION) aux = (size_t)rows_all * L.d.dims[2] * L.d.dims[0] * 4;  // log-sum-exp per head and query
+        if (aux) {
             L.aux_off = soff;
-            soff = align_up(soff + (size_t)rows_all * 4, 256);
+            soff = align_up(soff + aux, 256);
+        }
+        if (L.act == 2) {
+            L.z_off = soff;
+            soff = align_up(soff + (size_t)rows_all * L.out_elems * st.asz, 256);
         }
     }
     st.stash_bytes = soff;
 
-    // scratch: two gradient buffers of M rows, two boundary-gradient buffers, split-K workspace
+    // scratch: gradient buffers of M rows, two boundary-gradient buffers, fp32 workspace
     size_t o = 0;
-    st.gbuf_bytes = align_up((size_t)M * max_elems * st.asz, 256);
-    st.gbuf_off[0] = o; o += st.gbuf_bytes;
-    st.gbuf_off[1] = o; o += st.gbuf_bytes;
+    st.n_gbuf = any_skip ? 4 : 2;
+    st.gbuf_bytes = align_up((size_t)M * std::max<int64_t>(gmax, 1) * st.asz, 256);
+    for (int k = 0; k < st.n_gbuf; ++k) { st.gbuf_off[k] = o; o += st.gbuf_bytes; }
     st.dxout_bytes = align_up((size_t)M * st.in_elems * st.asz, 256);
     st.dxout_off[0] = o; o += st.dxout_bytes;
     st.dxout_off[1] = o; o += st.dxout_bytes;
@@ -168,7 +238,7 @@ void* stage_dxout(tmps_stage* st, int which) { return st->scratch + st->dxout_of
 
 float* stage_row_loss(tmps_stage* st, int slot) {
     const LayerRT& L = st->layers.back();
-    return reinterpret_cast<float*>(st->stash + L.aux_off) + (size_t)slot * st->cfg.micro_batch;
+    return reinterpret_cast<float*>(st->stash + L.aux_off) + (size_t)slot * st->cfg.micro_batch * L.rps;
 }
 
 }  // namespace tmps
@@ -246,6 +316,11 @@ extern "C" void* tmps_stage_output_ptr(const tmps_stage* stage, int slot) {
     return stage->out_ptr(L, (int64_t)slot * stage->cfg.micro_batch);
 }
 
+// what layer li reads: the stage input (x0, rows from row0 on) or the stashed output of the layer before it
+static const void* layer_input(const tmps_stage* st, int li, const void* x0, int64_t row0) {
+    return li == 0 ? x0 : (const void*)st->out_ptr(st->layers[li - 1], row0);
+}
+
 extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void* y, const int32_t* labels,
                                   float* loss_out, void* hip_stream) {
     if (!st || !x) return fail(TMPS_EINVAL, "stage or x is null");
@@ -256,32 +331,57 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
     const int mb = st->cfg.micro_batch;
     const int dt = st->cfg.dtype;
     const int64_t row0 = (int64_t)slot * mb;
-    const void* in = x;
+    const void* x0 = x;
     float* ws = reinterpret_cast<float*>(st->scratch + st->ws_off);
     if (!st->cfg.borrow_input) {
-        char* dst = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->asz;
-        TMPS_RUN(kcCopy, s, hipMemcpyAsync(dst, x, (size_t)mb * st->in_elems * st->asz, hipMemcpyDeviceToDevice, s));
-        in = dst;
+        char* dst = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->in_esize;
+        TMPS_RUN(kcCopy, s, hipMemcpyAsync(dst, x, (size_t)mb * st->in_elems * st->in_esize, hipMemcpyDeviceToDevice, s));
+        x0 = dst;
     }
     st->slot_x[slot] = x;
+    const void* in = x0;
     for (size_t li = 0; li < st->layers.size(); ++li) {
         const LayerRT& L = st->layers[li];
         void* out = st->out_ptr(L, row0);
         const int32_t* d = L.d.dims;
         switch (L.d.kind) {
-            case TMPS_LINEAR:
-                TMPS_GEMM(dense_forward(dt, in, st->wptr(L), st->bptr(L), out, mb, d[0], d[1], L.relu, L.out_f32, ws, s));
+            case TMPS_LINEAR: {
+                const void* res = nullptr;
+                if (L.skip) {
+                    const int src = (int)li - L.skip;
+                    res = src == 0 ? x0 : (const void*)st->out_ptr(st->layers[src - 1], row0);
+                }
+                void* zout = L.act == 2 ? (void*)(st->stash + L.z_off + (size_t)row0 * L.out_elems * st->asz) : nullptr;
+                TMPS_GEMM(dense_forward(dt, in, st->wptr(L), st->bptr(L), out, mb * L.rps, d[0], d[1], L.act, L.out_f32, res,
+                                        zout, ws, s));
                 break;
+            }
             case TMPS_CONV2D:
                 TMPS_GEMM(conv_forward(dt, in, st->wptr(L), st->bptr(L), out, conv_shape(L.d, mb), L.relu, ws, s));
                 break;
             case TMPS_MAXPOOL:
                 TMPS_RUN(kcPoolFwd, s, maxpool_forward(dt, in, out, mb, d[0], d[1], d[2], d[3], d[4], s));
                 break;
+            case TMPS_LAYERNORM:
+                TMPS_GEMM(layernorm_forward(dt, in, st->master + L.w_off, st->master + L.b_off, out,
+                                            reinterpret_cast<float*>(st->stash + L.aux_off) + (size_t)row0 * L.rps * 2,
+                                            (int64_t)mb * L.rps, d[0], 1e-5f, s));
+                break;
+            case TMPS_ATTENTION:
+                TMPS_GEMM(attention_forward(dt, in, out,
+                                            reinterpret_cast<float*>(st->stash + L.aux_off) + (size_t)row0 * d[2] * d[0], mb,
+                                            d[0], d[1], d[2], s));
+                break;
+            case TMPS_EMBEDDING:
+                TMPS_GEMM(embedding_forward(dt, (const int32_t*)in, st->wptr(L), st->bptr_c(L), out, (int64_t)mb * d[1], d[1],
+                                            d[2], d[0], s));
+                break;
             case TMPS_SOFTMAX_CE: {
                 float* rl = stage_row_loss(st, slot);
-                TMPS_RUN(kcSoftmaxCE, s, softmax_ce(dt, (const float*)in, labels, out, rl, mb, d[0], 1.0f / (float)st->M(), s));
-                if (loss_out) TMPS_RUN(kcReduce, s, reduce_scaled_sum(rl, mb, 1.0f / (float)mb, loss_out, s));
+                const int rows = mb * L.rps;
+                TMPS_RUN(kcSoftmaxCE, s, softmax_ce(dt, (const float*)in, labels, out, rl, rows, d[0],
+                                                    1.0f / ((float)st->M() * (float)L.rps), s));
+                if (loss_out) TMPS_RUN(kcReduce, s, reduce_scaled_sum(rl, rows, 1.0f / (float)rows, loss_out, s));
                 break;
             }
         }
@@ -317,19 +417,34 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
     const char* x0;
     if (st->cfg.borrow_input) {
         x0 = (const char*)st->slot_x[g0];
-        const size_t step = (size_t)mb * st->in_elems * st->asz;
+        const size_t step = (size_t)mb * st->in_elems * st->in_esize;
         for (int j = 1; j < N; ++j)
             if ((const char*)st->slot_x[g0 + j] != x0 + j * step)
                 return fail(TMPS_ESHAPE, "borrowed inputs of a mini-batch must be consecutive in memory");
     } else {
-        x0 = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->asz;
+        x0 = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->in_esize;
     }
 
-    char* gbuf[2] = {st->scratch + st->gbuf_off[0], st->scratch + st->gbuf_off[1]};
+    // Gradient buffers: the gradient w.r.t. a layer's output is read while the one w.r.t. its input is written;
+    // the gradient entering a residual layer is kept until the layer at the start of the connection has added it.
+    char* gbuf[4];
+    bool busy[4] = {false, false, false, false};
+    for (int k = 0; k < st->n_gbuf; ++k) gbuf[k] = st->scratch + st->gbuf_off[k];
+    auto take = [&]() -> int {
+        for (int k = 0; k < st->n_gbuf; ++k)
+            if (!busy[k]) {
+                busy[k] = true;
+                return k;
+            }
+        return -1;
+    };
+    const int nl = (int)st->layers.size();
+    std::vector<const void*> held(nl, nullptr);   // by the layer whose input gradient it is added to
+    std::vector<int> held_buf(nl, -1);
     float* ws = reinterpret_cast<float*>(st->scratch + st->ws_off);
-    int cur = -1;  // which gbuf holds g, -1: external memory
+    int cur = -1;  // which buffer holds g, -1: memory that is not ours
     const void* g;
-    int top = (int)st->layers.size() - 1;
+    int top = nl - 1;
     if (st->cfg.is_last) {
         g = st->out_ptr(st->layers[top], row0);  // softmax error signal stored by the forward passes
         --top;
@@ -337,27 +452,53 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         g = dy;
         const LayerRT& T = st->layers[top];
         if (T.relu) {
-            TMPS_RUN(kcReluMask, s, relu_mask(dt, dy, st->out_ptr(T, row0), gbuf[0], (int64_t)M * T.out_elems, s));
-            g = gbuf[0];
-            cur = 0;
+            cur = take();
+            TMPS_RUN(kcReluMask, s, relu_mask(dt, dy, st->out_ptr(T, row0), gbuf[cur], (int64_t)M * T.out_elems, s));
+            g = gbuf[cur];
         }
     }
     for (int li = top; li >= 0; --li) {
         const LayerRT& L = st->layers[li];
         const int32_t* d = L.d.dims;
-        const void* in = li == 0 ? (const void*)x0 : (const void*)st->out_ptr(st->layers[li - 1], row0);
-        const bool want_dx = li > 0 || dx != nullptr;
+        const void* in = layer_input(st, li, x0, row0);
+        const bool want_dx = (li > 0 || dx != nullptr) && L.d.kind != TMPS_EMBEDDING;
         void* dst = nullptr;
-        if (want_dx) dst = li == 0 ? dx : (void*)gbuf[cur == 0 ? 1 : 0];
-        // the gradient written for the layer below is masked by that layer's ReLU output
-        const bool below_relu = li > 0 && st->layers[li - 1].relu;
-        const void* mask = below_relu ? in : nullptr;
+        int dst_buf = -1;
+        if (want_dx) {
+            if (li == 0) {
+                dst = dx;
+            } else {
+                dst_buf = take();
+                if (dst_buf < 0) return fail(TMPS_EUNSUPPORTED, "out of gradient buffers (nested residual connections)");
+                dst = gbuf[dst_buf];
+            }
+        }
+        // the gradient written for the layer below passes through that layer's stored activation
+        const void* mask = nullptr;
+        int mask_mode = 1;
+        if (li > 0) {
+            const LayerRT& Bl = st->layers[li - 1];
+            if (Bl.act == 1) mask = in;
+            if (Bl.act == 2) {
+                mask = st->stash + Bl.z_off + (size_t)row0 * Bl.out_elems * st->asz;
+                mask_mode = 2;
+            }
+        }
         float* gw = st->grad + L.w_off;
+        bool keep_g = false;
+        if (held[li] && L.d.kind != TMPS_LAYERNORM) return fail(TMPS_EUNSUPPORTED, "residual connection into layer kind %d", L.d.kind);
         switch (L.d.kind) {
-            case TMPS_LINEAR:
-                TMPS_GEMM(dense_wgrad(dt, g, in, gw, M, d[0], d[1], ws, s));
-                if (want_dx) TMPS_GEMM(dense_dgrad(dt, g, st->wptr(L), dst, mask, M, d[0], d[1], ws, s));
+            case TMPS_LINEAR: {
+                const int rows = M * L.rps;
+                if (L.skip) {
+                    held[li - L.skip] = g;
+                    held_buf[li - L.skip] = cur;
+                    keep_g = true;
+                }
+                TMPS_GEMM(dense_wgrad(dt, g, in, gw, rows, d[0], d[1], ws, s));
+                if (want_dx) TMPS_GEMM(dense_dgrad(dt, g, st->wptr(L), dst, mask, mask_mode, rows, d[0], d[1], ws, s));
                 break;
+            }
             case TMPS_CONV2D: {
                 ConvShape c = conv_shape(L.d, M);
                 TMPS_GEMM(conv_wgrad(dt, g, in, gw, c, ws, s));
@@ -366,13 +507,32 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
             }
             case TMPS_MAXPOOL:
                 if (want_dx)
-                    TMPS_RUN(kcPoolBwd, s, maxpool_backward(dt, in, g, dst, M, d[0], d[1], d[2], d[3], d[4], below_relu ? 1 : 0, s));
+                    TMPS_RUN(kcPoolBwd, s, maxpool_backward(dt, in, g, dst, M, d[0], d[1], d[2], d[3], d[4], mask ? 1 : 0, s));
+                break;
+            case TMPS_LAYERNORM:
+                if (mask) return fail(TMPS_EUNSUPPORTED, "layer normalisation directly after an activation");
+                TMPS_GEMM(layernorm_backward(dt, g, in, reinterpret_cast<const float*>(st->stash + L.aux_off) + (size_t)row0 * L.rps * 2,
+                                             st->master + L.w_off, held[li], want_dx ? dst : nullptr, gw, ws, (int64_t)M * L.rps,
+                                             d[0], s));
+                if (held_buf[li] >= 0) busy[held_buf[li]] = false;
+                held[li] = nullptr;
+                break;
+            case TMPS_ATTENTION:
+                if (mask) return fail(TMPS_EUNSUPPORTED, "attention directly after an activation");
+                if (want_dx)
+                    TMPS_GEMM(attention_backward(dt, in, st->out_ptr(L, row0), g,
+                                                 reinterpret_cast<const float*>(st->stash + L.aux_off) + (size_t)row0 * d[2] * d[0], ws,
+                                                 dst, M, d[0], d[1], d[2], s));
+                break;
+            case TMPS_EMBEDDING:
+                TMPS_GEMM(embedding_backward(dt, (const int32_t*)in, g, gw, st->grad + L.b_off, M, d[1], d[2], d[0], s));
                 break;
             default:
                 return fail(TMPS_EUNSUPPORTED, "layer kind %d has no backward", L.d.kind);
         }
+        if (cur >= 0 && !keep_g) busy[cur] = false;
         if (want_dx && li > 0) {
-            cur = cur == 0 ? 1 : 0;
+            cur = dst_buf;
             g = dst;
         }
     }

@@ -12,9 +12,13 @@ struct LayerRT {
     size_t out_off = 0;    // stash byte offset of this layer's output array (all slots)
     size_t out_esize = 0;  // bytes per element of that array
     size_t aux_off = 0;    // softmax-CE: stash byte offset of the per-row losses (fp32)
+    size_t z_off = 0;      // GELU linear: stash byte offset of the stored pre-activations
     bool relu = false;
+    int act = 0;           // 0 none, 1 ReLU, 2 GELU (linear / convolution epilogue)
+    int rps = 1;           // rows per sample the layer works on (sequence positions)
+    int skip = 0;          // linear: > 0 adds the input of layer (index - skip)
     bool out_f32 = false;  // the logits layer (followed by softmax-CE) writes fp32
-    size_t ws_elems = 0;   // split-K workspace of the weight-gradient GEMM (fp32 elements)
+    size_t ws_elems = 0;   // fp32 workspace elements (split-k partial sums, reductions)
 };
 
 struct tmps_stage {
@@ -23,6 +27,9 @@ struct tmps_stage {
     int64_t P = 0;  // flat parameter count (with alignment gaps)
     int64_t in_elems = 0, out_elems = 0;
     size_t asz = 4;  // bytes per activation / gradient element
+    size_t in_esize = 4;  // bytes per element of the stage input (int32 tokens in front of an embedding)
+    int label_rps = 1;    // labels per sample on the last stage
+    int n_gbuf = 2;       // gradient buffers in scratch
     char* params = nullptr;
     char* state = nullptr;
     char* stash = nullptr;
@@ -33,7 +40,7 @@ struct tmps_stage {
     float* grad = nullptr;
     size_t in_off = 0;  // stash offset of the copied inputs (borrow_input == 0)
     size_t stash_bytes = 0, scratch_bytes = 0;
-    size_t gbuf_off[2] = {0, 0}, gbuf_bytes = 0;  // gradient ping-pong buffers (M rows)
+    size_t gbuf_off[4] = {0, 0, 0, 0}, gbuf_bytes = 0;  // gradient buffers (M rows each)
     size_t dxout_off[2] = {0, 0}, dxout_bytes = 0;  // boundary gradient buffers used by the scheduler
     size_t ws_off = 0;
     std::vector<char> slot_used;
@@ -46,6 +53,10 @@ struct tmps_stage {
         return wcopy ? (const void*)((const char*)wcopy + L.w_off * 2) : (const void*)(master + L.w_off);
     }
     const float* bptr(const LayerRT& L) const { return master + L.b_off; }
+    // second parameter array in the contraction dtype (position table of an embedding)
+    const void* bptr_c(const LayerRT& L) const {
+        return wcopy ? (const void*)((const char*)wcopy + L.b_off * 2) : (const void*)(master + L.b_off);
+    }
     char* out_ptr(const LayerRT& L, int64_t row) const {
         return stash + L.out_off + (size_t)row * L.out_elems * L.out_esize;
     }

@@ -24,7 +24,13 @@ def _params(specs, rng, scale=1.0):
     for sp in specs:
         shp = param_shapes(sp)
         p = {}
-        if shp:
+        if shp and sp["kind"] == "layernorm":
+            p["w"] = (1.0 + 0.2 * rng.standard_normal(shp["w"])).astype(np.float32)
+            p["b"] = (0.1 * rng.standard_normal(shp["b"])).astype(np.float32)
+        elif shp and sp["kind"] == "embedding":
+            p["w"] = (0.5 * rng.standard_normal(shp["w"])).astype(np.float32)
+            p["b"] = (0.5 * rng.standard_normal(shp["b"])).astype(np.float32)
+        elif shp:
             fan = np.prod(shp["w"][1:])
             p["w"] = (rng.standard_normal(shp["w"]) * np.sqrt(2.0 / fan) * scale).astype(np.float32)
             p["b"] = (rng.standard_normal(shp["b"]) * 0.1).astype(np.float32)
@@ -34,7 +40,13 @@ def _params(specs, rng, scale=1.0):
 
 def _in_shape(sp):
     if sp["kind"] == "linear":
-        return (sp["din"],)
+        return (sp.get("rows", 1) * sp["din"],)
+    if sp["kind"] == "layernorm":
+        return (sp["rows"] * sp["d"],)
+    if sp["kind"] == "attention":
+        return (sp["s"] * 3 * sp["d"],)
+    if sp["kind"] == "embedding":
+        return (sp["s"],)
     if sp["kind"] == "conv":
         return (sp["h"], sp["w"], sp["cin"])
     if sp["kind"] == "maxpool":
@@ -53,10 +65,15 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False):
     p0 = _params(specs, rng)
     p1 = [{k: (v + 0.05 * np.abs(v).max() * rng.standard_normal(v.shape)).astype(np.float32) for k, v in p.items()}
           for p in p0]
-    x = rng.standard_normal((M,) + _in_shape(specs[0])).astype(np.float32)
-    if dtype == "bf16":
-        x = to_bf16_grid(x)
-    labels = rng.integers(0, specs[-1].get("classes", 2), M).astype(np.int32)
+    tokens_in = specs[0]["kind"] == "embedding"
+    if tokens_in:
+        x = rng.integers(0, specs[0]["vocab"], (M,) + _in_shape(specs[0])).astype(np.int32)
+    else:
+        x = rng.standard_normal((M,) + _in_shape(specs[0])).astype(np.float32)
+        if dtype == "bf16":
+            x = to_bf16_grid(x)
+    lrows = specs[-1].get("rows", 1)
+    labels = rng.integers(0, specs[-1].get("classes", 2), (M, lrows) if lrows > 1 else M).astype(np.int32)
     lr, mu = 0.05, 0.9
 
     ost = OStage(specs, p0, lr, mu, M, N, precision="bf16" if dtype == "bf16" else "f64")
@@ -97,12 +114,16 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False):
         if dtype == "bf16":
             dy = to_bf16_grid(dy)
         dyd = torch.from_numpy(dy).to(adt).to(dev)
-    dxd = torch.empty(M * gst.in_elems, dtype=adt, device=dev)
+    dxd = None if tokens_in else torch.empty(M * gst.in_elems, dtype=adt, device=dev)
     gst.backward(list(range(base, base + N)), dy=dyd, dx=dxd)
     torch.cuda.synchronize()
     o_dx = ost.backward(list(range(N)), dy)
-    got_dx = gst.crop_input_grad(dxd, M).reshape(o_dx.shape)
-    if has_pool and dtype == "bf16":
+    if tokens_in:
+        assert o_dx is None
+    got_dx = None if tokens_in else gst.crop_input_grad(dxd, M).reshape(o_dx.shape)
+    if tokens_in:
+        pass
+    elif has_pool and dtype == "bf16":
         # near-ties of a pooling window can be won by a different element in bf16 than in fp64: such
         # isolated reroutings are valid; everything else must agree
         assert frac_outside(got_dx, o_dx, tol) < 2e-3 and rel_l2(got_dx, o_dx) < 2 * tol
