@@ -43,12 +43,32 @@ def algorithmic_work(cfg):
         P = 0
         for li, sp in enumerate(st):
             if sp["kind"] == "linear":
-                din, dout = sp["din"], sp["dout"]
+                din, dout, rows = sp["din"], sp["dout"], sp.get("rows", 1)
                 P += din * dout + dout
-                add("dense_fwd", N, N * 2.0 * mb * din * dout, N * (mb * din * asz + din * dout * asz + mb * dout * asz))
-                add("dense_wgrad", 1, 2.0 * M * din * dout, M * (din + dout) * asz + (din * dout + dout) * 4)
+                rf, rb = mb * rows, M * rows        # GEMM rows of a forward pass and of the backward pass
+                osz = 4 if (li + 1 < len(st) and st[li + 1]["kind"] == "softmax_ce") else asz
+                extra = (1 if sp.get("skip") else 0) + (1 if sp.get("act") == "gelu" else 0)   # residual read, z write
+                add("dense_fwd", N, N * 2.0 * rf * din * dout,
+                    N * (rf * din * asz + din * dout * asz + rf * dout * (osz + extra * asz)))
+                add("dense_wgrad", 1, 2.0 * rb * din * dout, rb * (din + dout) * asz + (din * dout + dout) * 4)
                 if not (si == 0 and li == 0):
-                    add("dense_dgrad", 1, 2.0 * M * din * dout, M * (din + dout) * asz + din * dout * asz)
+                    add("dense_dgrad", 1, 2.0 * rb * din * dout, rb * (din + dout) * asz + din * dout * asz)
+            elif sp["kind"] == "layernorm":
+                d, rows = sp["d"], sp["rows"]
+                P += 2 * d
+                # forward: read x, write y (+ statistics); backward: read dy, x (+ joined residual gradient), write dx
+                add("layernorm", N + 3, 0.0, N * mb * rows * (2 * d * asz + 8) + M * rows * (4 * d * asz + 8) + M * rows * 2 * d * asz)
+            elif sp["kind"] == "attention":
+                s_, d, h = sp["s"], sp["d"], sp["heads"]
+                dh = d // h
+                pairs = s_ * (s_ + 1) // 2          # causal: query i sees keys 0..i
+                # forward: QK^T and PV; backward: QK^T, dO V^T, dV, dQ, dK: 2 and 5 products of 2*dh FLOPs per (query, key)
+                add("attn_fwd", N, N * mb * h * pairs * 2.0 * dh * 2, N * mb * s_ * (4 * d * asz + h * 4))
+                add("attn_bwd", 3, M * h * pairs * 2.0 * dh * 5, M * s_ * (8 * d * asz + 3 * h * 4))
+            elif sp["kind"] == "embedding":
+                v, s_, d = sp["vocab"], sp["s"], sp["d"]
+                P += v * d + s_ * d
+                add("embedding", N + 3, 0.0, N * mb * s_ * (4 + 2 * d * asz) + v * d * 4 + M * s_ * (d * asz + 4 + 8 * d) + s_ * d * 4)
             elif sp["kind"] == "conv":
                 ho = (sp["h"] + 2 * sp["pad"] - sp["r"]) // sp["stride"] + 1
                 wo = (sp["w"] + 2 * sp["pad"] - sp["s"]) // sp["stride"] + 1
@@ -65,15 +85,15 @@ def algorithmic_work(cfg):
                 add("pool_fwd", N, 0.0, N * mb * (x_e + y_e) * asz)
                 add("pool_bwd", 1, 0.0, M * (2 * x_e + y_e) * asz)
             elif sp["kind"] == "softmax_ce":
-                c = sp["classes"]
-                add("softmax_ce", N, 0.0, N * mb * (c * 4 + c * asz + 8))
+                c, rows = sp["classes"], sp.get("rows", 1)
+                add("softmax_ce", N, 0.0, N * mb * rows * (c * 4 + c * asz + 8))
         add("update", 1, 0.0, P * (22 if cfg.dtype == "bf16" else 20))
     return work
 
 
 # classes whose kernels carry their own start/stop timestamps (no bracket overhead)
 KERNEL_STAMPED = ("dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "splitk_finish",
-                  "slice_sum")
+                  "slice_sum", "layernorm", "attn_fwd", "attn_bwd", "embedding")
 
 
 def measured_traffic(workload, kernel_class):
@@ -97,6 +117,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="vgg16_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="issue all K workers on one stream (no overlap between kernels): a diagnostic, not the metric")
     ap.add_argument("--cpu-steps", type=int, default=0, help="mini-batches the oracle is timed on (0: about 15 s worth)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy kernel (reference for scaling HBM byte counters)")
@@ -122,7 +144,7 @@ def main():
         del src, dst
     cfg = get_config(args.workload)
     params = init_params(cfg)
-    pipe = T.Pipeline(cfg, params)
+    pipe = T.Pipeline(cfg, params, one_stream=args.one_stream)
     n_distinct = min(32, max(args.steps, args.warmup, 1))
     distinct = [make_batch(cfg, i) for i in range(n_distinct)]
 
@@ -171,7 +193,7 @@ def main():
         kernels.append(ent)
     kernels.sort(key=lambda e: -e["ms_per_step"])
     dom = kernels[0]
-    if dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce"):
+    if dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce", "layernorm", "embedding"):
         roof = {"kernel": dom["class"], "bound": "hbm", "achieved": dom.get("gbs", 0.0), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": dom.get("gbs", 0.0) / HBM_PEAK_GBS, "traffic": None}
     else:
@@ -183,23 +205,51 @@ def main():
     roof["event_pair_us_subtracted"] = pair_us
     roof["traffic"] = measured_traffic(cfg.name, dom["class"])
 
+    flops_step = sum(v[1] for v in work.values())
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import pipeline as opipe
         cores = len(os.sched_getaffinity(0))
-        n_cpu = args.cpu_steps
-        if n_cpu <= 0:
+        if flops_step > 1e12 and args.cpu_steps <= 0:
+            # A whole mini-batch through the fp64 oracle would take minutes: time ONE stage's step instead
+            # (N micro-batch forward passes, the backward pass, the update) on an inner stage of the same
+            # workload, fed Gaussian activations of that stage's input shape.
+            from oracle.stage import Stage as OStage
+            from workloads.configs import stage_shapes
+            from workloads import to_bf16_grid
+            si = 1 if cfg.K > 2 else 0
+            in_shape, out_shape = stage_shapes(cfg)[si]
+            rng = np.random.default_rng(cfg.seed)
+            if si == 0 and cfg.vocab:
+                xin = distinct[0][0]
+            else:
+                xin = to_bf16_grid(rng.standard_normal((cfg.M, int(np.prod(in_shape)))).astype(np.float32))
+            dy = to_bf16_grid((rng.standard_normal((cfg.M, int(np.prod(out_shape)))) / cfg.M).astype(np.float32))
+            ost = OStage(cfg.stages[si], params[si], cfg.lr, cfg.momentum, cfg.M, cfg.N,
+                         precision="bf16" if cfg.dtype == "bf16" else "f64")
             t1 = time.perf_counter()
-            opipe.run(cfg, params, distinct[:2])
-            per = (time.perf_counter() - t1) / 2
-            n_cpu = int(max(2, min(n_distinct, 15.0 / max(per, 1e-3))))
-        t1 = time.perf_counter()
-        opipe.run(cfg, params, distinct[:n_cpu])
-        dc = time.perf_counter() - t1
-        cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
-               "sample": "%d mini-batches of the same workload through the numpy fp64 oracle pipeline (%.1f s)" % (n_cpu, dc)}
+            for j in range(cfg.N):
+                ost.forward_micro(j, xin[j * cfg.micro:(j + 1) * cfg.micro])
+            ost.backward(list(range(cfg.N)), dy)
+            ost.update()
+            dc = time.perf_counter() - t1
+            cpu = {"value": cfg.M / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
+                   "sample": "one training step (N forward passes, backward pass, update) of stage %d of %d alone (its "
+                             "layers only: samples/s of that stage, not of the whole pipeline) through the numpy fp64 "
+                             "oracle (%.1f s)" % (si, cfg.K, dc)}
+        else:
+            from oracle import pipeline as opipe
+            n_cpu = args.cpu_steps
+            if n_cpu <= 0:
+                t1 = time.perf_counter()
+                opipe.run(cfg, params, distinct[:2])
+                per = (time.perf_counter() - t1) / 2
+                n_cpu = int(max(2, min(n_distinct, 15.0 / max(per, 1e-3))))
+            t1 = time.perf_counter()
+            opipe.run(cfg, params, distinct[:n_cpu])
+            dc = time.perf_counter() - t1
+            cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
+                   "sample": "%d mini-batches of the same workload through the numpy fp64 oracle pipeline (%.1f s)" % (n_cpu, dc)}
 
-    flops_step = sum(v[1] for v in work.values())
     out = {
         "metric": "training samples/sec (all K stages, nF1B) on 1 MI355X",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

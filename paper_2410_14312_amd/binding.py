@@ -308,7 +308,7 @@ class Stage:
 class Pipeline:
     """K stages of a workloads.Config on K streams of one GPU, run in nF1B order by tmps_schedule_run."""
 
-    def __init__(self, cfg, params, device="cuda:0", extra_groups=0):
+    def __init__(self, cfg, params, device="cuda:0", extra_groups=0, one_stream=False):
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -321,7 +321,9 @@ class Pipeline:
                        borrow_input=True, device=device)
             st.set_params(params[s])
             self.stages.append(st)
-        self.streams = [torch.cuda.Stream(device=self.device) for _ in range(K)]
+        # one_stream: every worker issues on the same stream, so kernels never overlap (for per-kernel timing)
+        shared = torch.cuda.Stream(device=self.device) if one_stream else None
+        self.streams = [shared if one_stream else torch.cuda.Stream(device=self.device) for _ in range(K)]
         self.act_dtype = self.stages[0].act_dtype
 
     def upload(self, batches):

@@ -189,6 +189,28 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
 
 enum { kActNone = 0, kActRelu = 1, kActGelu = 2 };
 
+// 8 consecutive elements with 16-byte accesses (the address is 16-byte aligned)
+__device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
+    Pack8 pk;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pk.h[e] = (bf16_t)v[e];
+    *reinterpret_cast<uint4*>(p) = pk.u;
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
+    Pack8 pk;
+    pk.u = *reinterpret_cast<const uint4*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)pk.h[e];
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
 // out[m, n] = act(v + bias[n]) + res[m, n].  With GELU the pre-activation is also stored (zout), for the
 // derivative in the backward pass.  res: a residual connection's source, same shape as out.
 template <typename TOut> struct EpiBiasAct {
@@ -214,6 +236,30 @@ template <typename TOut> struct EpiBiasAct {
     // the same in two steps: column(n) fetches the bias once, at() finishes element idx = m*ld + n
     __device__ __forceinline__ float column(int n) const { return bias ? bias[n] : 0.0f; }
     __device__ __forceinline__ void at(float b, int64_t idx, float v, int) const { finish(idx, v + b); }
+    // 8 consecutive columns n..n+7 of one row (n and idx multiples of 8; bias, res, zout, out 16-byte aligned)
+    __device__ __forceinline__ void at8(int n, int64_t idx, float (&v)[8], int) const {
+        if (bias) {
+            float b[8];
+            load8(bias + n, b);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += b[e];
+        }
+        if (relu == kActRelu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+        } else if (relu == kActGelu) {
+            if (zout) store8(zout + idx, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+        }
+        if (res) {
+            float r[8];
+            load8(res + idx, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += r[e];
+        }
+        store8(out + idx, v);
+    }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 
@@ -235,6 +281,18 @@ template <typename TOut, typename TMask> struct EpiMask {
     __device__ __forceinline__ void operator()(int m, int n, float v, int) const { finish((int64_t)m * ld + n, v); }
     __device__ __forceinline__ int column(int) const { return 0; }
     __device__ __forceinline__ void at(int, int64_t i, float v, int) const { finish(i, v); }
+    __device__ __forceinline__ void at8(int, int64_t i, float (&v)[8], int) const {
+        if (mask) {
+            float t[8];
+            load8(mask + i, t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (mode == kActGelu) v[e] *= gelu_grad_f(t[e]);
+                else if (!(t[e] > 0.0f)) v[e] = 0.0f;
+            }
+        }
+        store8(out + i, v);
+    }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 
@@ -251,6 +309,9 @@ struct EpiWgrad {
     __device__ __forceinline__ int column(int) const { return 0; }
     __device__ __forceinline__ void at(int, int64_t idx, float v, int z) const {
         out[z * slice_stride + idx] = v;
+    }
+    __device__ __forceinline__ void at8(int, int64_t idx, float (&v)[8], int z) const {
+        store8(out + z * slice_stride + idx, v);
     }
     __device__ __forceinline__ void rowsum(int m, float v, int z) const {
         out[z * slice_stride + bias_off + m] = v;

@@ -506,6 +506,9 @@ struct EpiPartial {
     __device__ __forceinline__ void at(int, int64_t idx, float v, int z) const {
         part[z * slice_stride + idx] = v;
     }
+    __device__ __forceinline__ void at8(int, int64_t idx, float (&v)[8], int z) const {
+        store8(part + z * slice_stride + idx, v);
+    }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 

@@ -425,7 +425,9 @@ __global__ __launch_bounds__(64) void attn_bwd_kv_row_kernel(const T* __restrict
 }
 
 // ---------------------------------------------------------------------------- attention, MFMA path
-// bf16, 64 features per head.  LDS tiles are [64 rows][64 + 8] bf16 (144-byte rows).
+// bf16, 64 features per head.  LDS tiles are [64 rows][64 + 8] bf16 (144-byte rows).  Exponentials use the
+// hardware exp2 (a few ulp of fp32, far below the bf16 rounding of the results): the library expf costs some
+// 25 instructions and made the softmax, not the MFMAs, the bulk of these kernels.
 constexpr int kAP = 72;   // LDS row pitch in elements
 
 // B-operand / A-operand fragment of a row-major tile: lane holds row (lane % 32), 8 consecutive features
@@ -472,18 +474,44 @@ __device__ __forceinline__ void load_tile(bf16_t* tile, const bf16_t* base, int6
     }
 }
 
+// The same copy in two halves, so that the global loads of the next tile are in flight while the current one is
+// multiplied: fetch() issues the loads into registers, put() writes them to the LDS tile.
+template <int NT> struct TileFetch {
+    static constexpr int N = 512 / NT;
+    uint4 r[N];
+    __device__ __forceinline__ void fetch(const bf16_t* base, int64_t ld, int row0, int max_row, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = tid + i * NT;
+            int row = row0 + (c >> 3);
+            row = row < max_row ? row : max_row - 1;
+            r[i] = *reinterpret_cast<const uint4*>(base + row * ld + (c & 7) * 8);
+        }
+    }
+    __device__ __forceinline__ void put(bf16_t* tile, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = tid + i * NT;
+            *reinterpret_cast<uint4*>(tile + (c >> 3) * kAP + (c & 7) * 8) = r[i];
+        }
+    }
+};
+
 // Forward.  Block = NW waves = 32*NW query rows of one (batch, head).
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                                 float* __restrict__ lse, int S, int D, int H, float scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t sK[64 * kAP];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[64 * kAP];
+    __shared__ __attribute__((aligned(16))) bf16_t sKb[2][64 * kAP];
+    __shared__ __attribute__((aligned(16))) bf16_t sVb[2][64 * kAP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t ld = 3 * (int64_t)D;
     const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
     const int q0 = (qb * NW + wave) * 32;
     const int q = q0 + (lane & 31);
+    TileFetch<64 * NW> fk, fv;
+    fk.fetch(base + D, ld, 0, S, tid);
+    fv.fetch(base + 2 * D, ld, 0, S, tid);
     bf16x8_t qf[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) qf[t] = gfrag(base, ld, q0, S, t, lane);
@@ -494,11 +522,17 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
         for (int r = 0; r < 16; ++r) ot[i][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
     const int kv_end = min(S, (qb + 1) * NW * 32);
-    for (int kv0 = 0; kv0 < kv_end; kv0 += 64) {
-        __syncthreads();
-        load_tile<64 * NW>(sK, base + D, ld, kv0, S, tid);
-        load_tile<64 * NW>(sV, base + 2 * D, ld, kv0, S, tid);
-        __syncthreads();
+    fk.put(sKb[0], tid);
+    fv.put(sVb[0], tid);
+    __syncthreads();
+    for (int kv0 = 0, it = 0; kv0 < kv_end; kv0 += 64, ++it) {
+        const bf16_t* sK = sKb[it & 1];
+        const bf16_t* sV = sVb[it & 1];
+        const bool more = kv0 + 64 < kv_end;
+        if (more) {   // the next tile's loads fly while this one is multiplied
+            fk.fetch(base + D, ld, kv0 + 64, S, tid);
+            fv.fetch(base + 2 * D, ld, kv0 + 64, S, tid);
+        }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = kv0 + 32 * sub;
@@ -519,11 +553,11 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
             mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
             const float m_new = fmaxf(m_run, mt);
             const float m_use = m_new == -INFINITY ? 0.0f : m_new;   // a query with no key yet keeps zeros
-            const float alpha = expf(m_run - m_use);
+            const float alpha = __expf(m_run - m_use);
             float ls = 0.0f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                st[r] = expf(st[r] - m_use);
+                st[r] = __expf(st[r] - m_use);
                 ls += st[r];
             }
             l_run = l_run * alpha + ls;
@@ -540,6 +574,11 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
                     ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag_t(sV, 32 * sub + 16 * t, 32 * i, lane), pf, ot[i], 0, 0, 0);
             }
         }
+        if (more) {   // the other buffer was last read before the previous barrier
+            fk.put(sKb[(it + 1) & 1], tid);
+            fv.put(sVb[(it + 1) & 1], tid);
+        }
+        __syncthreads();
     }
     const float l = l_run + __shfl_xor(l_run, 32, 64);
     if (q < S) {
@@ -566,13 +605,16 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
                                                                   const float* __restrict__ delta,
                                                                   bf16_t* __restrict__ dqkv, int S, int D, int H,
                                                                   float scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t sK[64 * kAP];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[64 * kAP];
+    __shared__ __attribute__((aligned(16))) bf16_t sKb[2][64 * kAP];
+    __shared__ __attribute__((aligned(16))) bf16_t sVb[2][64 * kAP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t ld = 3 * (int64_t)D;
     const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
     const bf16_t* dob = dout + (int64_t)b * S * D + h * 64;
+    TileFetch<64 * NW> fk, fv;
+    fk.fetch(base + D, ld, 0, S, tid);
+    fv.fetch(base + 2 * D, ld, 0, S, tid);
     const int q0 = (qb * NW + wave) * 32;
     const int q = q0 + (lane & 31);
     const int qc = q < S ? q : S - 1;
@@ -589,11 +631,17 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[i][r] = 0.0f;
     const int kv_end = min(S, (qb + 1) * NW * 32);
-    for (int kv0 = 0; kv0 < kv_end; kv0 += 64) {
-        __syncthreads();
-        load_tile<64 * NW>(sK, base + D, ld, kv0, S, tid);
-        load_tile<64 * NW>(sV, base + 2 * D, ld, kv0, S, tid);
-        __syncthreads();
+    fk.put(sKb[0], tid);
+    fv.put(sVb[0], tid);
+    __syncthreads();
+    for (int kv0 = 0, it = 0; kv0 < kv_end; kv0 += 64, ++it) {
+        const bf16_t* sK = sKb[it & 1];
+        const bf16_t* sV = sVb[it & 1];
+        const bool more = kv0 + 64 < kv_end;
+        if (more) {
+            fk.fetch(base + D, ld, kv0 + 64, S, tid);
+            fv.fetch(base + 2 * D, ld, kv0 + 64, S, tid);
+        }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = kv0 + 32 * sub;
@@ -609,7 +657,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                const float p = key <= q ? expf(st[r] * scale - L) : 0.0f;
+                const float p = key <= q ? __expf(st[r] * scale - L) : 0.0f;
                 st[r] = p * (dp[r] - dl);
             }
 #pragma unroll
@@ -620,6 +668,11 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
                     dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag_t(sK, 32 * sub + 16 * t, 32 * i, lane), df, dq[i], 0, 0, 0);
             }
         }
+        if (more) {
+            fk.put(sKb[(it + 1) & 1], tid);
+            fv.put(sVb[(it + 1) & 1], tid);
+        }
+        __syncthreads();
     }
     if (q < S) {
         bf16_t* drow = dqkv + ((int64_t)b * S + q) * ld + h * 64;
@@ -644,9 +697,9 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
                                                                    const float* __restrict__ delta,
                                                                    bf16_t* __restrict__ dqkv, int S, int D, int H,
                                                                    float scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t sQ[64 * kAP];
-    __shared__ __attribute__((aligned(16))) bf16_t sO[64 * kAP];
-    __shared__ float sL[64], sDl[64];
+    __shared__ __attribute__((aligned(16))) bf16_t sQb[2][64 * kAP];
+    __shared__ __attribute__((aligned(16))) bf16_t sOb[2][64 * kAP];
+    __shared__ float sLb[2][64], sDlb[2][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int kblk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t ld = 3 * (int64_t)D;
@@ -666,16 +719,39 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
 #pragma unroll
         for (int r = 0; r < 16; ++r) dk[i][r] = dv[i][r] = 0.0f;
     const int qstart = (kblk * NW * 32) / 64 * 64;   // first query block that can see a key of this workgroup
-    for (int qb0 = qstart; qb0 < S; qb0 += 64) {
-        __syncthreads();
-        load_tile<64 * NW>(sQ, base, ld, qb0, S, tid);
-        load_tile<64 * NW>(sO, dob, D, qb0, S, tid);
+    TileFetch<64 * NW> fq, fo;
+    float pl = 0.0f, pd = 0.0f;   // statistics of query qb0 + tid (threads 0..63)
+    auto fetch_stats = [&](int qb0) {
         if (tid < 64) {
             const int qq = qb0 + tid < S ? qb0 + tid : S - 1;
-            sL[tid] = lse[((int64_t)b * H + h) * S + qq];
-            sDl[tid] = delta[((int64_t)b * H + h) * S + qq];
+            pl = lse[((int64_t)b * H + h) * S + qq];
+            pd = delta[((int64_t)b * H + h) * S + qq];
         }
-        __syncthreads();
+    };
+    auto put_stats = [&](int buf) {
+        if (tid < 64) {
+            sLb[buf][tid] = pl;
+            sDlb[buf][tid] = pd;
+        }
+    };
+    fq.fetch(base, ld, qstart, S, tid);
+    fo.fetch(dob, D, qstart, S, tid);
+    fetch_stats(qstart);
+    fq.put(sQb[0], tid);
+    fo.put(sOb[0], tid);
+    put_stats(0);
+    __syncthreads();
+    for (int qb0 = qstart, it = 0; qb0 < S; qb0 += 64, ++it) {
+        const bf16_t* sQ = sQb[it & 1];
+        const bf16_t* sO = sOb[it & 1];
+        const float* sL = sLb[it & 1];
+        const float* sDl = sDlb[it & 1];
+        const bool more = qb0 + 64 < S;
+        if (more) {
+            fq.fetch(base, ld, qb0 + 64, S, tid);
+            fo.fetch(dob, D, qb0 + 64, S, tid);
+            fetch_stats(qb0 + 64);
+        }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int qs = qb0 + 32 * sub;
@@ -692,7 +768,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
             for (int r = 0; r < 16; ++r) {
                 const int ql = 32 * sub + 8 * (r >> 2) + 4 * half + (r & 3);
                 const int qq = qb0 + ql;
-                const float p = (key <= qq && qq < S) ? expf(st[r] * scale - sL[ql]) : 0.0f;
+                const float p = (key <= qq && qq < S) ? __expf(st[r] * scale - sL[ql]) : 0.0f;
                 st[r] = p;
                 dp[r] = p * (dp[r] - sDl[ql]);
             }
@@ -706,6 +782,12 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
                 }
             }
         }
+        if (more) {
+            fq.put(sQb[(it + 1) & 1], tid);
+            fo.put(sOb[(it + 1) & 1], tid);
+            put_stats((it + 1) & 1);
+        }
+        __syncthreads();
     }
     if (key < S) {
         bf16_t* drow = dqkv + ((int64_t)b * S + key) * ld + h * 64;
