@@ -176,31 +176,80 @@ def conv_backward(dy, cache, w_now, stride, pad, relu):
     return dx, dw, db
 
 
-# ----------------------------------------------------------------------------- max pooling
-def maxpool_forward(x, k, stride):
-    """Window maximum; the winner of a window is its first maximum in row-major window order."""
+# ----------------------------------------------------------------------------- per-channel affine
+def affine_forward(x, gain, shift, relu):
+    """y[..., c] = gain[c] * x[..., c] + shift[c], then ReLU if asked (channels last)."""
+    y = x * gain + shift
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y, {"x": x, "y": y}
+
+
+def affine_backward(dy, cache, gain_now, relu):
+    """Returns (dx, dgain, dshift); the ReLU mask and the input are the forward pass's."""
+    x = cache["x"]
+    dz = dy.reshape(x.shape)
+    if relu:
+        dz = dz * (cache["y"] > 0.0)
+    c = x.shape[-1]
+    return dz * gain_now, (dz * x).reshape(-1, c).sum(axis=0), dz.reshape(-1, c).sum(axis=0)
+
+
+# ----------------------------------------------------------------------------- residual join
+def resadd_forward(a, b, relu):
+    """y = act(a + b)."""
+    y = a + b.reshape(a.shape)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y, {"y": y}
+
+
+def resadd_backward(dy, cache, relu):
+    """Gradient w.r.t. a (and, identically, w.r.t. b)."""
+    dz = dy.reshape(cache["y"].shape)
+    return dz * (cache["y"] > 0.0) if relu else dz
+
+
+# ----------------------------------------------------------------------------- global average pooling
+def avgpool_forward(x):
+    """[B, H, W, C] -> [B, C]: mean over the H*W positions."""
     n, h, wd, c = x.shape
-    ho = (h - k) // stride + 1
-    wo = (wd - k) // stride + 1
+    return x.reshape(n, h * wd, c).mean(axis=1), {"x_shape": x.shape}
+
+
+def avgpool_backward(dy, cache):
+    n, h, wd, c = cache["x_shape"]
+    return np.broadcast_to(dy.reshape(n, 1, 1, c) / (h * wd), (n, h, wd, c)).copy()
+
+
+# ----------------------------------------------------------------------------- max pooling
+def maxpool_forward(x, k, stride, pad=0):
+    """Window maximum; the winner of a window is its first maximum in row-major window order.
+    pad: rows / columns of padding on every side, which never win (they count as -infinity)."""
+    n, h, wd, c = x.shape
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (wd + 2 * pad - k) // stride + 1
+    xp = np.full((n, h + 2 * pad, wd + 2 * pad, c), -np.inf)
+    xp[:, pad:pad + h, pad:pad + wd, :] = x
     y = np.full((n, ho, wo, c), -np.inf)
     win = np.zeros((n, ho, wo, c), dtype=np.int64)
     for r in range(k):
         for s in range(k):
-            v = x[:, r:r + stride * ho:stride, s:s + stride * wo:stride, :]
+            v = xp[:, r:r + stride * ho:stride, s:s + stride * wo:stride, :]
             better = v > y
             y = np.where(better, v, y)
             win = np.where(better, r * k + s, win)
     return y, {"win": win, "x_shape": x.shape}
 
 
-def maxpool_backward(dy, cache, k, stride):
+def maxpool_backward(dy, cache, k, stride, pad=0):
     n, h, wd, c = cache["x_shape"]
     _, ho, wo, _ = dy.shape
-    dx = np.zeros((n, h, wd, c))
+    dxp = np.zeros((n, h + 2 * pad, wd + 2 * pad, c))
     for r in range(k):
         for s in range(k):
-            dx[:, r:r + stride * ho:stride, s:s + stride * wo:stride, :] += dy * (cache["win"] == r * k + s)
-    return dx
+            dxp[:, r:r + stride * ho:stride, s:s + stride * wo:stride, :] += dy * (cache["win"] == r * k + s)
+    return dxp[:, pad:pad + h, pad:pad + wd, :]
 
 
 # ----------------------------------------------------------------------------- loss

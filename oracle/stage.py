@@ -42,10 +42,19 @@ class Stage:
         caches = []
         q = self.q
         a = x if self.specs[0]["kind"] == "embedding" else q(x)
+        x_in = a
         loss = None
         inputs = []   # inputs[li] = what layer li read (a residual connection adds one of these)
+        outs = []     # outs[li] = what layer li produced
+
+        def earlier(li, k):
+            """Result of the layer k positions before layer li; one before the first layer is the stage input."""
+            return outs[li - k] if li - k >= 0 else x_in
+
         for li, (spec, p) in enumerate(zip(self.specs, self.params)):
             k = spec["kind"]
+            if k == "conv" and spec.get("src", 1) != 1:
+                a = earlier(li, spec["src"])
             inputs.append(a)
             feeds_loss = li + 1 < len(self.specs) and self.specs[li + 1]["kind"] == "softmax_ce"
             if k == "linear":
@@ -55,10 +64,20 @@ class Stage:
                 if not feeds_loss:
                     a = c["y"] = q(a)
             elif k == "conv":
+                a = a.reshape(a.shape[0], spec["h"], spec["w"], spec["cin"])
                 a, c = L.conv_forward(a, q(p["w"]), p["b"], spec["stride"], spec["pad"], spec["relu"])
                 a = c["y"] = q(a)
             elif k == "maxpool":
-                a, c = L.maxpool_forward(a, spec["k"], spec["stride"])
+                a, c = L.maxpool_forward(a, spec["k"], spec["stride"], spec.get("pad", 0))
+            elif k == "affine":
+                a, c = L.affine_forward(a.reshape(a.shape[0], spec["h"], spec["w"], spec["c"]), p["w"], p["b"], spec["relu"])
+                a = c["y"] = q(a)
+            elif k == "resadd":
+                a, c = L.resadd_forward(a, earlier(li, spec["src_b"]), spec["relu"])
+                a = c["y"] = q(a)
+            elif k == "avgpool":
+                a, c = L.avgpool_forward(a.reshape(a.shape[0], spec["h"], spec["w"], spec["c"]))
+                a = q(a)
             elif k == "layernorm":
                 a, c = L.layernorm_forward(a, p["w"], p["b"], spec["d"], spec["eps"])
                 a = q(a)
@@ -74,6 +93,7 @@ class Stage:
             else:
                 raise ValueError(k)
             caches.append(c)
+            outs.append(a)
         self.stash[slot] = caches
         return (a, loss) if self.is_last else a
 
@@ -90,12 +110,26 @@ class Stage:
         for i, slot in enumerate(slots):
             caches = self.stash.pop(slot)
             q = self.q
-            g = None if dy is None else q(dy[i * micro:(i + 1) * micro])
+            n_l = len(self.specs)
+            # Gradients by the result they belong to: index li = result of layer li, -1 = the stage input.  A
+            # result that several layers read (the start of a residual connection) collects one contribution
+            # from each reader, in reverse layer order; under the bf16 policy the stored sum is rounded after
+            # every contribution, as a stored tensor is.
+            grad_of = {}
+
+            def give(t, contribution):
+                c2 = contribution.reshape(contribution.shape[0], -1)
+                grad_of[t] = q(c2) if t not in grad_of else q(grad_of[t] + c2)
+
+            if dy is not None:
+                give(n_l - 1, dy[i * micro:(i + 1) * micro])
             held = {}   # layer index -> gradient of a residual connection that joins that layer's input
-            for li in range(len(self.specs) - 1, -1, -1):
+            for li in range(n_l - 1, -1, -1):
                 spec, p, c = self.specs[li], self.params[li], caches[li]
                 k = spec["kind"]
                 dw = db = None
+                g = grad_of.pop(li, None)
+                src = li - (spec.get("src", 1) if k == "conv" else 1)
                 if k == "softmax_ce":
                     g = L.softmax_ce_backward(c, self.M * spec.get("rows", 1))
                 elif k == "linear":
@@ -106,7 +140,14 @@ class Stage:
                     g = g.reshape(c["y"].shape)
                     g, dw, db = L.conv_backward(g, c, q(p["w"]), spec["stride"], spec["pad"], spec["relu"])
                 elif k == "maxpool":
-                    g = L.maxpool_backward(g.reshape(c["win"].shape), c, spec["k"], spec["stride"])
+                    g = L.maxpool_backward(g.reshape(c["win"].shape), c, spec["k"], spec["stride"], spec.get("pad", 0))
+                elif k == "affine":
+                    g, dw, db = L.affine_backward(g, c, p["w"], spec["relu"])
+                elif k == "resadd":
+                    g = L.resadd_backward(g, c, spec["relu"])
+                    give(max(li - spec["src_b"], -1), g)
+                elif k == "avgpool":
+                    g = L.avgpool_backward(g, c)
                 elif k == "layernorm":
                     g, dw, db = L.layernorm_backward(g, c, p["w"])
                 elif k == "attention":
@@ -116,8 +157,8 @@ class Stage:
                     g = None
                 if li in held:
                     g = g.reshape(g.shape[0], -1) + held.pop(li).reshape(g.shape[0], -1)
-                if g is not None and k != "maxpool":
-                    g = q(g).reshape(g.shape[0], -1)
+                if g is not None:
+                    give(max(src, -1), g)
                 if dw is None:
                     continue
                 if acc[li] is None:
@@ -125,6 +166,7 @@ class Stage:
                 else:
                     acc[li]["w"] = acc[li]["w"] + dw
                     acc[li]["b"] = acc[li]["b"] + db
+            g = grad_of.pop(-1, None)
             dxs.append(g)
         self.grads = acc
         return None if dxs[0] is None else np.concatenate(dxs, axis=0)

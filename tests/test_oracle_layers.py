@@ -186,6 +186,75 @@ def test_maxpool_gradient_goes_to_one_winner_per_window():
     assert dx.sum() == 1.0 and dx[0, 0, 0, 0] == 1.0
 
 
+@pytest.mark.parametrize("k,stride,pad", [(3, 2, 1), (2, 2, 1)])
+def test_padded_maxpool_against_library_autograd(k, stride, pad):
+    rng = np.random.default_rng(18)
+    x = rng.standard_normal((2, 9, 8, 3)) - 2.0   # mostly negative: padding (which never wins) must not read as 0
+    y, c = L.maxpool_forward(x, k, stride, pad)
+    dy = rng.standard_normal(y.shape)
+    dx = L.maxpool_backward(dy, c, k, stride, pad)
+    xt = torch.tensor(x.transpose(0, 3, 1, 2).copy(), requires_grad=True)
+    yt = F.max_pool2d(xt, k, stride, padding=pad)
+    yt.backward(torch.tensor(dy.transpose(0, 3, 1, 2).copy()))
+    assert np.array_equal(y, yt.detach().permute(0, 2, 3, 1).numpy())
+    assert np.allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy())
+
+
+# ------------------------------------------------------------------ per-channel affine, residual join, average pooling
+@pytest.mark.parametrize("relu", [False, True])
+def test_affine_against_library_autograd_and_fd(relu):
+    rng = np.random.default_rng(19)
+    x = rng.standard_normal((3, 4, 5, 6))
+    g = rng.standard_normal(6) + 1.0
+    b = rng.standard_normal(6)
+    y, c = L.affine_forward(x, g, b, relu)
+    dy = rng.standard_normal(y.shape)
+    dx, dg, db = L.affine_backward(dy, c, g, relu)
+    xt, gt, bt = (torch.tensor(v, requires_grad=True) for v in (x, g, b))
+    yt = xt * gt + bt
+    if relu:
+        yt = F.relu(yt)
+    yt.backward(torch.tensor(dy))
+    assert np.allclose(y, yt.detach().numpy()) and np.allclose(dx, xt.grad.numpy())
+    assert np.allclose(dg, gt.grad.numpy()) and np.allclose(db, bt.grad.numpy())
+    # the same layer is what a batch-normalisation layer computes at inference with mean 0 and variance 1 - eps
+    bn = F.batch_norm(torch.tensor(x).permute(0, 3, 1, 2), torch.zeros(6), torch.ones(6) - 1e-5, torch.tensor(g),
+                      torch.tensor(b), training=False, eps=1e-5).permute(0, 2, 3, 1)
+    assert np.allclose(np.maximum(bn.numpy(), 0.0) if relu else bn.numpy(), y)
+    # finite differences of sum(dy * y) w.r.t. the gain
+    f = lambda: float(np.sum(dy * L.affine_forward(x, g, b, relu)[0]))
+    assert _rel(_fd(f, g), dg) < 1e-6
+
+
+def test_affine_backward_uses_the_gain_it_is_given():
+    rng = np.random.default_rng(20)
+    x = rng.standard_normal((2, 3, 3, 4))
+    g0, g1 = rng.standard_normal(4), rng.standard_normal(4)
+    y, c = L.affine_forward(x, g0, np.zeros(4), False)
+    dy = rng.standard_normal(y.shape)
+    assert np.allclose(L.affine_backward(dy, c, g1, False)[0], dy * g1)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_resadd_and_avgpool_against_library(relu):
+    rng = np.random.default_rng(21)
+    a, b = rng.standard_normal((2, 3, 4, 5)), rng.standard_normal((2, 3, 4, 5))
+    y, c = L.resadd_forward(a, b, relu)
+    dy = rng.standard_normal(y.shape)
+    da = L.resadd_backward(dy, c, relu)
+    at, bt = torch.tensor(a, requires_grad=True), torch.tensor(b, requires_grad=True)
+    yt = F.relu(at + bt) if relu else at + bt
+    yt.backward(torch.tensor(dy))
+    assert np.allclose(y, yt.detach().numpy()) and np.allclose(da, at.grad.numpy()) and np.allclose(da, bt.grad.numpy())
+    p, c = L.avgpool_forward(a)
+    dp = rng.standard_normal(p.shape)
+    at = torch.tensor(a.transpose(0, 3, 1, 2).copy(), requires_grad=True)
+    pt = F.adaptive_avg_pool2d(at, 1).flatten(1)
+    pt.backward(torch.tensor(dp))
+    assert np.allclose(p, pt.detach().numpy())
+    assert np.allclose(L.avgpool_backward(dp, c), at.grad.permute(0, 2, 3, 1).numpy())
+
+
 # ------------------------------------------------------------------ GELU, residual linear
 def test_gelu_closed_forms_and_library():
     z = np.linspace(-6, 6, 97)

@@ -32,8 +32,30 @@ def _torch_net_loss(cfg, params, x, labels):
     a = torch.tensor(np.asarray(x, dtype=np.float64))
     for st, ps in zip(cfg.stages, params):
         ins = []      # inputs of this stage's layers (sources of residual connections)
-        for spec, p in zip(st, ps):
+        outs = []     # results of this stage's layers
+        x_stage = a
+        for li, (spec, p) in enumerate(zip(st, ps)):
             k = spec["kind"]
+            if k in ("affine", "resadd", "avgpool") or (k == "conv" and spec.get("src", 1) != 1):
+                def earlier(kk):
+                    return outs[li - kk] if li - kk >= 0 else x_stage
+                if k == "conv":
+                    a = earlier(spec["src"])
+                ins.append(a)
+                if k == "conv":
+                    a = F.conv2d(a.permute(0, 3, 1, 2), p["w"].permute(0, 3, 1, 2), p["b"],
+                                 stride=spec["stride"], padding=spec["pad"]).permute(0, 2, 3, 1)
+                    a = F.relu(a) if spec["relu"] else a
+                elif k == "affine":
+                    a = a * p["w"] + p["b"]
+                    a = F.relu(a) if spec["relu"] else a
+                elif k == "resadd":
+                    a = a + earlier(spec["src_b"])
+                    a = F.relu(a) if spec["relu"] else a
+                else:
+                    a = a.mean(dim=(1, 2))
+                outs.append(a)
+                continue
             if k == "linear" and spec.get("rows", 1) > 1:
                 src = ins[len(ins) - spec["skip"]] if spec.get("skip") else None
                 ins.append(a)
@@ -43,6 +65,7 @@ def _torch_net_loss(cfg, params, x, labels):
                 a = a.reshape(a.shape[0], -1)
                 if src is not None:
                     a = a + src
+                outs.append(a)
                 continue
             ins.append(a)
             if k == "linear":
@@ -66,10 +89,11 @@ def _torch_net_loss(cfg, params, x, labels):
                 if spec["relu"]:
                     a = F.relu(a)
             elif k == "maxpool":
-                a = F.max_pool2d(a.permute(0, 3, 1, 2), spec["k"], spec["stride"]).permute(0, 2, 3, 1)
+                a = F.max_pool2d(a.permute(0, 3, 1, 2), spec["k"], spec["stride"], padding=spec.get("pad", 0)).permute(0, 2, 3, 1)
             elif k == "softmax_ce":
                 return F.cross_entropy(a.reshape(-1, spec["classes"]),
                                        torch.tensor(np.asarray(labels, dtype=np.int64)).reshape(-1))
+            outs.append(a)
     raise AssertionError
 
 
@@ -79,7 +103,7 @@ def _torch_params(params):
 
 
 @pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=2, N=2),
-                                    lambda: get_config("tiny_transformer_f32")])
+                                    lambda: get_config("tiny_transformer_f32"), lambda: get_config("tiny_resnet_f32")])
 def test_micro_batched_forward_and_gradients_equal_full_batch(cfg_fn):
     cfg = cfg_fn()
     params = init_params(cfg, bias_std=0.1)
@@ -114,7 +138,7 @@ def test_micro_batched_forward_and_gradients_equal_full_batch(cfg_fn):
 
 
 @pytest.mark.parametrize("cfg_fn", [lambda: get_config("tiny_mlp_f32"), lambda: _small_conv_cfg(K=1, N=2),
-                                    lambda: get_config("tiny_transformer_f32")])
+                                    lambda: get_config("tiny_transformer_f32"), lambda: get_config("tiny_resnet_f32")])
 def test_single_worker_equals_textbook_sgd_momentum(cfg_fn):
     cfg = cfg_fn()
     flat_layers = [l for st in cfg.stages for l in st]

@@ -38,14 +38,53 @@ def transformer_block(s, d, heads, ffn):
             layernorm(d, s), linear(d, ffn, False, act="gelu", rows=s), linear(ffn, d, False, rows=s, skip=2)]
 
 
-def conv(h, w, cin, cout, r=3, stride=1, pad=1, relu=True):
+def conv(h, w, cin, cout, r=3, stride=1, pad=1, relu=True, src=1):
+    """src: which earlier result the layer reads: 1 = the layer before it (the default), k = the layer k
+    positions before it; one position before the first layer of a stage is the stage input."""
     return {"kind": "conv", "h": int(h), "w": int(w), "cin": int(cin), "cout": int(cout),
-            "r": int(r), "s": int(r), "stride": int(stride), "pad": int(pad), "relu": bool(relu)}
+            "r": int(r), "s": int(r), "stride": int(stride), "pad": int(pad), "relu": bool(relu), "src": int(src)}
 
 
-def maxpool(h, w, c, k=2, stride=2):
+def maxpool(h, w, c, k=2, stride=2, pad=0):
+    """pad: rows / columns of padding on every side; padded positions never win."""
     return {"kind": "maxpool", "h": int(h), "w": int(w), "c": int(c), "k": int(k),
-            "stride": int(stride)}
+            "stride": int(stride), "pad": int(pad)}
+
+
+def affine(h, w, c, relu):
+    """Trainable per-channel scale and shift (a batch-normalisation layer with its statistics folded away):
+    y = gain[c] * x + shift[c], then ReLU if asked."""
+    return {"kind": "affine", "h": int(h), "w": int(w), "c": int(c), "relu": bool(relu)}
+
+
+def resadd(h, w, c, src_b, relu=True):
+    """y = act(a + b): a is the result of the layer before, b that of the layer src_b positions before
+    (same convention as conv's src): the join of a residual connection."""
+    return {"kind": "resadd", "h": int(h), "w": int(w), "c": int(c), "src_b": int(src_b), "relu": bool(relu)}
+
+
+def avgpool(h, w, c):
+    """Mean over all h*w positions: [h, w, c] -> [c]."""
+    return {"kind": "avgpool", "h": int(h), "w": int(w), "c": int(c)}
+
+
+def bottleneck(h, cin, width, stride, project):
+    """ResNet bottleneck block on an h x h x cin input: 1x1 (width) - 3x3 (width, stride) - 1x1 (4 width), each
+    followed by a per-channel affine layer, ReLU after the first two; the block input (or, in the first block
+    of a group, a strided 1x1 projection of it with its own affine layer) is added before the last ReLU."""
+    ho = (h + 2 - 3) // stride + 1
+    cout = 4 * width
+    layers = [conv(h, h, cin, width, 1, 1, 0, False), affine(h, h, width, True),
+              conv(h, h, width, width, 3, stride, 1, False), affine(ho, ho, width, True),
+              conv(ho, ho, width, cout, 1, 1, 0, False), affine(ho, ho, cout, False)]
+    if project:
+        # the projection reads the block input: 7 positions before itself
+        layers += [conv(h, h, cin, cout, 1, stride, 0, False, src=7), affine(ho, ho, cout, False),
+                   resadd(ho, ho, cout, src_b=1 + 2, relu=True)]
+        # resadd: a = the projection's affine (the layer before), b = the main path's affine, 3 positions before
+    else:
+        layers += [resadd(ho, ho, cout, src_b=7, relu=True)]   # b = the block input
+    return layers, ho, cout
 
 
 def softmax_ce(classes, rows=1):
@@ -135,6 +174,37 @@ def _transformer(name, dtype, layers, d, heads, ffn, s, vocab, M, N, K, seed):
                         "eps 1e-5; S+1 tokens are drawn per sample: the first S are the input, the last S the targets")
 
 
+def _resnet(name, dtype, size, widths, blocks, classes, M, N, seed, stem_c=64):
+    """Bottleneck residual network on size x size x 3 images, one stage per group of blocks (the stem joins the
+    first group, the classifier the last)."""
+    h = (size + 2 * 3 - 7) // 2 + 1
+    stem = [conv(size, size, 3, stem_c, 7, 2, 3, False), affine(h, h, stem_c, True), maxpool(h, h, stem_c, 3, 2, 1)]
+    h = (h + 2 - 3) // 2 + 1
+    cin = stem_c
+    stages = []
+    for gi, (w, nb) in enumerate(zip(widths, blocks)):
+        st = stem if gi == 0 else []
+        for bi in range(nb):
+            ls, h, cin = bottleneck(h, cin, w, 2 if (bi == 0 and gi > 0) else 1, bi == 0)
+            st = st + ls
+        if gi == len(widths) - 1:
+            st = st + [avgpool(h, h, cin), linear(cin, classes, False), softmax_ce(classes)]
+        stages.append(st)
+    return Config(name=name, dtype=dtype, M=M, N=N, seed=seed, steps=2, in_shape=(size, size, 3), classes=classes,
+                  stages=stages,
+                  notes="bottleneck blocks, batch normalisation folded to a trainable per-channel affine layer (gain 1, "
+                        "shift 0 at the start), stride on the 3x3, projection shortcut in the first block of each group, "
+                        "bias on every convolution")
+
+
+def _resnet50():
+    return _resnet("resnet50_bf16", "bf16", 224, (64, 128, 256, 512), (3, 4, 6, 3), 1000, M=64, N=8, seed=3)
+
+
+def _tiny_resnet(dtype):
+    return lambda: _resnet("tiny_resnet_" + dtype, dtype, 32, (8, 16), (2, 2), 10, M=8, N=4, seed=6, stem_c=8)
+
+
 def _gpt2_small():
     return _transformer("gpt2_small_bf16", "bf16", 12, 768, 12, 3072, 512, 32000, M=16, N=8, K=4, seed=4)
 
@@ -147,7 +217,10 @@ CONFIGS = {
     "tiny_mlp_f32": _tiny_mlp,
     "mlp4x1024_bf16": _mlp_bf16,
     "vgg16_bf16": _vgg16,
+    "resnet50_bf16": _resnet50,
     "gpt2_small_bf16": _gpt2_small,
+    "tiny_resnet_f32": _tiny_resnet("f32"),
+    "tiny_resnet_bf16": _tiny_resnet("bf16"),
     "tiny_transformer_f32": _tiny_transformer("f32"),
     "tiny_transformer_bf16": _tiny_transformer("bf16"),
 }
@@ -173,9 +246,13 @@ def layer_out_shape(layer, in_shape):
         wo = (layer["w"] + 2 * layer["pad"] - layer["s"]) // layer["stride"] + 1
         return (ho, wo, layer["cout"])
     if k == "maxpool":
-        ho = (layer["h"] - layer["k"]) // layer["stride"] + 1
-        wo = (layer["w"] - layer["k"]) // layer["stride"] + 1
+        ho = (layer["h"] + 2 * layer.get("pad", 0) - layer["k"]) // layer["stride"] + 1
+        wo = (layer["w"] + 2 * layer.get("pad", 0) - layer["k"]) // layer["stride"] + 1
         return (ho, wo, layer["c"])
+    if k in ("affine", "resadd"):
+        return (layer["h"], layer["w"], layer["c"])
+    if k == "avgpool":
+        return (layer["c"],)
     if k == "softmax_ce":
         return (layer["classes"],) if layer.get("rows", 1) == 1 else (layer["rows"], layer["classes"])
     raise ValueError(k)

@@ -2,7 +2,7 @@
 
 Inputs follow the recipe of the benchmark configurations: standard-normal
 inputs, labels uniform over the classes, He-normal weights ``N(0, 2/fan_in)``
-and zero biases; layer-normalisation gains 1 and shifts 0; embedding tables
+and zero biases; layer-normalisation and per-channel affine gains 1 and shifts 0; embedding tables
 ``N(0, 0.02^2)``; token inputs uniform over the vocabulary, S+1 per sample
 (the first S are the input, the last S the next-token targets).  Everything is drawn with numpy's PCG64 generator keyed by
 ``(seed, stream, index)`` so that a batch can be regenerated independently.
@@ -41,6 +41,8 @@ def param_shapes(layer):
         return {"w": (layer["cout"], layer["r"], layer["s"], layer["cin"]), "b": (layer["cout"],)}
     if layer["kind"] == "layernorm":      # w = gain, b = shift
         return {"w": (layer["d"],), "b": (layer["d"],)}
+    if layer["kind"] == "affine":         # w = gain, b = shift, per channel
+        return {"w": (layer["c"],), "b": (layer["c"],)}
     if layer["kind"] == "embedding":      # w = token table, b = position table
         return {"w": (layer["vocab"], layer["d"]), "b": (layer["s"], layer["d"])}
     return {}
@@ -55,7 +57,7 @@ def init_params(cfg, bias_std=0.0):
         for layer in st:
             shp = param_shapes(layer)
             p = {}
-            if shp and layer["kind"] == "layernorm":
+            if shp and layer["kind"] in ("layernorm", "affine"):
                 g = _rng(cfg.seed, 1, idx)
                 p["w"] = np.ones(shp["w"], dtype=np.float32)
                 p["b"] = np.zeros(shp["b"], dtype=np.float32)
