@@ -58,19 +58,30 @@ enum {
                             rows per sample, the layer maps every row [Din] -> [Dout].  skip > 0: the input of the
                             layer `skip` positions before this one (which must be a TMPS_LAYERNORM) is added to the
                             result: a residual connection around the layers in between */
-    TMPS_CONV2D = 2,     /* dims = {H, W, Cin, Cout, R, S, stride, pad}; flags TMPS_FLAG_RELU */
-    TMPS_MAXPOOL = 3,    /* dims = {H, W, C, k, stride} (no padding) */
+    TMPS_CONV2D = 2,     /* dims = {H, W, Cin, Cout, R, S, stride, pad}; flags TMPS_FLAG_RELU, TMPS_FLAG_SRC(k) */
+    TMPS_MAXPOOL = 3,    /* dims = {H, W, C, k, stride, pad}; padded positions never win */
     TMPS_SOFTMAX_CE = 4, /* dims = {classes, rows}; only as the last layer of the last stage, after a plain
                             TMPS_LINEAR with the same rows; labels are int32 [samples, rows]; the loss is the
                             mean over all rows */
     TMPS_LAYERNORM = 5,  /* dims = {D, rows}; per row of D features, eps 1e-5; parameters gain (w) and shift (b) */
     TMPS_ATTENTION = 6,  /* dims = {S, D, heads}; causal multi-head self-attention; input rows [q | k | v] of 3*D
                             features, output [S, D]; scores scaled by 1/sqrt(D/heads) */
-    TMPS_EMBEDDING = 7   /* dims = {vocab, S, D}; first layer of a stage only; the stage input is int32 tokens
+    TMPS_EMBEDDING = 7,  /* dims = {vocab, S, D}; first layer of a stage only; the stage input is int32 tokens
                             [samples, S]; output [S, D] = token table row + position table row; parameters
                             token table (w, [vocab, D]) and position table (b, [S, D]) */
+    TMPS_AFFINE = 8,     /* dims = {H, W, C}; y = gain[c] * x + shift[c] per channel (channels last), then ReLU with
+                            TMPS_FLAG_RELU; parameters gain (w, [C]) and shift (b, [C]); must follow a layer without
+                            activation */
+    TMPS_RESADD = 9,     /* dims = {H, W, C, k}; y = act(a + b): a = the result of the layer before, b = the result of
+                            the layer k positions before (one before the first layer = the stage input);
+                            TMPS_FLAG_RELU */
+    TMPS_AVGPOOL = 10    /* dims = {H, W, C}; mean over the H*W positions: [H, W, C] -> [C] */
 };
 enum { TMPS_FLAG_RELU = 1, TMPS_FLAG_GELU = 2 /* exact: z * Phi(z) */ };
+/* A convolution normally reads the result of the layer before it.  TMPS_FLAG_SRC(k), k = 2..255, in its flags
+ * makes it read the result of the layer k positions before it instead (one position before the first layer of a
+ * stage = the stage input): the branch of a residual connection. */
+#define TMPS_FLAG_SRC(k) ((int)(k) << 8)
 
 typedef struct tmps_stage tmps_stage; /* opaque */
 
@@ -209,7 +220,7 @@ enum {
     TMPS_KC_CONV_DGRAD, TMPS_KC_CONV_WGRAD, TMPS_KC_SOFTMAX_CE, TMPS_KC_UPDATE, TMPS_KC_POOL_FWD,
     TMPS_KC_POOL_BWD, TMPS_KC_RELU_MASK, TMPS_KC_REDUCE, TMPS_KC_COPY, TMPS_KC_EVENT_PAIR,
     TMPS_KC_SPLIT_FINISH, TMPS_KC_SLICE_SUM, TMPS_KC_LAYERNORM,
-    TMPS_KC_ATTN_FWD, TMPS_KC_ATTN_BWD, TMPS_KC_EMBEDDING, TMPS_KERNEL_CLASSES
+    TMPS_KC_ATTN_FWD, TMPS_KC_ATTN_BWD, TMPS_KC_EMBEDDING, TMPS_KC_AFFINE, TMPS_KC_RESADD, TMPS_KERNEL_CLASSES
 };
 int tmps_profile_enable(int on);
 int tmps_profile_read(double* total_ms, int64_t* launches, int n_classes);

@@ -10,6 +10,7 @@ _lib = None
 
 TMPS_F32, TMPS_BF16_F32MASTER = 0, 1
 TMPS_LINEAR, TMPS_CONV2D, TMPS_MAXPOOL, TMPS_SOFTMAX_CE, TMPS_LAYERNORM, TMPS_ATTENTION, TMPS_EMBEDDING = 1, 2, 3, 4, 5, 6, 7
+TMPS_AFFINE, TMPS_RESADD, TMPS_AVGPOOL = 8, 9, 10
 TMPS_FLAG_RELU, TMPS_FLAG_GELU = 1, 2
 
 
@@ -105,7 +106,7 @@ def version_diff_simulated(W, N):
 
 KERNEL_CLASSES = ["dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "softmax_ce",
                   "update", "pool_fwd", "pool_bwd", "relu_mask", "reduce", "copy", "event_pair", "splitk_finish", "slice_sum",
-                  "layernorm", "attn_fwd", "attn_bwd", "embedding"]
+                  "layernorm", "attn_fwd", "attn_bwd", "embedding", "affine", "resadd"]
 
 
 def profile_enable(on):
@@ -141,9 +142,17 @@ def layer_descs(specs):
         elif k == "conv":
             d.kind = TMPS_CONV2D
             dims[:8] = [sp["h"], sp["w"], sp["cin"], sp["cout"], sp["r"], sp["s"], sp["stride"], sp["pad"]]
-            d.flags = TMPS_FLAG_RELU if sp["relu"] else 0
+            d.flags = (TMPS_FLAG_RELU if sp["relu"] else 0) | ((sp.get("src", 1) << 8) if sp.get("src", 1) > 1 else 0)
         elif k == "maxpool":
-            d.kind, dims[:5] = TMPS_MAXPOOL, [sp["h"], sp["w"], sp["c"], sp["k"], sp["stride"]]
+            d.kind, dims[:6] = TMPS_MAXPOOL, [sp["h"], sp["w"], sp["c"], sp["k"], sp["stride"], sp.get("pad", 0)]
+        elif k == "affine":
+            d.kind, dims[:3] = TMPS_AFFINE, [sp["h"], sp["w"], sp["c"]]
+            d.flags = TMPS_FLAG_RELU if sp["relu"] else 0
+        elif k == "resadd":
+            d.kind, dims[:4] = TMPS_RESADD, [sp["h"], sp["w"], sp["c"], sp["src_b"]]
+            d.flags = TMPS_FLAG_RELU if sp["relu"] else 0
+        elif k == "avgpool":
+            d.kind, dims[:3] = TMPS_AVGPOOL, [sp["h"], sp["w"], sp["c"]]
         elif k == "softmax_ce":
             d.kind, dims[:2] = TMPS_SOFTMAX_CE, [sp["classes"], sp.get("rows", 1)]
         else:

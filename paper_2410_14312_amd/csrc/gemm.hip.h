@@ -265,12 +265,16 @@ template <typename TOut> struct EpiBiasAct {
 
 // Gradient through the stored activation of the layer below: mode kActRelu: v where mask[m, n] > 0 else 0
 // (mask = that layer's output); mode kActGelu: v * gelu'(mask[m, n]) (mask = that layer's pre-activation).
+// add (may be null, may be out itself): what other readers of the same tensor have already contributed to its
+// gradient; it joins v before the mask is applied.
 template <typename TOut, typename TMask> struct EpiMask {
     TOut* out;
     const TMask* mask;  // may be null
     int64_t ld;
     int mode = kActRelu;
+    const TOut* add = nullptr;
     __device__ __forceinline__ void finish(int64_t i, float v) const {
+        if (add) v += to_f32(add[i]);
         if (mask) {
             const float t = to_f32(mask[i]);
             if (mode == kActGelu) v *= gelu_grad_f(t);
@@ -282,6 +286,12 @@ template <typename TOut, typename TMask> struct EpiMask {
     __device__ __forceinline__ int column(int) const { return 0; }
     __device__ __forceinline__ void at(int, int64_t i, float v, int) const { finish(i, v); }
     __device__ __forceinline__ void at8(int, int64_t i, float (&v)[8], int) const {
+        if (add) {
+            float a[8];
+            load8(add + i, a);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += a[e];
+        }
         if (mask) {
             float t[8];
             load8(mask + i, t);

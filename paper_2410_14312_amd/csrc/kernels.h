@@ -37,14 +37,16 @@ hipError_t dense_forward(int dtype, const void* x, const void* w, const float* b
 // where mask[B, Din] <= 0 (mask = that layer's output); mask_mode 2: times gelu'(mask) (mask = that
 // layer's pre-activation).  mask may be null; activation dtype.
 hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode,
-                       int B, int Din, int Dout, float* ws, hipStream_t s);
+                       const void* add, int B, int Din, int Dout, float* ws, hipStream_t s);
+// `add` (may be null; may be dx itself): tensor of dx's shape added BEFORE the mask is applied: the
+// gradient that other readers of the same input have already contributed.
 // gw[Dout, Din] = dy^T x and gb[Dout] = column sums of dy, with gb stored right after gw.
 hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout,
                        float* ws, hipStream_t s);
 
 hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y,
                         const ConvShape& c, int relu, float* ws, hipStream_t s);
-hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask,
+hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const void* add,
                       const ConvShape& c, float* ws, hipStream_t s);
 hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c,
                       float* ws, hipStream_t s);
@@ -52,9 +54,26 @@ hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const
 // 2-D max pooling, channels-last, no padding.  Backward recomputes the winner (first maximum in
 // row-major window order) from the stored input; relu_mask: also zero where the input is <= 0.
 hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int W, int C, int k,
-                           int stride, hipStream_t s);
+                           int stride, int pad, hipStream_t s);
 hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, int B, int H, int W,
-                            int C, int k, int stride, int relu_mask, hipStream_t s);
+                            int C, int k, int stride, int pad, int relu_mask, hipStream_t s);
+
+// Per-channel affine layer on channels-last rows: y[r, c] = gain[c] x[r, c] + shift[c], then ReLU if asked.
+hipError_t affine_forward(int dtype, const void* x, const float* gain, const float* shift, void* y, int64_t rows, int C,
+                          int relu, hipStream_t s);
+// dx (may be null) = gain * dy; dgain_dshift: C gain gradients (sum of dy * x) followed by C shift gradients (sum
+// of dy); dy has already passed through the layer's own ReLU; ws: affine_workspace_elems.
+hipError_t affine_backward(int dtype, const void* dy, const void* x, const float* gain, void* dx, float* dgain_dshift,
+                           float* ws, int64_t rows, int C, hipStream_t s);
+size_t affine_workspace_elems(int64_t rows, int C);
+
+// y = act(a + b), n elements.
+hipError_t resadd_forward(int dtype, const void* a, const void* b, void* y, int64_t n, int relu, hipStream_t s);
+
+// Global average pooling [B, HW, C] -> [B, C] and its gradient (relu_mask: zero where the stored input is <= 0).
+hipError_t avgpool_forward(int dtype, const void* x, void* y, int B, int HW, int C, hipStream_t s);
+hipError_t avgpool_backward(int dtype, const void* dy, const void* x, void* dx, int B, int HW, int C, int relu_mask,
+                            hipStream_t s);
 
 // Layer normalisation over rows of D features.  stats[rows][2] = (mean, 1/std) of the forward pass.
 hipError_t layernorm_forward(int dtype, const void* x, const float* gamma, const float* beta, void* y,

@@ -212,7 +212,7 @@ hipError_t cast_f32_to_bf16(const float* in, void* out, int64_t n, hipStream_t s
 // One thread per output element (channels fastest, so a wave reads/writes consecutive channels).
 template <typename T>
 __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int B, int H, int W, int C,
-                                   int Ho, int Wo, int k, int stride) {
+                                   int Ho, int Wo, int k, int stride, int pad) {
     int64_t total = (int64_t)B * Ho * Wo * C;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -224,7 +224,9 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, i
     float best = -INFINITY;
     for (int r = 0; r < k; ++r)
         for (int s = 0; s < k; ++s) {
-            float v = to_f32(x[(((int64_t)n * H + ho * stride + r) * W + wo * stride + s) * C + c]);
+            const int hh = ho * stride - pad + r, ww = wo * stride - pad + s;
+            if ((unsigned)hh >= (unsigned)H || (unsigned)ww >= (unsigned)W) continue;   // padding never wins
+            float v = to_f32(x[(((int64_t)n * H + hh) * W + ww) * C + c]);
             if (v > best) best = v;
         }
     y[i] = from_f32<T>(best);
@@ -234,7 +236,7 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, i
 // row-major window order) it is.  Handles overlapping windows and inputs no window covers.
 template <typename T>
 __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx,
-                                   int B, int H, int W, int C, int Ho, int Wo, int k, int stride,
+                                   int B, int H, int W, int C, int Ho, int Wo, int k, int stride, int pad,
                                    int relu_mask) {
     int64_t total = (int64_t)B * H * W * C;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -247,14 +249,17 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict_
     float xv = to_f32(x[i]);
     float acc = 0.0f;
     if (!(relu_mask && !(xv > 0.0f))) {
-        int ho_lo = h - k + 1 > 0 ? (h - k + 1 + stride - 1) / stride : 0;
-        int wo_lo = w - k + 1 > 0 ? (w - k + 1 + stride - 1) / stride : 0;
-        for (int ho = ho_lo; ho < Ho && ho * stride <= h; ++ho)
-            for (int wo = wo_lo; wo < Wo && wo * stride <= w; ++wo) {
+        // windows that contain (h, w): ho * stride - pad <= h <= ho * stride - pad + k - 1
+        const int hp = h + pad, wp = w + pad;
+        int ho_lo = hp - k + 1 > 0 ? (hp - k + 1 + stride - 1) / stride : 0;
+        int wo_lo = wp - k + 1 > 0 ? (wp - k + 1 + stride - 1) / stride : 0;
+        for (int ho = ho_lo; ho < Ho && ho * stride <= hp; ++ho)
+            for (int wo = wo_lo; wo < Wo && wo * stride <= wp; ++wo) {
                 bool win = true;
                 for (int r = 0; r < k && win; ++r)
                     for (int s = 0; s < k; ++s) {
-                        int hh = ho * stride + r, ww = wo * stride + s;
+                        int hh = ho * stride - pad + r, ww = wo * stride - pad + s;
+                        if ((unsigned)hh >= (unsigned)H || (unsigned)ww >= (unsigned)W) continue;
                         float v = to_f32(x[(((int64_t)n * H + hh) * W + ww) * C + c]);
                         bool before = (hh < h) || (hh == h && ww < w);
                         if (v > xv || (before && v == xv)) { win = false; break; }
@@ -303,27 +308,27 @@ __global__ __launch_bounds__(256) void maxpool2x2_bwd_bf16_kernel(const bf16_t* 
     for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(dx + base + off[q]) = out[q].u;
 }
 
-hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int W, int C, int k, int stride,
+hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int W, int C, int k, int stride, int pad,
                            hipStream_t s) {
-    int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+    int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     int64_t total = (int64_t)B * Ho * Wo * C;
     if (total <= 0) return hipSuccess;
     dim3 grid(cdiv64(total, 256));
     if (dtype == kBF16)
         hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, B, H,
-                           W, C, Ho, Wo, k, stride);
+                           W, C, Ho, Wo, k, stride, pad);
     else
         hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)y, B, H, W,
-                           C, Ho, Wo, k, stride);
+                           C, Ho, Wo, k, stride, pad);
     return hipGetLastError();
 }
 
 hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, int B, int H, int W, int C,
-                            int k, int stride, int relu_mask, hipStream_t s) {
-    int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+                            int k, int stride, int pad, int relu_mask, hipStream_t s) {
+    int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     int64_t total = (int64_t)B * H * W * C;
     if (total <= 0) return hipSuccess;
-    if (dtype == kBF16 && k == 2 && stride == 2 && H % 2 == 0 && W % 2 == 0 && C % 8 == 0 &&
+    if (dtype == kBF16 && k == 2 && stride == 2 && pad == 0 && H % 2 == 0 && W % 2 == 0 && C % 8 == 0 &&
         (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(dx) & 15) == 0) {
         int64_t windows = (int64_t)B * Ho * Wo * (C / 8);
@@ -334,10 +339,10 @@ hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, 
     dim3 grid(cdiv64(total, 256));
     if (dtype == kBF16)
         hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x,
-                           (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, Ho, Wo, k, stride, relu_mask);
+                           (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, Ho, Wo, k, stride, pad, relu_mask);
     else
         hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (const float*)dy,
-                           (float*)dx, B, H, W, C, Ho, Wo, k, stride, relu_mask);
+                           (float*)dx, B, H, W, C, Ho, Wo, k, stride, pad, relu_mask);
     return hipGetLastError();
 }
 

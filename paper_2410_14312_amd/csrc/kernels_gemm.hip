@@ -182,11 +182,11 @@ hipError_t dense_forward(int dtype, const void* x, const void* w, const float* b
     return launch_f32<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu, (const float*)res, (float*)zout}, B, Dout, Din, one_slice(Din, 16), 1, s);
 }
 
-hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode, int B,
-                       int Din, int Dout, float* ws, hipStream_t s) {
+hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode,
+                       const void* add, int B, int Din, int Dout, float* ws, hipStream_t s) {
     // dx[m, n] = sum_k dy[m, k] * w[k, n]:  A = dy (k-contiguous), B(n, k) = w[k*Din + n] (row-contiguous)
     if (dtype == kBF16) {
-        EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode};
+        EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode, (const bf16_t*)add};
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(w);
         if (fast) {
             DenseKC A{(const bf16_t*)dy, B, Dout, Dout};
@@ -199,7 +199,7 @@ hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const
     }
     DenseView<float, true> A{(const float*)dy, B, Dout, Dout, 0};
     DenseView<float, false> Bv{(const float*)w, Din, Dout, Din, 0};
-    return launch_f32<false>(kcDenseDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din, mask_mode}, B, Din, Dout, one_slice(Dout, 16), 1, s);
+    return launch_f32<false>(kcDenseDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din, mask_mode, (const float*)add}, B, Din, Dout, one_slice(Dout, 16), 1, s);
 }
 
 hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout, float* ws,
@@ -265,11 +265,11 @@ hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bi
     return launch_f32<false>(kcConvFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, c.Cout, relu}, M, c.Cout, K, one_slice(K, 16), 1, s);
 }
 
-hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const ConvShape& c,
-                      float* ws, hipStream_t s) {
+hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const void* add,
+                      const ConvShape& c, float* ws, hipStream_t s) {
     int M = c.B * c.H * c.W, K = c.R * c.S * c.Cout;
     if (dtype == kBF16) {
-        EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, c.Cin};
+        EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, c.Cin, kActRelu, (const bf16_t*)add};
         if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w) && small_enough(c)) {
             ConvDgradA2 A{(const bf16_t*)dy, geom2(c), M, K};
             ConvDgradB2 Bv{(const bf16_t*)w, geom2(c), c.Cin, K};
@@ -281,7 +281,7 @@ hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const 
     }
     ConvDgradA<float> A{(const float*)dy, geom(c), M, K, 0};
     ConvDgradB<float> Bv{(const float*)w, geom(c), c.Cin, K};
-    return launch_f32<false>(kcConvDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, c.Cin}, M, c.Cin, K, one_slice(K, 16), 1, s);
+    return launch_f32<false>(kcConvDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, c.Cin, kActRelu, (const float*)add}, M, c.Cin, K, one_slice(K, 16), 1, s);
 }
 
 hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c, float* ws,

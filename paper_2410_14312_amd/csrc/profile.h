@@ -7,7 +7,7 @@ namespace tmps {
 enum KernelClass {
     kcDenseFwd = 0, kcDenseDgrad, kcDenseWgrad, kcConvFwd, kcConvDgrad, kcConvWgrad, kcSoftmaxCE,
     kcUpdate, kcPoolFwd, kcPoolBwd, kcReluMask, kcReduce, kcCopy, kcEventPair, kcSplitFinish, kcSliceSum, kcLayerNorm,
-    kcAttnFwd, kcAttnBwd, kcEmbedding, kcCount
+    kcAttnFwd, kcAttnBwd, kcEmbedding, kcAffine, kcResAdd, kcCount
 };
 
 bool profile_on();

@@ -69,15 +69,23 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
     const int mb = cfg->micro_batch;
     const int M = mb * cfg->n_micro;
     const int64_t rows_all = (int64_t)cfg->max_stash * mb;
-    int64_t cur = -1, poff = 0, gmax = 0;
+    int64_t poff = 0, gmax = 0;
     size_t soff = 0, ws = 0;
-    bool any_skip = false;
+    bool any_skip = false, any_join = false;
     for (int i = 0; i < n_layers; ++i) {
         LayerRT L;
         L.d = layers[i];
         const int32_t* d = L.d.dims;
         L.relu = (L.d.flags & TMPS_FLAG_RELU) != 0;
         L.act = L.relu ? 1 : ((L.d.flags & TMPS_FLAG_GELU) ? 2 : 0);
+        L.in_t = i - 1;
+        const int src = (L.d.flags >> 8) & 0xff;
+        if (src > 1) {
+            if (L.d.kind != TMPS_CONV2D) return fail(TMPS_EUNSUPPORTED, "layer %d: only a convolution can read an earlier layer's result", i);
+            if (i - src < -1) return fail(TMPS_ESHAPE, "layer %d: its source lies before the stage input", i);
+            L.in_t = i - src;
+            any_join = true;
+        }
         switch (L.d.kind) {
             case TMPS_LINEAR: {
                 if (d[0] < 1 || d[1] < 1) return fail(TMPS_EINVAL, "layer %d: linear dims must be positive", i);
@@ -123,14 +131,40 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                 break;
             }
             case TMPS_MAXPOOL: {
-                if (d[0] < 1 || d[1] < 1 || d[2] < 1 || d[3] < 1 || d[4] < 1 || d[3] > d[0] || d[3] > d[1])
+                if (d[0] < 1 || d[1] < 1 || d[2] < 1 || d[3] < 1 || d[4] < 1 || d[5] < 0 || d[5] >= d[3] ||
+                    d[3] > d[0] + 2 * d[5] || d[3] > d[1] + 2 * d[5])
                     return fail(TMPS_EINVAL, "layer %d: bad pooling dims", i);
-                int Ho = (d[0] - d[3]) / d[4] + 1, Wo = (d[1] - d[3]) / d[4] + 1;
+                int Ho = (d[0] + 2 * d[5] - d[3]) / d[4] + 1, Wo = (d[1] + 2 * d[5] - d[3]) / d[4] + 1;
                 L.in_elems = (int64_t)d[0] * d[1] * d[2];
                 L.out_elems = (int64_t)Ho * Wo * d[2];
                 L.relu = false; L.act = 0;
                 break;
             }
+            case TMPS_AFFINE:
+                if (d[0] < 1 || d[1] < 1 || d[2] < 1) return fail(TMPS_EINVAL, "layer %d: affine dims must be positive", i);
+                if (L.act == 2) return fail(TMPS_EUNSUPPORTED, "layer %d: GELU on an affine layer is not built", i);
+                if (i == 0 || st.layers[i - 1].act != 0)
+                    return fail(TMPS_EUNSUPPORTED, "layer %d: an affine layer must follow a layer without activation", i);
+                L.in_elems = L.out_elems = (int64_t)d[0] * d[1] * d[2];
+                L.w_count = d[2]; L.b_count = d[2];
+                L.ws_elems = affine_workspace_elems((int64_t)M * d[0] * d[1], d[2]);
+                break;
+            case TMPS_RESADD:
+                if (d[0] < 1 || d[1] < 1 || d[2] < 1 || d[3] < 1) return fail(TMPS_EINVAL, "layer %d: bad residual join", i);
+                if (L.act == 2) return fail(TMPS_EUNSUPPORTED, "layer %d: GELU on a residual join is not built", i);
+                if (i == 0 || i - d[3] < -1) return fail(TMPS_ESHAPE, "layer %d: a source of the join lies before the stage input", i);
+                if (st.layers[i - 1].act != 0)
+                    return fail(TMPS_EUNSUPPORTED, "layer %d: the layer before a residual join must have no activation", i);
+                L.in_b = i - d[3];
+                L.in_elems = L.out_elems = (int64_t)d[0] * d[1] * d[2];
+                any_join = true;
+                break;
+            case TMPS_AVGPOOL:
+                if (d[0] < 1 || d[1] < 1 || d[2] < 1) return fail(TMPS_EINVAL, "layer %d: pooling dims must be positive", i);
+                L.in_elems = (int64_t)d[0] * d[1] * d[2];
+                L.out_elems = d[2];
+                L.relu = false; L.act = 0;
+                break;
             case TMPS_LAYERNORM:
                 if (d[0] < 1 || d[1] < 0) return fail(TMPS_EINVAL, "layer %d: bad layer-normalisation dims", i);
                 L.rps = d[1] > 0 ? d[1] : 1;
@@ -174,10 +208,13 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
             default:
                 return fail(TMPS_EUNSUPPORTED, "layer %d: kind %d not built", i, L.d.kind);
         }
-        if (cur >= 0 && cur != L.in_elems)
-            return fail(TMPS_ESHAPE, "layer %d expects %lld input elements per sample, previous layer gives %lld", i,
-                        (long long)L.in_elems, (long long)cur);
-        cur = L.out_elems;
+        if (i == 0) st.in_elems = L.in_elems;
+        for (int t : {L.in_t, L.d.kind == TMPS_RESADD ? L.in_b : L.in_t}) {
+            const int64_t have = t < 0 ? st.in_elems : st.layers[t].out_elems;
+            if (have != L.in_elems)
+                return fail(TMPS_ESHAPE, "layer %d expects %lld input elements per sample, its source gives %lld", i,
+                            (long long)L.in_elems, (long long)have);
+        }
         if (L.w_count) {
             L.w_off = poff;
             L.b_off = poff + L.w_count;
@@ -223,7 +260,16 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
 
     // scratch: gradient buffers of M rows, two boundary-gradient buffers, fp32 workspace
     size_t o = 0;
-    st.n_gbuf = any_skip ? 4 : 2;
+    st.n_gbuf = any_join ? 6 : (any_skip ? 4 : 2);
+    // how many layers read each result (the backward pass collects one gradient contribution per reader)
+    st.readers.assign(n_layers + 1, 0);
+    for (int i = 0; i < n_layers; ++i) {
+        const LayerRT& L = st.layers[i];
+        if (L.d.kind == TMPS_EMBEDDING) continue;
+        ++st.readers[L.in_t + 1];
+        if (L.d.kind == TMPS_RESADD) ++st.readers[L.in_b + 1];
+        if (L.d.kind == TMPS_LINEAR && L.skip) ++st.readers[st.layers[i - L.skip].in_t + 1];
+    }
     st.gbuf_bytes = align_up((size_t)M * std::max<int64_t>(gmax, 1) * st.asz, 256);
     for (int k = 0; k < st.n_gbuf; ++k) { st.gbuf_off[k] = o; o += st.gbuf_bytes; }
     st.dxout_bytes = align_up((size_t)M * st.in_elems * st.asz, 256);
@@ -339,11 +385,11 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
         x0 = dst;
     }
     st->slot_x[slot] = x;
-    const void* in = x0;
     for (size_t li = 0; li < st->layers.size(); ++li) {
         const LayerRT& L = st->layers[li];
         void* out = st->out_ptr(L, row0);
         const int32_t* d = L.d.dims;
+        const void* in = L.in_t < 0 ? x0 : (const void*)st->out_ptr(st->layers[L.in_t], row0);
         switch (L.d.kind) {
             case TMPS_LINEAR: {
                 const void* res = nullptr;
@@ -360,7 +406,19 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
                 TMPS_GEMM(conv_forward(dt, in, st->wptr(L), st->bptr(L), out, conv_shape(L.d, mb), L.relu, ws, s));
                 break;
             case TMPS_MAXPOOL:
-                TMPS_RUN(kcPoolFwd, s, maxpool_forward(dt, in, out, mb, d[0], d[1], d[2], d[3], d[4], s));
+                TMPS_RUN(kcPoolFwd, s, maxpool_forward(dt, in, out, mb, d[0], d[1], d[2], d[3], d[4], d[5], s));
+                break;
+            case TMPS_AFFINE:
+                TMPS_GEMM(affine_forward(dt, in, st->master + L.w_off, st->master + L.b_off, out, (int64_t)mb * d[0] * d[1], d[2],
+                                         L.relu, s));
+                break;
+            case TMPS_RESADD: {
+                const void* b = L.in_b < 0 ? x0 : (const void*)st->out_ptr(st->layers[L.in_b], row0);
+                TMPS_GEMM(resadd_forward(dt, in, b, out, (int64_t)mb * L.out_elems, L.relu, s));
+                break;
+            }
+            case TMPS_AVGPOOL:
+                TMPS_GEMM(avgpool_forward(dt, in, out, mb, d[0] * d[1], d[2], s));
                 break;
             case TMPS_LAYERNORM:
                 TMPS_GEMM(layernorm_forward(dt, in, st->master + L.w_off, st->master + L.b_off, out,
@@ -385,7 +443,6 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
                 break;
             }
         }
-        in = out;
     }
     if (y) {
         const LayerRT& L = st->cfg.is_last ? st->layers[st->layers.size() - 2] : st->layers.back();
@@ -425,116 +482,230 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         x0 = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->in_esize;
     }
 
-    // Gradient buffers: the gradient w.r.t. a layer's output is read while the one w.r.t. its input is written;
-    // the gradient entering a residual layer is kept until the layer at the start of the connection has added it.
-    char* gbuf[4];
-    bool busy[4] = {false, false, false, false};
+    // Gradients are kept per result: grads[t + 1] is the gradient w.r.t. the result of layer t (t = -1: the stage
+    // input).  Layers are visited last to first; every layer that reads a result contributes to its gradient: the
+    // first contribution is written, later ones are added to what is there (in the epilogue of the kernel that
+    // computes them).  Buffers come from a small pool and are shared by reference count: a residual connection
+    // hands the SAME gradient to both of its sources without copying it.
+    struct Grad {
+        const void* ptr = nullptr;
+        int buf = -1;      // pool buffer that holds it; -1: memory that is not ours to write or free (dy, the stash, dx)
+        bool set = false;
+    };
+    const int nl = (int)st->layers.size();
+    std::vector<Grad> grads(nl + 1);
+    std::vector<int> remaining(st->readers);
+    char* gbuf[8];
+    int refs[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int k = 0; k < st->n_gbuf; ++k) gbuf[k] = st->scratch + st->gbuf_off[k];
     auto take = [&]() -> int {
         for (int k = 0; k < st->n_gbuf; ++k)
-            if (!busy[k]) {
-                busy[k] = true;
+            if (refs[k] == 0) {
+                refs[k] = 1;
                 return k;
             }
         return -1;
     };
-    const int nl = (int)st->layers.size();
-    std::vector<const void*> held(nl, nullptr);   // by the layer whose input gradient it is added to
-    std::vector<int> held_buf(nl, -1);
+    auto release = [&](int buf) {
+        if (buf >= 0) --refs[buf];
+    };
     float* ws = reinterpret_cast<float*>(st->scratch + st->ws_off);
-    int cur = -1;  // which buffer holds g, -1: memory that is not ours
-    const void* g;
+    // the stored activation that a gradient written for result t has to pass through (mode 1: ReLU, 2: GELU)
+    auto mask_of = [&](int t, int& mode) -> const void* {
+        mode = 1;
+        if (t < 0) return nullptr;
+        const LayerRT& P = st->layers[t];
+        if (P.act == 1) return st->out_ptr(P, row0);
+        if (P.act == 2) {
+            mode = 2;
+            return st->stash + P.z_off + (size_t)row0 * P.out_elems * st->asz;
+        }
+        return nullptr;
+    };
+    // Where the contribution of a kernel to result t goes: `dst` to write, `add` to join first (null: nothing yet).
+    struct Target {
+        void* dst = nullptr;
+        const void* add = nullptr;
+        int buf = -1;
+        bool wanted = false;
+    };
+    auto target = [&](int t, Target& T) -> int {
+        T = Target();
+        Grad& G = grads[t + 1];
+        if (t < 0) {
+            if (!dx) return TMPS_OK;   // nobody wants the gradient w.r.t. the stage input
+            T.wanted = true;
+            T.dst = dx;
+            T.add = G.set ? dx : nullptr;
+            return TMPS_OK;
+        }
+        T.wanted = true;
+        if (G.set && G.buf >= 0 && refs[G.buf] == 1) {   // ours alone: add in place
+            T.dst = gbuf[G.buf];
+            T.add = G.ptr;
+            T.buf = G.buf;
+            return TMPS_OK;
+        }
+        T.buf = take();
+        if (T.buf < 0) return fail(TMPS_EUNSUPPORTED, "out of gradient buffers (too many open residual connections)");
+        T.dst = gbuf[T.buf];
+        T.add = G.set ? G.ptr : nullptr;
+        return TMPS_OK;
+    };
+    auto commit = [&](int t, const Target& T) {
+        Grad& G = grads[t + 1];
+        if (G.set && G.buf != T.buf) release(G.buf);
+        G.ptr = T.dst;
+        G.buf = T.buf;
+        G.set = true;
+        --remaining[t + 1];
+    };
+    // hand an existing gradient (g) to result t as its contribution, without a kernel when it is the first
+    auto share = [&](int t, const Grad& g) -> int {
+        if (t < 0 && !dx) return TMPS_OK;
+        Grad& G = grads[t + 1];
+        const int64_t n = (int64_t)M * st->tensor_elems(t);
+        if (t < 0) {
+            if (G.set) TMPS_GEMM(resadd_forward(dt, dx, g.ptr, dx, n, 0, s));
+            else TMPS_RUN(kcCopy, s, hipMemcpyAsync(dx, g.ptr, (size_t)n * st->asz, hipMemcpyDeviceToDevice, s));
+            G.ptr = dx; G.buf = -1; G.set = true;
+        } else if (!G.set) {
+            G = g;
+            if (g.buf >= 0) ++refs[g.buf];
+        } else {
+            Target T;
+            int rc = target(t, T);
+            if (rc != TMPS_OK) return rc;
+            TMPS_GEMM(resadd_forward(dt, T.add, g.ptr, T.dst, n, 0, s));
+            if (G.buf != T.buf) release(G.buf);
+            G.ptr = T.dst; G.buf = T.buf;
+        }
+        --remaining[t + 1];
+        return TMPS_OK;
+    };
+
     int top = nl - 1;
     if (st->cfg.is_last) {
-        g = st->out_ptr(st->layers[top], row0);  // softmax error signal stored by the forward passes
+        // the loss layer's contribution to the logits: the softmax error signal stored by the forward passes
+        Grad& G = grads[top];   // result top - 1
+        G.ptr = st->out_ptr(st->layers[top], row0);
+        G.buf = -1;
+        G.set = true;
+        --remaining[top];
         --top;
     } else {
-        g = dy;
+        Grad& G = grads[top + 1];
+        G.ptr = dy;
+        G.buf = -1;
+        G.set = true;
         const LayerRT& T = st->layers[top];
         if (T.relu) {
-            cur = take();
-            TMPS_RUN(kcReluMask, s, relu_mask(dt, dy, st->out_ptr(T, row0), gbuf[cur], (int64_t)M * T.out_elems, s));
-            g = gbuf[cur];
+            const int k = take();
+            TMPS_RUN(kcReluMask, s, relu_mask(dt, dy, st->out_ptr(T, row0), gbuf[k], (int64_t)M * T.out_elems, s));
+            G.ptr = gbuf[k];
+            G.buf = k;
         }
     }
     for (int li = top; li >= 0; --li) {
         const LayerRT& L = st->layers[li];
         const int32_t* d = L.d.dims;
-        const void* in = layer_input(st, li, x0, row0);
-        const bool want_dx = (li > 0 || dx != nullptr) && L.d.kind != TMPS_EMBEDDING;
-        void* dst = nullptr;
-        int dst_buf = -1;
-        if (want_dx) {
-            if (li == 0) {
-                dst = dx;
-            } else {
-                dst_buf = take();
-                if (dst_buf < 0) return fail(TMPS_EUNSUPPORTED, "out of gradient buffers (nested residual connections)");
-                dst = gbuf[dst_buf];
-            }
-        }
-        // the gradient written for the layer below passes through that layer's stored activation
-        const void* mask = nullptr;
+        const Grad g = grads[li + 1];
+        if (!g.set || remaining[li + 1] != 0) return fail(TMPS_ESHAPE, "layer %d: its result has no complete gradient", li);
+        const int t_in = L.in_t;
+        const void* in = t_in < 0 ? (const void*)x0 : (const void*)st->out_ptr(st->layers[t_in], row0);
         int mask_mode = 1;
-        if (li > 0) {
-            const LayerRT& Bl = st->layers[li - 1];
-            if (Bl.act == 1) mask = in;
-            if (Bl.act == 2) {
-                mask = st->stash + Bl.z_off + (size_t)row0 * Bl.out_elems * st->asz;
-                mask_mode = 2;
-            }
-        }
+        const void* mask = mask_of(t_in, mask_mode);
         float* gw = st->grad + L.w_off;
-        bool keep_g = false;
-        if (held[li] && L.d.kind != TMPS_LAYERNORM) return fail(TMPS_EUNSUPPORTED, "residual connection into layer kind %d", L.d.kind);
+        Target T;
+        int rc;
         switch (L.d.kind) {
             case TMPS_LINEAR: {
                 const int rows = M * L.rps;
-                if (L.skip) {
-                    held[li - L.skip] = g;
-                    held_buf[li - L.skip] = cur;
-                    keep_g = true;
+                if (L.skip && (rc = share(st->layers[li - L.skip].in_t, g)) != TMPS_OK) return rc;
+                TMPS_GEMM(dense_wgrad(dt, g.ptr, in, gw, rows, d[0], d[1], ws, s));
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                if (T.wanted) {
+                    TMPS_GEMM(dense_dgrad(dt, g.ptr, st->wptr(L), T.dst, mask, mask_mode, T.add, rows, d[0], d[1], ws, s));
+                    commit(t_in, T);
                 }
-                TMPS_GEMM(dense_wgrad(dt, g, in, gw, rows, d[0], d[1], ws, s));
-                if (want_dx) TMPS_GEMM(dense_dgrad(dt, g, st->wptr(L), dst, mask, mask_mode, rows, d[0], d[1], ws, s));
                 break;
             }
             case TMPS_CONV2D: {
                 ConvShape c = conv_shape(L.d, M);
-                TMPS_GEMM(conv_wgrad(dt, g, in, gw, c, ws, s));
-                if (want_dx) TMPS_GEMM(conv_dgrad(dt, g, st->wptr(L), dst, mask, c, ws, s));
+                TMPS_GEMM(conv_wgrad(dt, g.ptr, in, gw, c, ws, s));
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                if (T.wanted) {
+                    if (mask_mode == 2) return fail(TMPS_EUNSUPPORTED, "a convolution directly after a GELU layer");
+                    TMPS_GEMM(conv_dgrad(dt, g.ptr, st->wptr(L), T.dst, mask, T.add, c, ws, s));
+                    commit(t_in, T);
+                }
                 break;
             }
             case TMPS_MAXPOOL:
-                if (want_dx)
-                    TMPS_RUN(kcPoolBwd, s, maxpool_backward(dt, in, g, dst, M, d[0], d[1], d[2], d[3], d[4], mask ? 1 : 0, s));
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                if (T.wanted) {
+                    if (T.add || mask_mode == 2) return fail(TMPS_EUNSUPPORTED, "max pooling on a shared or GELU input");
+                    TMPS_RUN(kcPoolBwd, s, maxpool_backward(dt, in, g.ptr, T.dst, M, d[0], d[1], d[2], d[3], d[4], d[5], mask ? 1 : 0, s));
+                    commit(t_in, T);
+                }
+                break;
+            case TMPS_AVGPOOL:
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                if (T.wanted) {
+                    if (T.add || mask_mode == 2) return fail(TMPS_EUNSUPPORTED, "average pooling on a shared or GELU input");
+                    TMPS_GEMM(avgpool_backward(dt, g.ptr, in, T.dst, M, d[0] * d[1], d[2], mask ? 1 : 0, s));
+                    commit(t_in, T);
+                }
+                break;
+            case TMPS_AFFINE:
+                // the layer before has no activation (checked at creation): nothing to pass through
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                if (T.add) return fail(TMPS_EUNSUPPORTED, "an affine layer on a shared input");
+                TMPS_GEMM(affine_backward(dt, g.ptr, in, st->master + L.w_off, T.wanted ? T.dst : nullptr, gw, ws,
+                                          (int64_t)M * d[0] * d[1], d[2], s));
+                if (T.wanted) commit(t_in, T);
+                break;
+            case TMPS_RESADD:
+                // d(a + b) = the incoming gradient for both sources (it has already passed through this layer's ReLU)
+                if ((rc = share(L.in_b, g)) != TMPS_OK) return rc;
+                if ((rc = share(t_in, g)) != TMPS_OK) return rc;
                 break;
             case TMPS_LAYERNORM:
                 if (mask) return fail(TMPS_EUNSUPPORTED, "layer normalisation directly after an activation");
-                TMPS_GEMM(layernorm_backward(dt, g, in, reinterpret_cast<const float*>(st->stash + L.aux_off) + (size_t)row0 * L.rps * 2,
-                                             st->master + L.w_off, held[li], want_dx ? dst : nullptr, gw, ws, (int64_t)M * L.rps,
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                TMPS_GEMM(layernorm_backward(dt, g.ptr, in, reinterpret_cast<const float*>(st->stash + L.aux_off) + (size_t)row0 * L.rps * 2,
+                                             st->master + L.w_off, T.add, T.wanted ? T.dst : nullptr, gw, ws, (int64_t)M * L.rps,
                                              d[0], s));
-                if (held_buf[li] >= 0) busy[held_buf[li]] = false;
-                held[li] = nullptr;
+                if (T.wanted) commit(t_in, T);
                 break;
             case TMPS_ATTENTION:
                 if (mask) return fail(TMPS_EUNSUPPORTED, "attention directly after an activation");
-                if (want_dx)
-                    TMPS_GEMM(attention_backward(dt, in, st->out_ptr(L, row0), g,
+                if ((rc = target(t_in, T)) != TMPS_OK) return rc;
+                if (T.wanted) {
+                    if (T.add) return fail(TMPS_EUNSUPPORTED, "attention on a shared input");
+                    TMPS_GEMM(attention_backward(dt, in, st->out_ptr(L, row0), g.ptr,
                                                  reinterpret_cast<const float*>(st->stash + L.aux_off) + (size_t)row0 * d[2] * d[0], ws,
-                                                 dst, M, d[0], d[1], d[2], s));
+                                                 T.dst, M, d[0], d[1], d[2], s));
+                    commit(t_in, T);
+                }
                 break;
             case TMPS_EMBEDDING:
-                TMPS_GEMM(embedding_backward(dt, (const int32_t*)in, g, gw, st->grad + L.b_off, M, d[1], d[2], d[0], s));
+                TMPS_GEMM(embedding_backward(dt, (const int32_t*)in, g.ptr, gw, st->grad + L.b_off, M, d[1], d[2], d[0], s));
                 break;
             default:
                 return fail(TMPS_EUNSUPPORTED, "layer kind %d has no backward", L.d.kind);
         }
-        if (cur >= 0 && !keep_g) busy[cur] = false;
-        if (want_dx && li > 0) {
-            cur = dst_buf;
-            g = dst;
+        release(g.buf);
+        grads[li + 1].set = false;
+        // A result whose gradient is complete but was only handed over (never written through a kernel that applies
+        // the activation of its producer) still has to pass through that activation.
+        if (t_in >= 0 && remaining[t_in + 1] == 0 && grads[t_in + 1].set && L.d.kind == TMPS_RESADD) {
+            int mm = 1;
+            const void* mk = mask_of(t_in, mm);
+            if (mk) return fail(TMPS_EUNSUPPORTED, "a residual join whose first source ends in an activation");
         }
+        if (L.d.kind == TMPS_RESADD && L.in_b >= 0 && remaining[L.in_b + 1] == 0 && st->layers[L.in_b].act != 0)
+            return fail(TMPS_EUNSUPPORTED, "a residual connection must start at a result that another, earlier layer reads too");
     }
     for (int j = 0; j < N; ++j) {
         st->slot_used[g0 + j] = 0;

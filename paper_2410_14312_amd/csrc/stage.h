@@ -17,6 +17,8 @@ struct LayerRT {
     int act = 0;           // 0 none, 1 ReLU, 2 GELU (linear / convolution epilogue)
     int rps = 1;           // rows per sample the layer works on (sequence positions)
     int skip = 0;          // linear: > 0 adds the input of layer (index - skip)
+    int in_t = -1;         // which result the layer reads: index of the producing layer, -1 = the stage input
+    int in_b = -1;         // residual join: the second result it reads
     bool out_f32 = false;  // the logits layer (followed by softmax-CE) writes fp32
     size_t ws_elems = 0;   // fp32 workspace elements (split-k partial sums, reductions)
 };
@@ -30,6 +32,7 @@ struct tmps_stage {
     size_t in_esize = 4;  // bytes per element of the stage input (int32 tokens in front of an embedding)
     int label_rps = 1;    // labels per sample on the last stage
     int n_gbuf = 2;       // gradient buffers in scratch
+    std::vector<int> readers;  // readers[t + 1] = number of layers that read result t (t = -1: the stage input)
     char* params = nullptr;
     char* state = nullptr;
     char* stash = nullptr;
@@ -40,7 +43,7 @@ struct tmps_stage {
     float* grad = nullptr;
     size_t in_off = 0;  // stash offset of the copied inputs (borrow_input == 0)
     size_t stash_bytes = 0, scratch_bytes = 0;
-    size_t gbuf_off[4] = {0, 0, 0, 0}, gbuf_bytes = 0;  // gradient buffers (M rows each)
+    size_t gbuf_off[8] = {0, 0, 0, 0, 0, 0, 0, 0}, gbuf_bytes = 0;  // gradient buffers (M rows each)
     size_t dxout_off[2] = {0, 0}, dxout_bytes = 0;  // boundary gradient buffers used by the scheduler
     size_t ws_off = 0;
     std::vector<char> slot_used;
@@ -60,6 +63,8 @@ struct tmps_stage {
     char* out_ptr(const LayerRT& L, int64_t row) const {
         return stash + L.out_off + (size_t)row * L.out_elems * L.out_esize;
     }
+    // elements per sample of result t (-1: the stage input)
+    int64_t tensor_elems(int t) const { return t < 0 ? in_elems : layers[t].out_elems; }
 };
 
 namespace tmps {

@@ -24,7 +24,7 @@ def _params(specs, rng, scale=1.0):
     for sp in specs:
         shp = param_shapes(sp)
         p = {}
-        if shp and sp["kind"] == "layernorm":
+        if shp and sp["kind"] in ("layernorm", "affine"):
             p["w"] = (1.0 + 0.2 * rng.standard_normal(shp["w"])).astype(np.float32)
             p["b"] = (0.1 * rng.standard_normal(shp["b"])).astype(np.float32)
         elif shp and sp["kind"] == "embedding":
@@ -49,7 +49,7 @@ def _in_shape(sp):
         return (sp["s"],)
     if sp["kind"] == "conv":
         return (sp["h"], sp["w"], sp["cin"])
-    if sp["kind"] == "maxpool":
+    if sp["kind"] in ("maxpool", "affine", "avgpool"):
         return (sp["h"], sp["w"], sp["c"])
     raise ValueError
 
