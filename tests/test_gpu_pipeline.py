@@ -92,6 +92,12 @@ def test_small_conv_net_three_stages(dtype):
     _compare(cfg, 5, bias_std=0.05)
 
 
+@pytest.mark.parametrize("name", ["tiny_transformer_f32", "tiny_transformer_bf16", "tiny_resnet_f32", "tiny_resnet_bf16"])
+def test_small_transformer_and_residual_networks(name):
+    cfg = get_config(name)
+    _compare(cfg, 5, bias_std=0.05)
+
+
 def test_vgg16_bf16_two_steps():
     cfg = get_config("vgg16_bf16")
     _compare(cfg, 2)

@@ -54,7 +54,21 @@ def _in_shape(sp):
     raise ValueError
 
 
-def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False):
+def _cos(a, b):
+    a, b = np.asarray(a, np.float64).ravel(), np.asarray(b, np.float64).ravel()
+    return float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
+
+
+def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False, deep=False):
+    """deep (bf16 only): a stage of tens of ReLU layers.  The two sides store the same bf16 tensors only up to
+    rounding ties (fp32 against fp64 sums); a stored activation that lands on the other side of zero flips its
+    ReLU mask, the flips accumulate along the backward pass, and after a few dozen layers two CORRECT
+    evaluations of the same stage differ by a few percent in the gradients of the earliest layers (the effect
+    tests/test_oracle_precision.py measures between two precisions of the oracle itself).  Such stages are held
+    to relative L2 error < 0.2 and direction cosine > 0.98 in bf16.  In fp32 the same happens to a handful of
+    activations that lie within rounding of zero, and one flipped mask perturbs the whole receptive field below
+    it (a whole 14 x 14 image after six blocks): there the element-wise bar must hold on 90 % of the elements
+    of the input gradient, and the relative L2 error of every result must stay below 1e-2."""
     import torch
     from paper_2410_14312_amd import Stage
 
@@ -121,8 +135,20 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False):
     if tokens_in:
         assert o_dx is None
     got_dx = None if tokens_in else gst.crop_input_grad(dxd, M).reshape(o_dx.shape)
+    deep32 = deep and dtype == "f32"
+    deep = deep and dtype == "bf16"
+
+    def mostly(got, ref, what, per_sample=True):
+        # a weight gradient sums over all samples, so one perturbed sample touches every element of it a little
+        f, l2 = frac_outside(got, ref, tol), rel_l2(got, ref)
+        assert (f < 0.1 or not per_sample) and l2 < 1e-2, "%s: %g of the elements outside, l2 %g" % (what, f, l2)
+
     if tokens_in:
         pass
+    elif deep32:
+        mostly(got_dx, o_dx, "dx")
+    elif deep:
+        assert rel_l2(got_dx, o_dx) < 0.2 and _cos(got_dx, o_dx) > 0.98, "dx: l2 %g cos %g" % (rel_l2(got_dx, o_dx), _cos(got_dx, o_dx))
     elif has_pool and dtype == "bf16":
         # near-ties of a pooling window can be won by a different element in bf16 than in fp64: such
         # isolated reroutings are valid; everything else must agree
@@ -134,6 +160,13 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False):
         if g is None:
             continue
         for k in g:
+            if deep:
+                a, b = grads[li][k], g[k]
+                assert rel_l2(a, b) < 0.2 and _cos(a, b) > 0.98, "grad layer %d %s: l2 %g cos %g" % (li, k, rel_l2(a, b), _cos(a, b))
+                continue
+            if deep32:
+                mostly(grads[li][k], g[k], "grad layer %d %s" % (li, k), per_sample=False)
+                continue
             if has_pool and dtype == "bf16":
                 # the gradient below a pooling layer is sparse (one winner per window), so each rerouted
                 # winner is a visible share of a weight-gradient sum: hold these to the L2 norm and direction
@@ -150,20 +183,21 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False):
     torch.cuda.synchronize()
     assert gst.version() == 1
     w_after = gst.get_params()
-    loose = has_pool and dtype == "bf16"
+    loose = (has_pool and dtype == "bf16") or deep or deep32
+    step_tol = 0.2 if deep else (1e-2 if deep32 else (3 * tol if loose else tol))
     for li, p in enumerate(ost.params):
         for k in p:
-            assert (rel_l2(w_after[li][k], p[k]) if loose else rel_err(w_after[li][k], p[k])) < tol
+            assert (rel_l2(w_after[li][k], p[k]) if loose else rel_err(w_after[li][k], p[k])) < (step_tol if (deep or deep32) else tol)
             # the step itself, not hidden behind the size of the weights
             step_g = w_after[li][k].astype(np.float64) - w_before[li][k]
             step_o = p[k] - p1[li][k].astype(np.float64)
             e = rel_l2(step_g, step_o) if loose else rel_err(step_g, step_o)
-            assert e < (3 * tol if loose else tol), "update step layer %d %s: %g" % (li, k, e)
+            assert e < step_tol, "update step layer %d %s: %g" % (li, k, e)
     mom = gst.get_momentum()
     for li, b in enumerate(ost.bufs):
         for k in b:
             e = rel_l2(mom[li][k], b[k]) if loose else rel_err(mom[li][k], b[k])
-            assert e < (3 * tol if loose else tol)
+            assert e < step_tol
     # slots were freed: the group can be forwarded into again
     gst.forward_micro(base, xd[:micro], labels=ld[:micro] if is_last else None)
     torch.cuda.synchronize()
