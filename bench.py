@@ -79,8 +79,20 @@ def algorithmic_work(cfg):
                 add("conv_wgrad", 1, 2.0 * M * ho * wo * kk * sp["cout"], M * (x_e + y_e) * asz + kk * sp["cout"] * 4)
                 if not (si == 0 and li == 0):
                     add("conv_dgrad", 1, 2.0 * M * ho * wo * kk * sp["cout"], M * (x_e + y_e) * asz + kk * sp["cout"] * asz)
+            elif sp["kind"] == "affine":
+                e = sp["h"] * sp["w"] * sp["c"]
+                P += 2 * sp["c"]
+                add("affine", N + 2, 0.0, N * mb * 2 * e * asz + M * 3 * e * asz)
+            elif sp["kind"] == "resadd":
+                e = sp["h"] * sp["w"] * sp["c"]
+                add("resadd", N, 0.0, N * mb * 3 * e * asz)
+            elif sp["kind"] == "avgpool":
+                e = sp["h"] * sp["w"] * sp["c"]
+                add("pool_fwd", N, 0.0, N * mb * (e + sp["c"]) * asz)
+                add("pool_bwd", 1, 0.0, M * (2 * e + sp["c"]) * asz)
             elif sp["kind"] == "maxpool":
-                ho, wo = (sp["h"] - sp["k"]) // sp["stride"] + 1, (sp["w"] - sp["k"]) // sp["stride"] + 1
+                pad = sp.get("pad", 0)
+                ho, wo = (sp["h"] + 2 * pad - sp["k"]) // sp["stride"] + 1, (sp["w"] + 2 * pad - sp["k"]) // sp["stride"] + 1
                 x_e, y_e = sp["h"] * sp["w"] * sp["c"], ho * wo * sp["c"]
                 add("pool_fwd", N, 0.0, N * mb * (x_e + y_e) * asz)
                 add("pool_bwd", 1, 0.0, M * (2 * x_e + y_e) * asz)
@@ -93,7 +105,7 @@ def algorithmic_work(cfg):
 
 # classes whose kernels carry their own start/stop timestamps (no bracket overhead)
 KERNEL_STAMPED = ("dense_fwd", "dense_dgrad", "dense_wgrad", "conv_fwd", "conv_dgrad", "conv_wgrad", "splitk_finish",
-                  "slice_sum", "layernorm", "attn_fwd", "attn_bwd", "embedding")
+                  "slice_sum", "layernorm", "attn_fwd", "attn_bwd", "embedding", "affine", "resadd")
 
 
 def measured_traffic(workload, kernel_class):
@@ -193,7 +205,7 @@ def main():
         kernels.append(ent)
     kernels.sort(key=lambda e: -e["ms_per_step"])
     dom = kernels[0]
-    if dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce", "layernorm", "embedding"):
+    if dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce", "layernorm", "embedding", "affine", "resadd"):
         roof = {"kernel": dom["class"], "bound": "hbm", "achieved": dom.get("gbs", 0.0), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": dom.get("gbs", 0.0) / HBM_PEAK_GBS, "traffic": None}
     else:

@@ -342,7 +342,22 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN, z = blockIdx.z;
+    // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin in launch order.  Renumber the tiles
+    // of a k-slice so that the workgroups of one XCD own a contiguous run of tiles in row-major order: the tiles of
+    // a row share their A panel and then find it in their own L2, instead of every XCD fetching every panel.
+    int tile_x = blockIdx.x, tile_y = blockIdx.y;
+    {
+        const int gx = gridDim.x, nb = gridDim.x * gridDim.y;
+        if (nb >= 16) {
+            const int lin = tile_y * gx + tile_x;
+            const int xcd = lin & 7, idx = lin >> 3;
+            const int q = nb >> 3, r = nb & 7;
+            const int moved = xcd * q + min(xcd, r) + idx;
+            tile_y = moved / gx;
+            tile_x = moved - tile_y * gx;
+        }
+    }
+    const int m0 = tile_y * BM, n0 = tile_x * BN, z = blockIdx.z;
     const int k_begin = z * k_per_slice;
     const int k_end = min(K, k_begin + k_per_slice);
     const int nk = (k_end - k_begin + kBK2 - 1) / kBK2;
@@ -432,7 +447,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
-        if (ROWSUM && blockIdx.x == 0 && tid < BM) {
+        if (ROWSUM && tile_x == 0 && tid < BM) {
             if constexpr (AKC) {
                 const bf16_t* rowp = tA + tid * TileShape<BM, true>::pitch;
 #pragma unroll 8
@@ -495,7 +510,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
                 }
             }
     }
-    if (ROWSUM && blockIdx.x == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
+    if (ROWSUM && tile_x == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
 }
 
 // Split-k partial sums: slice z stores fp32 at part[z][m][n].

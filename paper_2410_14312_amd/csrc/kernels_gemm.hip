@@ -5,7 +5,7 @@
 // fp32 stages use the fp32 skeleton.
 #include <hip/hip_ext.h>
 
-#include "gemm2.hip.h"
+#include "gemm3.hip.h"
 #include "kernels.h"
 #include "launch.h"
 #include "profile.h"
@@ -24,7 +24,10 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const int64_t t128 = (int64_t)cdiv(M, 128) * cdiv(N, 128);
     const int64_t t64 = (int64_t)cdiv(M, 64) * cdiv(N, 64);
     const bool wide = N > 64 && M > 64;
-    p.tile = (wide && t128 >= 64) ? 128 : 64;
+    // A short output (a micro-batch's rows) with fewer 128-tiles than compute units is latency-bound: more, smaller
+    // workgroups finish sooner (measured on 1024-row transformer GEMMs: 13 us against 16 us).
+    const bool short_rows = M <= 2048 && t128 < 256;
+    p.tile = (wide && t128 >= 64 && !short_rows) ? 128 : 64;
     const int64_t tiles = p.tile == 128 ? t128 : t64;
     const int64_t target = 384;  // swept 32..2048 on the VGG workload: flat optimum around 384-512
     int64_t s = 1;
@@ -41,10 +44,17 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     return p;
 }
 
+static int g3_wgrad_slices(int64_t M, int64_t N, int64_t K);
+
 size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t K, int with_rowsum) {
     GemmPlan p = plan_gemm(M, N, K);
-    if (p.slices <= 1) return 0;
-    return (size_t)p.slices * ((size_t)M * N + (with_rowsum ? (size_t)M : 0));
+    int slices = p.slices;
+    if (with_rowsum) {   // a weight gradient may go to the persistent path, with its own number of slices
+        const int s3 = g3_wgrad_slices(M, N, K);
+        if (s3 > slices) slices = s3;
+    }
+    if (slices <= 1) return 0;
+    return (size_t)(slices + 1) * ((size_t)M * N + (with_rowsum ? (size_t)M : 0));
 }
 
 __global__ void slice_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int64_t count,
@@ -124,6 +134,56 @@ static int one_slice(int64_t K, int ktile) {
     return per < ktile ? ktile : per;
 }
 
+// ---- persistent MFMA path (gemm3.hip.h): large dense contractions --------------------------------------
+static int compute_units() {
+    static int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
+constexpr int kG3Tile = 256;
+static int64_t g3_tiles(int64_t M, int64_t N) { return (int64_t)cdiv(M, kG3Tile) * cdiv(N, kG3Tile); }
+// k-slices of a weight-gradient contraction on the persistent path (0: leave it to the other path).  Measured:
+// the path pays once a launch has about as many (tile, slice) units as the device has compute units.
+static int g3_wgrad_slices(int64_t M, int64_t N, int64_t K) {
+    if (K % 64 != 0 || M % 8 != 0 || N % 8 != 0) return 0;
+    const int64_t tiles = g3_tiles(M, N);
+    int64_t s = tiles >= 192 ? 1 : 256 / tiles;
+    if (s > K / 1024) s = K / 1024;
+    if (s < 1) s = 1;
+    return tiles * s >= 144 ? (int)s : 0;
+}
+static bool g3_forward_ok(int64_t M, int64_t N, int64_t K) { return K % 64 == 0 && N % 8 == 0 && g3_tiles(M, N) >= 192; }
+
+static G3Plan g3_plan(int M, int N, int K, int slices) {
+    G3Plan p;
+    p.tiles_m = cdiv(M, kG3Tile);
+    p.tiles_n = cdiv(N, kG3Tile);
+    int per = cdiv(cdiv(K, slices), 64) * 64;
+    p.k_per_slice = per;
+    p.slices = cdiv(K, per);
+    p.units = p.tiles_m * p.tiles_n * p.slices;
+    p.d_tn = FastDiv(p.tiles_n);
+    p.d_tiles = FastDiv(p.tiles_m * p.tiles_n);
+    return p;
+}
+
+// 256 x 256 x 64 tiles, 8 waves (2 x 4), two LDS stages: the configuration that did best on every large shape tried.
+template <bool AKC, bool BKC, bool ROWSUM, class Epi>
+static hipError_t launch3(int kc, const G3Operand<AKC>& A, const G3Operand<BKC>& B, const Epi& epi, int M, int N, int K,
+                          const G3Plan& plan, hipStream_t s) {
+    constexpr int lds = gemm3_lds_bytes<256, 256, 64, 2>();
+    auto kern = gemm3_kernel<256, 256, 64, 2, 4, 2, AKC, BKC, ROWSUM, Epi>;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    const int grid = plan.units < compute_units() ? plan.units : compute_units();
+    return launch_timed(kc, kern, dim3(grid), dim3(512), lds, s, A, B, epi, M, N, K, plan);
+}
+
 // ---- element-wise fallbacks ------------------------------------------------------------------
 template <bool ROWSUM, class AOp, class BOp, class Epi>
 static hipError_t launch_bf16(int kc, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, int per,
@@ -166,6 +226,13 @@ hipError_t dense_forward(int dtype, const void* x, const void* w, const float* b
                          int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
     if (dtype == kBF16) {
         const bool fast = (Din % 8 == 0) && aligned16(x) && aligned16(w);
+        if (fast && g3_forward_ok(B, Dout, Din) && aligned16(y) && aligned16(bias) && aligned16(res) && aligned16(zout)) {
+            G3Operand<true> A{(const bf16_t*)x, B, Din};
+            G3Operand<true> Bv{(const bf16_t*)w, Dout, Din};
+            const G3Plan plan = g3_plan(B, Dout, Din, 1);
+            if (out_f32) return launch3<true, true, false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, plan, s);
+            return launch3<true, true, false>(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, plan, s);
+        }
         if (fast) {
             DenseKC A{(const bf16_t*)x, B, Din, Din};
             DenseKC Bv{(const bf16_t*)w, Dout, Din, Din};
@@ -188,6 +255,11 @@ hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode, (const bf16_t*)add};
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(w);
+        if (fast && g3_forward_ok(B, Din, Dout) && aligned16(dx) && aligned16(mask) && aligned16(add)) {
+            G3Operand<true> A{(const bf16_t*)dy, B, Dout};
+            G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
+            return launch3<true, false, false>(kcDenseDgrad, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1), s);
+        }
         if (fast) {
             DenseKC A{(const bf16_t*)dy, B, Dout, Dout};
             DenseRC Bv{(const bf16_t*)w, Din, Dout, Din};
@@ -207,6 +279,18 @@ hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int 
     // gw[m, n] = sum_k dy[k, m] * x[k, n]: both operands row-contiguous, contraction over the batch
     if (dtype == kBF16) {
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(x);
+        const int s3 = fast && aligned16(gw) ? g3_wgrad_slices(Dout, Din, B) : 0;
+        if (s3 >= 1 && (s3 == 1 || (ws && aligned16(ws)))) {
+            G3Operand<false> A{(const bf16_t*)dy, Dout, Dout};
+            G3Operand<false> Bv{(const bf16_t*)x, Din, Din};
+            const G3Plan plan = g3_plan(Dout, Din, B, s3);
+            const int64_t count = (int64_t)Dout * Din + Dout;
+            EpiWgrad epi{plan.slices > 1 ? ws : gw, Din, (int64_t)Dout * Din, count};
+            hipError_t e = launch3<false, false, true>(kcDenseWgrad, A, Bv, epi, Dout, Din, B, plan, s);
+            if (e != hipSuccess || plan.slices <= 1) return e;
+            return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw, count,
+                                plan.slices);
+        }
         if (fast) {
             DenseRC A{(const bf16_t*)dy, Dout, B, Dout};
             DenseRC Bv{(const bf16_t*)x, Din, B, Din};

@@ -209,6 +209,11 @@ DENSE_CASES = [
     (100, 72, True, 24, 3),      # ragged in every dimension
     (200, 300, False, 70, 2),    # several tiles + tails, no ReLU
     (1024, 1024, True, 64, 4),   # the bf16 MLP config's hidden stage
+    # no ReLU on the three large cases: among 10^7 pre-activations one lies within fp32 rounding of zero, and its
+    # mask then differs between the fp32 and the fp64 evaluation
+    (128, 6144, False, 2048, 1), # wide output, many rows: the persistent 256x256 kernel in the forward pass
+    (6144, 128, False, 1024, 2), # wide input: the persistent kernel in the input-gradient pass
+    (1024, 1024, False, 4608, 2),  # long batch: the persistent kernel, k-split, in the weight-gradient pass
 ]
 
 

@@ -51,10 +51,10 @@ def maxpool(h, w, c, k=2, stride=2, pad=0):
             "stride": int(stride), "pad": int(pad)}
 
 
-def affine(h, w, c, relu):
+def affine(h, w, c, relu, init_gain=1.0):
     """Trainable per-channel scale and shift (a batch-normalisation layer with its statistics folded away):
-    y = gain[c] * x + shift[c], then ReLU if asked."""
-    return {"kind": "affine", "h": int(h), "w": int(w), "c": int(c), "relu": bool(relu)}
+    y = gain[c] * x + shift[c], then ReLU if asked.  init_gain: the value the gains start from."""
+    return {"kind": "affine", "h": int(h), "w": int(w), "c": int(c), "relu": bool(relu), "init_gain": float(init_gain)}
 
 
 def resadd(h, w, c, src_b, relu=True):
@@ -71,12 +71,15 @@ def avgpool(h, w, c):
 def bottleneck(h, cin, width, stride, project):
     """ResNet bottleneck block on an h x h x cin input: 1x1 (width) - 3x3 (width, stride) - 1x1 (4 width), each
     followed by a per-channel affine layer, ReLU after the first two; the block input (or, in the first block
-    of a group, a strided 1x1 projection of it with its own affine layer) is added before the last ReLU."""
+    of a group, a strided 1x1 projection of it with its own affine layer) is added before the last ReLU.
+    The last affine layer of the main path starts from gain 0.2: with no batch statistics to renormalise them,
+    sixteen blocks that each add a full-size branch to their input would grow the activations and gradients
+    by orders of magnitude, and plain SGD at the configured rate diverges within a few steps."""
     ho = (h + 2 - 3) // stride + 1
     cout = 4 * width
     layers = [conv(h, h, cin, width, 1, 1, 0, False), affine(h, h, width, True),
               conv(h, h, width, width, 3, stride, 1, False), affine(ho, ho, width, True),
-              conv(ho, ho, width, cout, 1, 1, 0, False), affine(ho, ho, cout, False)]
+              conv(ho, ho, width, cout, 1, 1, 0, False), affine(ho, ho, cout, False, init_gain=0.2)]
     if project:
         # the projection reads the block input: 7 positions before itself
         layers += [conv(h, h, cin, cout, 1, stride, 0, False, src=7), affine(ho, ho, cout, False),
@@ -193,7 +196,7 @@ def _resnet(name, dtype, size, widths, blocks, classes, M, N, seed, stem_c=64):
     return Config(name=name, dtype=dtype, M=M, N=N, seed=seed, steps=2, in_shape=(size, size, 3), classes=classes,
                   stages=stages,
                   notes="bottleneck blocks, batch normalisation folded to a trainable per-channel affine layer (gain 1, "
-                        "shift 0 at the start), stride on the 3x3, projection shortcut in the first block of each group, "
+                        "shift 0 at the start, gain 0.2 on the last affine layer of every block), stride on the 3x3, projection shortcut in the first block of each group, "
                         "bias on every convolution")
 
 

@@ -59,7 +59,7 @@ def init_params(cfg, bias_std=0.0):
             p = {}
             if shp and layer["kind"] in ("layernorm", "affine"):
                 g = _rng(cfg.seed, 1, idx)
-                p["w"] = np.ones(shp["w"], dtype=np.float32)
+                p["w"] = np.full(shp["w"], layer.get("init_gain", 1.0), dtype=np.float32)
                 p["b"] = np.zeros(shp["b"], dtype=np.float32)
                 if bias_std > 0.0:
                     p["w"] += (g.standard_normal(shp["w"]) * bias_std).astype(np.float32)
