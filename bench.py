@@ -82,7 +82,9 @@ def algorithmic_work(cfg):
             elif sp["kind"] == "affine":
                 e = sp["h"] * sp["w"] * sp["c"]
                 P += 2 * sp["c"]
-                add("affine", N + 2, 0.0, N * mb * 2 * e * asz + M * 3 * e * asz)
+                # the forward pass runs inside the convolution's epilogue; what is launched is the backward pass
+                # (read dy and x, write dx) and the reduction of its per-slab partial sums
+                add("affine", 2, 0.0, M * 3 * e * asz)
             elif sp["kind"] == "resadd":
                 e = sp["h"] * sp["w"] * sp["c"]
                 add("resadd", N, 0.0, N * mb * 3 * e * asz)

@@ -203,6 +203,14 @@ int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, cons
                       const int32_t* labels, void** hip_streams, float* losses_out,
                       int32_t* version_log_out);
 
+/* Streams for tmps_schedule_run.  The runtime spreads streams over a small number of hardware queues in creation
+ * order; streams that land on the same queue run one after the other.  tmps_streams_create makes n streams back to
+ * back (default priority, non-blocking with respect to the null stream), which puts up to as many of them as there are
+ * hardware queues on distinct queues.  out: host array of n stream handles.  The caller destroys them with
+ * tmps_streams_destroy once no work is pending on them.  Returns TMPS_OK or TMPS_EHIP. */
+int tmps_streams_create(void** out, int n);
+int tmps_streams_destroy(void** streams, int n);
+
 /* ---- measurement aid (not part of the method) ----
  *
  * While enabled, every kernel launch made by the calls above is timed with HIP events on the stream

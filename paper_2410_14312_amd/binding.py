@@ -52,6 +52,8 @@ EXPORTS = {
     "tmps_version_diff_simulated": (C.c_int, [C.c_int, C.c_int]),
     "tmps_schedule_run": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                     C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_int32)]),
+    "tmps_streams_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_int]),
+    "tmps_streams_destroy": (C.c_int, [C.POINTER(C.c_void_p), C.c_int]),
     "tmps_profile_enable": (C.c_int, [C.c_int]),
     "tmps_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]),
     "tmps_last_error": (C.c_char_p, []),
@@ -330,9 +332,25 @@ class Pipeline:
                        borrow_input=True, device=device)
             st.set_params(params[s])
             self.stages.append(st)
+        # K streams created back to back by the library, so that they land on distinct hardware queues (streams from
+        # torch's pool may share one, and then two workers run one after the other); wrapped for torch.
         # one_stream: every worker issues on the same stream, so kernels never overlap (for per-kernel timing)
-        shared = torch.cuda.Stream(device=self.device) if one_stream else None
-        self.streams = [shared if one_stream else torch.cuda.Stream(device=self.device) for _ in range(K)]
+        n = 1 if one_stream else K
+        self._raw_streams = (C.c_void_p * n)()
+        with torch.cuda.device(self.device):
+            _check(lib().tmps_streams_create(self._raw_streams, n))
+        ext = [torch.cuda.ExternalStream(int(self._raw_streams[i]), device=self.device) for i in range(n)]
+        self.streams = [ext[0] if one_stream else ext[s] for s in range(K)]
+
+    def __del__(self):
+        raw = getattr(self, "_raw_streams", None)
+        if raw is not None and _lib is not None:
+            try:
+                self.torch.cuda.synchronize(self.device)
+                _lib.tmps_streams_destroy(raw, len(raw))
+            except Exception:
+                pass
+            self._raw_streams = None
         self.act_dtype = self.stages[0].act_dtype
 
     def upload(self, batches):

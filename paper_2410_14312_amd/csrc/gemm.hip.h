@@ -263,6 +263,41 @@ template <typename TOut> struct EpiBiasAct {
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 
+// Convolution followed by a per-channel affine layer and, optionally, a residual join, in one epilogue:
+//   z = v + bias[n]                        -> out   (the convolution's result, kept for the affine layer's gradient)
+//   a = gain[n] * z + shift[n]             -> aout  (may be null when no later layer reads it... the join case stores it)
+//   y = act(a + res[m, n])                 -> yout  (res may be null)
+// Every stored tensor is rounded to its storage type before the next step reads it, exactly as if the three layers
+// had run one after the other.
+template <typename TOut> struct EpiConvAffine {
+    TOut* out;
+    const float* bias;   // may be null
+    int64_t ld;
+    const float* gain;
+    const float* shift;
+    TOut* aout;          // affine result; null when the affine layer itself applies the activation and writes yout
+    const TOut* res;     // second source of the residual join; may be null
+    TOut* yout;
+    int relu;
+    struct Col { float b, g, s; };
+    __device__ __forceinline__ Col column(int n) const { return Col{bias ? bias[n] : 0.0f, gain[n], shift[n]}; }
+    __device__ __forceinline__ void at(const Col& c, int64_t idx, float v, int) const {
+        const TOut z = from_f32<TOut>(v + c.b);
+        out[idx] = z;
+        float a = c.g * to_f32(z) + c.s;
+        if (aout) {
+            const TOut ar = from_f32<TOut>(a);
+            aout[idx] = ar;
+            a = to_f32(ar);
+        }
+        if (res) a += to_f32(res[idx]);
+        if (relu) a = a > 0.0f ? a : 0.0f;
+        yout[idx] = from_f32<TOut>(a);
+    }
+    __device__ __forceinline__ void operator()(int m, int n, float v, int z) const { at(column(n), (int64_t)m * ld + n, v, z); }
+    __device__ __forceinline__ void rowsum(int, float, int) const {}
+};
+
 // Gradient through the stored activation of the layer below: mode kActRelu: v where mask[m, n] > 0 else 0
 // (mask = that layer's output); mode kActGelu: v * gelu'(mask[m, n]) (mask = that layer's pre-activation).
 // add (may be null, may be out itself): what other readers of the same tensor have already contributed to its

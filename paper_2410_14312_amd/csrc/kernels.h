@@ -46,6 +46,12 @@ hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int 
 
 hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y,
                         const ConvShape& c, int relu, float* ws, hipStream_t s);
+// Convolution (no activation of its own) fused with the per-channel affine layer that follows it and, when res or
+// aout is given, with the residual join after that: y -> z (the convolution's result), aout (may be null) the affine
+// layer's result, yout = act(affine + res) (res may be null).
+hipError_t conv_affine_forward(int dtype, const void* x, const void* w, const float* bias, void* z, const float* gain,
+                               const float* shift, void* aout, const void* res, void* yout, int relu, const ConvShape& c,
+                               float* ws, hipStream_t s);
 hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const void* add,
                       const ConvShape& c, float* ws, hipStream_t s);
 hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const ConvShape& c,

@@ -270,6 +270,58 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict_
     dx[i] = from_f32<T>(acc);
 }
 
+// The same gather with 8 channels (16 bytes) per thread and access, bf16, C % 8 == 0: any window, stride, padding.
+__global__ __launch_bounds__(256) void maxpool_bwd_bf16x8_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
+                                                                 bf16_t* __restrict__ dx, int B, int H, int W, int C, int Ho,
+                                                                 int Wo, int k, int stride, int pad, int relu_mask) {
+    const int C8 = C >> 3;
+    const int64_t total = (int64_t)B * H * W * C8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c8 = (int)(i % C8);
+    int64_t t = i / C8;
+    const int w = (int)(t % W); t /= W;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    Pack8 me, out;
+    me.u = *reinterpret_cast<const uint4*>(x + i * 8);
+    float xv[8], acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        xv[e] = (float)me.h[e];
+        acc[e] = 0.0f;
+    }
+    const int hp = h + pad, wp = w + pad;
+    const int ho_lo = hp - k + 1 > 0 ? (hp - k + 1 + stride - 1) / stride : 0;
+    const int wo_lo = wp - k + 1 > 0 ? (wp - k + 1 + stride - 1) / stride : 0;
+    for (int ho = ho_lo; ho < Ho && ho * stride <= hp; ++ho)
+        for (int wo = wo_lo; wo < Wo && wo * stride <= wp; ++wo) {
+            bool win[8] = {true, true, true, true, true, true, true, true};
+            for (int r = 0; r < k; ++r)
+                for (int s = 0; s < k; ++s) {
+                    const int hh = ho * stride - pad + r, ww = wo * stride - pad + s;
+                    if ((unsigned)hh >= (unsigned)H || (unsigned)ww >= (unsigned)W) continue;
+                    if (hh == h && ww == w) continue;
+                    Pack8 o;
+                    o.u = *reinterpret_cast<const uint4*>(x + ((((int64_t)n * H + hh) * W + ww) * C8 + c8) * 8);
+                    const bool before = (hh < h) || (hh == h && ww < w);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float v = (float)o.h[e];
+                        if (v > xv[e] || (before && v == xv[e])) win[e] = false;
+                    }
+                }
+            Pack8 g;
+            g.u = *reinterpret_cast<const uint4*>(dy + ((((int64_t)n * Ho + ho) * Wo + wo) * C8 + c8) * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (win[e]) acc[e] += (float)g.h[e];
+        }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out.h[e] = (bf16_t)((relu_mask && !(xv[e] > 0.0f)) ? 0.0f : acc[e]);
+    *reinterpret_cast<uint4*>(dx + i * 8) = out.u;
+}
+
 // 2x2 windows with stride 2 on even H, W and C % 8 == 0 (bf16): one thread per window and 8 channels,
 // 16-byte loads of the 4 inputs and of dy, 16-byte stores of the 4 gradients.
 __global__ __launch_bounds__(256) void maxpool2x2_bwd_bf16_kernel(const bf16_t* __restrict__ x,
@@ -334,6 +386,12 @@ hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, 
         int64_t windows = (int64_t)B * Ho * Wo * (C / 8);
         hipLaunchKernelGGL(maxpool2x2_bwd_bf16_kernel, dim3(cdiv64(windows, 256)), dim3(256), 0, s, (const bf16_t*)x,
                            (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, relu_mask);
+        return hipGetLastError();
+    }
+    if (dtype == kBF16 && C % 8 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(dx) & 15) == 0) {
+        hipLaunchKernelGGL(maxpool_bwd_bf16x8_kernel, dim3(cdiv64(total / 8, 256)), dim3(256), 0, s, (const bf16_t*)x,
+                           (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, Ho, Wo, k, stride, pad, relu_mask);
         return hipGetLastError();
     }
     dim3 grid(cdiv64(total, 256));

@@ -349,6 +349,27 @@ hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bi
     return launch_f32<false>(kcConvFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, c.Cout, relu}, M, c.Cout, K, one_slice(K, 16), 1, s);
 }
 
+hipError_t conv_affine_forward(int dtype, const void* x, const void* w, const float* bias, void* z, const float* gain,
+                               const float* shift, void* aout, const void* res, void* yout, int relu, const ConvShape& c,
+                               float* ws, hipStream_t s) {
+    int M = c.B * c.Ho * c.Wo, K = c.R * c.S * c.Cin;
+    if (dtype == kBF16) {
+        EpiConvAffine<bf16_t> epi{(bf16_t*)z, bias, c.Cout, gain, shift, (bf16_t*)aout, (const bf16_t*)res, (bf16_t*)yout, relu};
+        if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w) && small_enough(c)) {
+            ConvFwdA2 A{(const bf16_t*)x, geom2(c), M, K};
+            DenseKC Bv{(const bf16_t*)w, c.Cout, K, K};
+            return run2(kcConvFwd, A, Bv, epi, M, c.Cout, K, ws, s);
+        }
+        ConvFwdA<bf16_t> A{(const bf16_t*)x, geom(c), M, K, 0};
+        DenseView<bf16_t, true> Bv{(const bf16_t*)w, c.Cout, K, K, 0};
+        return launch_bf16<false>(kcConvFwd, A, Bv, epi, M, c.Cout, K, one_slice(K, kBK), 1, s);
+    }
+    ConvFwdA<float> A{(const float*)x, geom(c), M, K, 0};
+    DenseView<float, true> Bv{(const float*)w, c.Cout, K, K, 0};
+    EpiConvAffine<float> epi{(float*)z, bias, c.Cout, gain, shift, (float*)aout, (const float*)res, (float*)yout, relu};
+    return launch_f32<false>(kcConvFwd, A, Bv, epi, M, c.Cout, K, one_slice(K, 16), 1, s);
+}
+
 hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const void* add,
                       const ConvShape& c, float* ws, hipStream_t s) {
     int M = c.B * c.H * c.W, K = c.R * c.S * c.Cout;

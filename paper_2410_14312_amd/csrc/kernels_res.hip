@@ -90,6 +90,8 @@ __global__ __launch_bounds__(256) void affine_bwd_bf16x8_kernel(const bf16_t* __
     if (col < C) {
         float g[8];
         load8(gain + col, g);
+        // several rows' loads in flight per thread: the loop is latency-bound otherwise
+#pragma unroll 4
         for (int64_t r = r0 + rl; r < r1; r += 32) {
             Pack8 d, xv, o;
             d.u = *reinterpret_cast<const uint4*>(dy + r * C + col);

@@ -222,3 +222,28 @@ extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_miniba
     }
     return TMPS_OK;
 }
+
+extern "C" int tmps_streams_create(void** out, int n) {
+    if (!out || n < 1) return fail(TMPS_EINVAL, "tmps_streams_create needs an array and a positive count");
+    for (int i = 0; i < n; ++i) out[i] = nullptr;
+    for (int i = 0; i < n; ++i) {
+        hipStream_t s = nullptr;
+        hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
+        if (e != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipStreamDestroy((hipStream_t)out[j]);
+            return fail(TMPS_EHIP, "hipStreamCreateWithFlags failed: %s", hipGetErrorString(e));
+        }
+        out[i] = s;
+    }
+    return TMPS_OK;
+}
+
+extern "C" int tmps_streams_destroy(void** streams, int n) {
+    if (!streams) return fail(TMPS_EINVAL, "streams is null");
+    for (int i = 0; i < n; ++i)
+        if (streams[i]) {
+            TMPS_HIP(hipStreamDestroy((hipStream_t)streams[i]));
+            streams[i] = nullptr;
+        }
+    return TMPS_OK;
+}

@@ -402,9 +402,31 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
                                         zout, ws, s));
                 break;
             }
-            case TMPS_CONV2D:
+            case TMPS_CONV2D: {
+                // A convolution without activation whose only reader is a per-channel affine layer runs fused with
+                // it, and with the residual join after the affine layer when that follows directly.
+                const size_t nl = st->layers.size();
+                if (L.act == 0 && li + 1 < nl && st->layers[li + 1].d.kind == TMPS_AFFINE && st->readers[li + 1] == 1) {
+                    const LayerRT& A = st->layers[li + 1];
+                    const bool join = !A.relu && li + 2 < nl && st->layers[li + 2].d.kind == TMPS_RESADD &&
+                                      st->readers[li + 2] == 1;
+                    void* aout = st->out_ptr(A, row0);
+                    if (join) {
+                        const LayerRT& J = st->layers[li + 2];
+                        const void* b = J.in_b < 0 ? x0 : (const void*)st->out_ptr(st->layers[J.in_b], row0);
+                        TMPS_GEMM(conv_affine_forward(dt, in, st->wptr(L), st->bptr(L), out, st->master + A.w_off, st->master + A.b_off,
+                                                      aout, b, st->out_ptr(J, row0), J.relu, conv_shape(L.d, mb), ws, s));
+                        li += 2;
+                    } else {
+                        TMPS_GEMM(conv_affine_forward(dt, in, st->wptr(L), st->bptr(L), out, st->master + A.w_off, st->master + A.b_off,
+                                                      nullptr, nullptr, aout, A.relu, conv_shape(L.d, mb), ws, s));
+                        li += 1;
+                    }
+                    break;
+                }
                 TMPS_GEMM(conv_forward(dt, in, st->wptr(L), st->bptr(L), out, conv_shape(L.d, mb), L.relu, ws, s));
                 break;
+            }
             case TMPS_MAXPOOL:
                 TMPS_RUN(kcPoolFwd, s, maxpool_forward(dt, in, out, mb, d[0], d[1], d[2], d[3], d[4], d[5], s));
                 break;
