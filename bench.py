@@ -127,9 +127,9 @@ def measured_traffic(workload, kernel_class):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="vgg16_bf16")
+    ap.add_argument("--workload", default="gpt2_small_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true",
                     help="issue all K workers on one stream (no overlap between kernels): a diagnostic, not the metric")

@@ -7,8 +7,8 @@
 // An operand is k-contiguous (element (row, k) at p[row*ld + k]) or row-contiguous (p[k*ld + row]).
 //
 // Work decomposition: the output is cut into BM x BN tiles and k into `slices` equal ranges; a work unit
-// is (tile, slice).  The grid has one workgroup per compute unit; workgroup b processes units
-// b, b + grid, b + 2 grid, ...  The k-loop is software-pipelined ACROSS units: the copies of the next
+// is (tile, slice).  The grid has one workgroup per compute unit; workgroup b (renumbered so that the workgroups
+// of an XCD are neighbours) processes units b, b + grid, b + 2 grid, ...  The k-loop is software-pipelined ACROSS units: the copies of the next
 // NS-1 k-tiles are always in flight, also over a unit boundary, so a unit's first tiles arrive while the
 // previous unit is still being multiplied and its results are being stored.  Short contractions (a dozen
 // k-tiles per unit) therefore pay the memory latency once per workgroup, not once per tile.
@@ -153,6 +153,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN, half = lane >> 5;
     const int grid = gridDim.x;
+    // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin in launch order.  Renumber them so that
+    // the workgroups of one XCD take CONSECUTIVE units of every round: consecutive units are tiles of one row and
+    // slice, which share their A panel (and all of them the few B panels), so an XCD fetches a panel once instead
+    // of every XCD fetching every panel.
+    int vb = blockIdx.x;
+    {
+        const int xcd = vb & 7, idx = vb >> 3, q = grid >> 3, r = grid & 7;
+        vb = xcd * q + min(xcd, r) + idx;
+    }
 
     auto unit_coords = [&](int u, int& tm, int& tn, int& z) {
         uint32_t zz, rem, m_, n_;
@@ -169,7 +178,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     // ---- copy cursor: runs NS-1 k-tiles ahead of the multiply cursor ----
     LoaderA la;
     LoaderB lb;
-    int iu = blockIdx.x, ikt = 0, ink = 0, istage = 0;
+    int iu = vb, ikt = 0, ink = 0, istage = 0;
     auto seek_unit = [&]() {
         if (iu < plan.units) {
             int tm, tn, z;
@@ -221,7 +230,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
         for (int j = 0; j < TN; ++j) bfr[0][j] = fb.read(sa + A_BYTES, j, 0);
     }
 
-    for (int cu = blockIdx.x; cu < plan.units; cu += grid) {
+    for (int cu = vb; cu < plan.units; cu += grid) {
         int tm, tn, z;
         unit_coords(cu, tm, tn, z);
         const int nk = unit_nk(z);
