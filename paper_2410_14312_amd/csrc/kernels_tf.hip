@@ -168,18 +168,109 @@ __global__ __launch_bounds__(256) void layernorm_pgrad_kernel(const T* __restric
     }
 }
 
-__global__ void slab_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int count, int slabs) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
+// Input gradient AND the per-slab partial sums of the gain / shift gradients in one pass over dy and x: bf16, 8 features
+// per lane and access, D % 8 == 0 and D <= 1024 (at most two 8-feature chunks per lane).  A wave walks over 8 rows of
+// its workgroup's slab of 4 * kLnRowsPerWave rows; the four waves' partial sums are combined through LDS.
+constexpr int kLnRowsPerWave = 4;
+__global__ __launch_bounds__(256) void layernorm_bwd_fused_bf16x8_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
+                                                                         const float* __restrict__ stats,
+                                                                         const float* __restrict__ gamma, const bf16_t* __restrict__ add,
+                                                                         bf16_t* __restrict__ dx, float* __restrict__ part,
+                                                                         int64_t rows, int D) {
+    __shared__ float sred[4][2][1024];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nch = D >> 3;
+    float g[2][8], ag[2][8], ab[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) load8(gamma + c * 8, g[i]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ag[i][e] = ab[i][e] = 0.0f;
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * (4 * kLnRowsPerWave) + wave * kLnRowsPerWave;
+#pragma unroll
+    for (int rr = 0; rr < kLnRowsPerWave; ++rr) {
+        const int64_t row = r0 + rr;
+        if (row >= rows) break;   // uniform per wave
+        const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+        float dyv[2][8], xh[2][8];
+        float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nch) {
+                float xv[8];
+                load8(dy + row * D + c * 8, dyv[i]);
+                load8(x + row * D + c * 8, xv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    xh[i][e] = (xv[e] - mean) * rstd;
+                    const float t = dyv[i][e] * g[i][e];
+                    s1 += t;
+                    s2 += t * xh[i][e];
+                    ag[i][e] += dyv[i][e] * xh[i][e];
+                    ab[i][e] += dyv[i][e];
+                }
+            }
+        }
+        const float m1 = wsum(s1) / (float)D, m2 = wsum(s2) / (float)D;
+        if (dx) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int c = lane + 64 * i;
+                if (c < nch) {
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = rstd * (dyv[i][e] * g[i][e] - m1 - xh[i][e] * m2);
+                    if (add) {
+                        float a[8];
+                        load8(add + row * D + c * 8, a);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] += a[e];
+                    }
+                    store8(dx + row * D + c * 8, v);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                sred[wave][0][c * 8 + e] = ag[i][e];
+                sred[wave][1][c * 8 + e] = ab[i][e];
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * D; i += 256) {
+        const int w = i >= D ? 1 : 0, col = i - w * D;
+        part[((int64_t)blockIdx.x * 2 + w) * D + col] = (sred[0][w][col] + sred[1][w][col]) + (sred[2][w][col] + sred[3][w][col]);
+    }
+}
+
+// out[i] = sum over the slabs of part[slab][i]: 64 outputs per workgroup, four lanes of slabs each, combined through LDS
+__global__ __launch_bounds__(256) void slab_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int count,
+                                                       int slabs) {
+    __shared__ float sp[4][64];
+    const int cl = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + cl;
     float a = 0.0f;
-    for (int z = 0; z < slabs; ++z) a += part[(int64_t)z * count + i];
-    out[i] = a;
+    if (i < count)
+        for (int z = sl; z < slabs; z += 4) a += part[(int64_t)z * count + i];
+    sp[sl][cl] = a;
+    __syncthreads();
+    if (sl == 0 && i < count) out[i] = (sp[0][cl] + sp[1][cl]) + (sp[2][cl] + sp[3][cl]);
 }
 
 static int ln_slab_rows(int64_t rows) { return rows > 4096 ? 128 : 32; }
 
 size_t layernorm_workspace_elems(int64_t rows, int D) {
-    return (size_t)cdiv_tf(rows, ln_slab_rows(rows)) * 2 * (size_t)D;
+    // the fused backward kernel works on slabs of 4 * kLnRowsPerWave rows whatever the row count
+    return (size_t)cdiv_tf(rows, 4 * kLnRowsPerWave) * 2 * (size_t)D;
 }
 
 hipError_t layernorm_forward(int dtype, const void* x, const float* gamma, const float* beta, void* y, float* stats,
@@ -203,10 +294,20 @@ hipError_t layernorm_backward(int dtype, const void* dy, const void* x, const fl
                               const void* add, void* dx, float* dgamma_dbeta, float* ws, int64_t rows, int D,
                               hipStream_t s) {
     if (rows <= 0) return hipSuccess;
+    hipError_t e;
+    if (dtype == kBF16 && D % 8 == 0 && D <= 1024 &&
+        ((reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(gamma) |
+          reinterpret_cast<uintptr_t>(add) | reinterpret_cast<uintptr_t>(dx)) & 15) == 0) {
+        const int slabs32 = cdiv_tf(rows, 4 * kLnRowsPerWave);
+        e = launch_timed(kcLayerNorm, layernorm_bwd_fused_bf16x8_kernel, dim3(slabs32), dim3(256), 0, s, (const bf16_t*)dy,
+                         (const bf16_t*)x, stats, gamma, (const bf16_t*)add, (bf16_t*)dx, ws, rows, D);
+        if (e != hipSuccess) return e;
+        return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 64)), dim3(256), 0, s, (const float*)ws,
+                            dgamma_dbeta, 2 * D, slabs32);
+    }
     const int slab = ln_slab_rows(rows);
     const int slabs = cdiv_tf(rows, slab);
     dim3 g1(cdiv_tf(rows, 4)), g2(cdiv_tf(D, 64), slabs);
-    hipError_t e;
     if (dtype == kBF16) {
         if (dx) {
             e = launch_timed(kcLayerNorm, layernorm_bwd_kernel<bf16_t>, g1, dim3(256), 0, s, (const bf16_t*)dy,
@@ -225,7 +326,7 @@ hipError_t layernorm_backward(int dtype, const void* dy, const void* x, const fl
                          stats, ws, rows, D, slab);
     }
     if (e != hipSuccess) return e;
-    return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 256)), dim3(256), 0, s, (const float*)ws,
+    return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 64)), dim3(256), 0, s, (const float*)ws,
                         dgamma_dbeta, 2 * D, slabs);
 }
 

@@ -230,8 +230,9 @@ def test_last_stage_two_linears_and_loss(dtype, borrow):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_last_stage_many_classes(dtype):
-    run_stage_case([linear(96, 1000, False), softmax_ce(1000)], dtype, 6, 2, seed=6)
+@pytest.mark.parametrize("classes", [1000, 2600, 2601])   # one wave per row; one block per row with the row in LDS; without
+def test_last_stage_many_classes(dtype, classes):
+    run_stage_case([linear(96, classes, False), softmax_ce(classes)], dtype, 6, 2, seed=6)
 
 
 CONV_CASES = [
