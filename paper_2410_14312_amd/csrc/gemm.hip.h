@@ -181,10 +181,31 @@ template <typename T> struct ConvWgradB {
 // Epilogues: called once per output element with the fp32 accumulator.  `z` is the split-K slice.
 // ------------------------------------------------------------------------------------------
 
-// Exact GELU z * Phi(z) and its derivative Phi(z) + z * phi(z).
-__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+// Exact GELU z * Phi(z) and its derivative Phi(z) + z * phi(z), Phi(z) = (1 + erf(z / sqrt 2)) / 2.
+// erf by the rational-times-Gaussian formula of Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7, at the level of fp32
+// rounding), with the hardware reciprocal and exp2: the library erff costs several dozen instructions per element,
+// which made the GELU epilogues longer than the k-loops of the GEMMs they end.  E = exp(-z^2 / 2) serves both the
+// erf and the density phi(z) = E / sqrt(2 pi).
+__device__ __forceinline__ void gelu_parts(float z, float& Phi, float& E) {
+    const float x = fabsf(z) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    E = __expf(-x * x);
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float er = 1.0f - p * t * E;             // erf(|z| / sqrt 2)
+    Phi = 0.5f * (1.0f + copysignf(er, z));
+}
+__device__ __forceinline__ float gelu_f(float z) {
+    float Phi, E;
+    gelu_parts(z, Phi, E);
+    return z * Phi;
+}
 __device__ __forceinline__ float gelu_grad_f(float z) {
-    return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
+    float Phi, E;
+    gelu_parts(z, Phi, E);
+    return Phi + z * 0.3989422804014327f * E;
 }
 
 enum { kActNone = 0, kActRelu = 1, kActGelu = 2 };

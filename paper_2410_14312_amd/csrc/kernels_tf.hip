@@ -252,18 +252,23 @@ __global__ __launch_bounds__(256) void layernorm_bwd_fused_bf16x8_kernel(const b
     }
 }
 
-// out[i] = sum over the slabs of part[slab][i]: 64 outputs per workgroup, four lanes of slabs each, combined through LDS
-__global__ __launch_bounds__(256) void slab_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int count,
-                                                       int slabs) {
-    __shared__ float sp[4][64];
+// out[i] = sum over the slabs of part[slab][i]: 64 outputs per workgroup, sixteen lanes of slabs each, combined through LDS
+__global__ __launch_bounds__(1024) void slab_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int count,
+                                                        int slabs) {
+    __shared__ float sp[16][64];
     const int cl = threadIdx.x & 63, sl = threadIdx.x >> 6;
     const int i = blockIdx.x * 64 + cl;
     float a = 0.0f;
     if (i < count)
-        for (int z = sl; z < slabs; z += 4) a += part[(int64_t)z * count + i];
+        for (int z = sl; z < slabs; z += 16) a += part[(int64_t)z * count + i];
     sp[sl][cl] = a;
     __syncthreads();
-    if (sl == 0 && i < count) out[i] = (sp[0][cl] + sp[1][cl]) + (sp[2][cl] + sp[3][cl]);
+    if (sl == 0 && i < count) {
+        float t = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += sp[k][cl];
+        out[i] = t;
+    }
 }
 
 static int ln_slab_rows(int64_t rows) { return rows > 4096 ? 128 : 32; }
@@ -302,7 +307,7 @@ hipError_t layernorm_backward(int dtype, const void* dy, const void* x, const fl
         e = launch_timed(kcLayerNorm, layernorm_bwd_fused_bf16x8_kernel, dim3(slabs32), dim3(256), 0, s, (const bf16_t*)dy,
                          (const bf16_t*)x, stats, gamma, (const bf16_t*)add, (bf16_t*)dx, ws, rows, D);
         if (e != hipSuccess) return e;
-        return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 64)), dim3(256), 0, s, (const float*)ws,
+        return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 64)), dim3(1024), 0, s, (const float*)ws,
                             dgamma_dbeta, 2 * D, slabs32);
     }
     const int slab = ln_slab_rows(rows);
@@ -326,7 +331,7 @@ hipError_t layernorm_backward(int dtype, const void* dy, const void* x, const fl
                          stats, ws, rows, D, slab);
     }
     if (e != hipSuccess) return e;
-    return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 64)), dim3(256), 0, s, (const float*)ws,
+    return launch_timed(kcLayerNorm, slab_sum_kernel, dim3(cdiv_tf(2 * D, 64)), dim3(1024), 0, s, (const float*)ws,
                         dgamma_dbeta, 2 * D, slabs);
 }
 
