@@ -11,6 +11,8 @@
 // from their row-major LDS tile with the transpose read of gfx950.
 // The generic path (any head size, fp32 or bf16) is a plain one-row-per-wave kernel for the fp32
 // configuration and odd shapes.
+#include <type_traits>
+#include <cstdlib>
 #include "gemm2.hip.h"
 #include "kernels.h"
 #include "launch.h"
@@ -535,6 +537,8 @@ __global__ __launch_bounds__(64) void attn_bwd_kv_row_kernel(const T* __restrict
 // hardware exp2 (a few ulp of fp32, far below the bf16 rounding of the results): the library expf costs some
 // 25 instructions and made the softmax, not the MFMAs, the bulk of these kernels.
 constexpr int kAP = 72;   // LDS row pitch in elements
+// 16 bytes in flight between global memory and LDS (a native vector: arrays of it stay in registers)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // B-operand / A-operand fragment of a row-major tile: lane holds row (lane % 32), 8 consecutive features
 // 16*t + 8*(lane / 32) ..; straight from global memory (rows clamped to the last valid one).
@@ -584,21 +588,21 @@ __device__ __forceinline__ void load_tile(bf16_t* tile, const bf16_t* base, int6
 // multiplied: fetch() issues the loads into registers, put() writes them to the LDS tile.
 template <int NT> struct TileFetch {
     static constexpr int N = 512 / NT;
-    uint4 r[N];
+    u32x4_t r[N];
     __device__ __forceinline__ void fetch(const bf16_t* base, int64_t ld, int row0, int max_row, int tid) {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int c = tid + i * NT;
             int row = row0 + (c >> 3);
             row = row < max_row ? row : max_row - 1;
-            r[i] = *reinterpret_cast<const uint4*>(base + row * ld + (c & 7) * 8);
+            r[i] = *reinterpret_cast<const u32x4_t*>(base + row * ld + (c & 7) * 8);
         }
     }
     __device__ __forceinline__ void put(bf16_t* tile, int tid) const {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int c = tid + i * NT;
-            *reinterpret_cast<uint4*>(tile + (c >> 3) * kAP + (c & 7) * 8) = r[i];
+            *reinterpret_cast<u32x4_t*>(tile + (c >> 3) * kAP + (c & 7) * 8) = r[i];
         }
     }
 };
@@ -634,11 +638,10 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
     for (int kv0 = 0, it = 0; kv0 < kv_end; kv0 += 64, ++it) {
         const bf16_t* sK = sKb[it & 1];
         const bf16_t* sV = sVb[it & 1];
-        const bool more = kv0 + 64 < kv_end;
-        if (more) {   // the next tile's loads fly while this one is multiplied
-            fk.fetch(base + D, ld, kv0 + 64, S, tid);
-            fv.fetch(base + 2 * D, ld, kv0 + 64, S, tid);
-        }
+        // the next tile's loads fly while this one is multiplied (past the last tile they re-read clamped, valid rows
+        // and the copy lands in the buffer that nobody reads again)
+        fk.fetch(base + D, ld, kv0 + 64, S, tid);
+        fv.fetch(base + 2 * D, ld, kv0 + 64, S, tid);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = kv0 + 32 * sub;
@@ -680,10 +683,8 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
                     ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag_t(sV, 32 * sub + 16 * t, 32 * i, lane), pf, ot[i], 0, 0, 0);
             }
         }
-        if (more) {   // the other buffer was last read before the previous barrier
-            fk.put(sKb[(it + 1) & 1], tid);
-            fv.put(sVb[(it + 1) & 1], tid);
-        }
+        fk.put(sKb[(it + 1) & 1], tid);   // the other buffer was last read before the previous barrier
+        fv.put(sVb[(it + 1) & 1], tid);
         __syncthreads();
     }
     const float l = l_run + __shfl_xor(l_run, 32, 64);
@@ -700,6 +701,145 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
                 *reinterpret_cast<uint2*>(orow + 32 * i + 8 * g + 4 * half) = pk.u;
             }
         if (half == 0) lse[((int64_t)b * H + h) * S + q] = m_run + logf(l);
+    }
+}
+
+// Forward for launches with few (batch, head) pairs, where the kernel above leaves most of the chip idle and its
+// longest workgroup walks the whole key range alone.  A workgroup owns 32 query rows; its NW waves take the 32-key
+// blocks up to the diagonal in turn (wave w: blocks w, w + NW, ...) with their own running statistics, and the
+// partial results are merged at the end: O = sum_w e^{m_w - m} O_w, l = sum_w e^{m_w - m} l_w, m = max_w m_w.
+// Nothing is shared between the waves inside the loop, so there is no workgroup barrier in it: K fragments come
+// straight from global memory, V passes through a wave-private LDS tile for the transpose read.
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+                                                                 float* __restrict__ lse, int S, int D, int H, float scale) {
+    __shared__ __attribute__((aligned(16))) bf16_t sVw[NW][32 * kAP];
+    __shared__ float sOw[NW - 1][32][64];
+    __shared__ float sMw[NW - 1][32], sLw[NW - 1][32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int64_t ld = 3 * (int64_t)D;
+    const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
+    const int q0 = qb * 32;
+    const int q = q0 + (lane & 31);
+    bf16_t* const sV = sVw[wave];
+    bf16x8_t qf[4], kn[4];
+    u32x4_t vn[4];
+    auto fetch = [&](int j) {   // rows are clamped: a fetch past the diagonal re-reads valid rows and is never used
+#pragma unroll
+        for (int t = 0; t < 4; ++t) kn[t] = gfrag(base + D, ld, 32 * j, S, t, lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = lane + 64 * i;
+            int row = 32 * j + (c >> 3);
+            row = row < S ? row : S - 1;
+            vn[i] = *reinterpret_cast<const u32x4_t*>(base + 2 * D + row * ld + (c & 7) * 8);
+        }
+    };
+    fetch(wave);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) qf[t] = gfrag(base, ld, q0, S, t, lane);
+    f32x16_t ot[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ot[i][r] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+    for (int j = wave; j <= qb; j += NW) {
+        bf16x8_t kf[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) kf[t] = kn[t];
+        // LDS serves a wave's accesses in order: the transpose reads of the previous block are done before these writes
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = lane + 64 * i;
+            *reinterpret_cast<u32x4_t*>(sV + (c >> 3) * kAP + (c & 7) * 8) = vn[i];
+        }
+        __builtin_amdgcn_wave_barrier();
+        fetch(j + NW);
+        const int kb = 32 * j;
+        f32x16_t st;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], st, 0, 0, 0);
+        float mt = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
+            st[r] = key <= q ? st[r] * scale : -INFINITY;
+            mt = fmaxf(mt, st[r]);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+        const float m_new = fmaxf(m_run, mt);
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        const float alpha = __expf(m_run - m_use);
+        float ls = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            st[r] = __expf(st[r] - m_use);
+            ls += st[r];
+        }
+        l_run = l_run * alpha + ls;
+        m_run = m_new;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const bf16x8_t pf = acc_frag(st, t);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                ot[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag_t(sV, 16 * t, 32 * i, lane), pf, ot[i], 0, 0, 0);
+        }
+    }
+    float l = l_run + __shfl_xor(l_run, 32, 64);
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sOw[wave - 1][16 * i + r][lane] = ot[i][r];
+        if (half == 0) {
+            sMw[wave - 1][lane] = m_run;
+            sLw[wave - 1][lane] = l;
+        }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    // wave 0 always owns key block 0, which every query sees: its maximum is finite
+    float m = m_run;
+#pragma unroll
+    for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, sMw[w][lane & 31]);
+    const float f0 = __expf(m_run - m);
+    l *= f0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ot[i][r] *= f0;
+#pragma unroll
+    for (int w = 0; w < NW - 1; ++w) {
+        const float fw = __expf(sMw[w][lane & 31] - m);   // a wave that had no block holds -inf: factor 0
+        l += fw * sLw[w][lane & 31];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ot[i][r] += fw * sOw[w][16 * i + r][lane];
+    }
+    if (q < S) {
+        const float inv = 1.0f / l;
+        bf16_t* orow = o + ((int64_t)b * S + q) * D + h * 64;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                union { bf16_t hv[4]; uint2 u; } pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk.hv[e] = (bf16_t)(ot[i][4 * g + e] * inv);
+                *reinterpret_cast<uint2*>(orow + 32 * i + 8 * g + 4 * half) = pk.u;
+            }
+        if (half == 0) lse[((int64_t)b * H + h) * S + q] = m + logf(l);
     }
 }
 
@@ -743,11 +883,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
     for (int kv0 = 0, it = 0; kv0 < kv_end; kv0 += 64, ++it) {
         const bf16_t* sK = sKb[it & 1];
         const bf16_t* sV = sVb[it & 1];
-        const bool more = kv0 + 64 < kv_end;
-        if (more) {
-            fk.fetch(base + D, ld, kv0 + 64, S, tid);
-            fv.fetch(base + 2 * D, ld, kv0 + 64, S, tid);
-        }
+        fk.fetch(base + D, ld, kv0 + 64, S, tid);
+        fv.fetch(base + 2 * D, ld, kv0 + 64, S, tid);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = kv0 + 32 * sub;
@@ -774,10 +911,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
                     dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag_t(sK, 32 * sub + 16 * t, 32 * i, lane), df, dq[i], 0, 0, 0);
             }
         }
-        if (more) {
-            fk.put(sKb[(it + 1) & 1], tid);
-            fv.put(sVb[(it + 1) & 1], tid);
-        }
+        fk.put(sKb[(it + 1) & 1], tid);
+        fv.put(sVb[(it + 1) & 1], tid);
         __syncthreads();
     }
     if (q < S) {
@@ -852,12 +987,9 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
         const bf16_t* sO = sOb[it & 1];
         const float* sL = sLb[it & 1];
         const float* sDl = sDlb[it & 1];
-        const bool more = qb0 + 64 < S;
-        if (more) {
-            fq.fetch(base, ld, qb0 + 64, S, tid);
-            fo.fetch(dob, D, qb0 + 64, S, tid);
-            fetch_stats(qb0 + 64);
-        }
+        fq.fetch(base, ld, qb0 + 64, S, tid);
+        fo.fetch(dob, D, qb0 + 64, S, tid);
+        fetch_stats(qb0 + 64);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int qs = qb0 + 32 * sub;
@@ -888,11 +1020,9 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
                 }
             }
         }
-        if (more) {
-            fq.put(sQb[(it + 1) & 1], tid);
-            fo.put(sOb[(it + 1) & 1], tid);
-            put_stats((it + 1) & 1);
-        }
+        fq.put(sQb[(it + 1) & 1], tid);
+        fo.put(sOb[(it + 1) & 1], tid);
+        put_stats((it + 1) & 1);
         __syncthreads();
     }
     if (key < S) {
@@ -913,6 +1043,16 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
     }
 }
 
+// Waves per workgroup of the tiled attention kernels.  Every workgroup streams the whole key (query) range of its
+// (batch, head) pair through LDS, so the traffic from L2 falls with the number of rows that share a tile: the widest
+// workgroup that still leaves about one per compute unit.
+static int attn_waves(int B, int S, int H) {
+    const int64_t bh = (int64_t)B * H;
+    if (cdiv_tf(S, 256) * bh >= 192) return 8;
+    if (cdiv_tf(S, 128) * bh >= 192) return 4;
+    return 2;
+}
+
 static bool attn_mfma_ok(int dtype, const void* a, const void* b, int D, int H) {
     return dtype == kBF16 && H > 0 && D == 64 * H &&
            ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0;
@@ -924,9 +1064,22 @@ hipError_t attention_forward(int dtype, const void* qkv, void* o, float* lse, in
     if (B <= 0) return hipSuccess;
     const float scale = 1.0f / sqrtf((float)(D / H));
     if (attn_mfma_ok(dtype, qkv, o, D, H)) {
-        constexpr int NW = 2;
-        return launch_timed(kcAttnFwd, attn_fwd_mfma_kernel<NW>, dim3(cdiv_tf(S, 32 * NW), H, B), dim3(64 * NW), 0, s,
-                            (const bf16_t*)qkv, (bf16_t*)o, lse, S, D, H, scale);
+        const bf16_t* in = (const bf16_t*)qkv;
+        bf16_t* out = (bf16_t*)o;
+        if ((int64_t)cdiv_tf(S, 64) * H * B < 512)   // too few workgroups of the tiled kernel to fill the chip
+            return launch_timed(kcAttnFwd, attn_fwd_split_kernel<4>, dim3(cdiv_tf(S, 32), H, B), dim3(256), 0, s, in, out,
+                                lse, S, D, H, scale);
+        switch (attn_waves(B, S, H)) {
+            case 8:
+                return launch_timed(kcAttnFwd, attn_fwd_mfma_kernel<8>, dim3(cdiv_tf(S, 256), H, B), dim3(512), 0, s, in, out,
+                                    lse, S, D, H, scale);
+            case 4:
+                return launch_timed(kcAttnFwd, attn_fwd_mfma_kernel<4>, dim3(cdiv_tf(S, 128), H, B), dim3(256), 0, s, in, out,
+                                    lse, S, D, H, scale);
+            default:
+                return launch_timed(kcAttnFwd, attn_fwd_mfma_kernel<2>, dim3(cdiv_tf(S, 64), H, B), dim3(128), 0, s, in, out,
+                                    lse, S, D, H, scale);
+        }
     }
     const unsigned lds = (unsigned)S * 4;
     if (dtype == kBF16)
@@ -950,13 +1103,21 @@ hipError_t attention_backward(int dtype, const void* qkv, const void* o, const v
                          (const float*)dout, delta, BS, S, D, H);
     if (e != hipSuccess) return e;
     if (attn_mfma_ok(dtype, qkv, dout, D, H) && (reinterpret_cast<uintptr_t>(dqkv) & 15) == 0) {
-        constexpr int NW = 2;
-        dim3 grid(cdiv_tf(S, 32 * NW), H, B);
-        e = launch_timed(kcAttnBwd, attn_bwd_q_mfma_kernel<NW>, grid, dim3(64 * NW), 0, s, (const bf16_t*)qkv,
-                         (const bf16_t*)dout, (const float*)lse, (const float*)delta, (bf16_t*)dqkv, S, D, H, scale);
-        if (e != hipSuccess) return e;
-        return launch_timed(kcAttnBwd, attn_bwd_kv_mfma_kernel<NW>, grid, dim3(64 * NW), 0, s, (const bf16_t*)qkv,
-                            (const bf16_t*)dout, (const float*)lse, (const float*)delta, (bf16_t*)dqkv, S, D, H, scale);
+        auto go = [&](auto nwc) {
+            constexpr int NW = decltype(nwc)::value;
+            dim3 grid(cdiv_tf(S, 32 * NW), H, B);
+            hipError_t e2 = launch_timed(kcAttnBwd, attn_bwd_q_mfma_kernel<NW>, grid, dim3(64 * NW), 0, s, (const bf16_t*)qkv,
+                                         (const bf16_t*)dout, (const float*)lse, (const float*)delta, (bf16_t*)dqkv, S, D, H,
+                                         scale);
+            if (e2 != hipSuccess) return e2;
+            return launch_timed(kcAttnBwd, attn_bwd_kv_mfma_kernel<NW>, grid, dim3(64 * NW), 0, s, (const bf16_t*)qkv,
+                                (const bf16_t*)dout, (const float*)lse, (const float*)delta, (bf16_t*)dqkv, S, D, H, scale);
+        };
+        switch (attn_waves(B, S, H)) {
+            case 8: return go(std::integral_constant<int, 8>{});
+            case 4: return go(std::integral_constant<int, 4>{});
+            default: return go(std::integral_constant<int, 2>{});
+        }
     }
     dim3 grid(S, H, B);
     if (dtype == kBF16) {

@@ -25,6 +25,8 @@ def test_layernorm_stage(dtype, d, rows, micro, N):
     (40, 128, 2, 2, 2),     # 64 features per head, one ragged key block
     (200, 64, 1, 1, 2),     # several key blocks and a ragged tail
     (128, 192, 3, 2, 2),    # whole blocks, three heads
+    (200, 256, 4, 12, 2),   # backward pass with four-wave workgroups
+    (300, 768, 12, 12, 2),  # forward pass through the tiled kernel, backward pass with eight-wave workgroups, ragged
 ])
 def test_attention_stage(dtype, s, d, heads, micro, N):
     # a linear layer in front so that the attention input gradient is used (and checked through dW as well)
