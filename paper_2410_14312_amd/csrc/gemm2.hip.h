@@ -396,13 +396,18 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
         }
     }
 
-    f32x16_t acc[TM][TN];
+    // A wave with a single 32x32 output tile alternates between two accumulators (even and odd 16-k steps), so that
+    // consecutive MFMAs do not wait for each other's result; they are added at the end.
+    constexpr int NACC = TM * TN == 1 ? 2 : 1;
+    f32x16_t acc[NACC][TM][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int a = 0; a < NACC; ++a)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][i][j][r] = 0.0f;
     float rsum = 0.0f;
 
     // Register ring: tile t is fetched into slot t % D.
@@ -434,19 +439,24 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
     auto multiply = [&](int buf) {
         const bf16_t* tA = sA + buf * A_ELEMS;
         const bf16_t* tB = sB + buf * B_ELEMS;
+        // every fragment of the k-tile is requested before the first MFMA: the LDS latency is paid once per k-tile,
+        // not once per 16-k step
+        constexpr int KK = kBK2 / 16;
+        bf16x8_t af[KK][TM], bfr[KK][TN];
 #pragma unroll
-        for (int kk = 0; kk < kBK2 / 16; ++kk) {
-            bf16x8_t af[TM], bfr[TN];
+        for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = read_frag<BM, AKC>(tA, wm * (BM / 2) + i * 32, kk, lane);
+            for (int i = 0; i < TM; ++i) af[kk][i] = read_frag<BM, AKC>(tA, wm * (BM / 2) + i * 32, kk, lane);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = read_frag<BN, BKC>(tB, wn * (BN / 2) + j * 32, kk, lane);
+            for (int j = 0; j < TN; ++j) bfr[kk][j] = read_frag<BN, BKC>(tB, wn * (BN / 2) + j * 32, kk, lane);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
+                    acc[kk % NACC][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[kk % NACC][i][j], 0, 0, 0);
         if (ROWSUM && tile_x == 0 && tid < BM) {
             if constexpr (AKC) {
                 const bf16_t* rowp = tA + tid * TileShape<BM, true>::pitch;
@@ -474,6 +484,10 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
         }
     }
 
+    if constexpr (NACC == 2) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][0][0][r] += acc[1][0][0][r];
+    }
     // Accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register r holds
     // row 8*(r/4) + 4*(lane/32) + r%4.  Output offsets advance by additions only.
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
@@ -491,7 +505,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
                 const auto col = epi.column(n);
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    epi.at(col, idx + (int64_t)(8 * (r >> 2) + (r & 3)) * ld, acc[i][j][r], z);
+                    epi.at(col, idx + (int64_t)(8 * (r >> 2) + (r & 3)) * ld, acc[0][i][j][r], z);
             }
     } else {
 #pragma unroll
@@ -506,7 +520,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = mb + 8 * (r >> 2) + (r & 3);
-                    if (m < M) epi.at(col, idx + (int64_t)(8 * (r >> 2) + (r & 3)) * ld, acc[i][j][r], z);
+                    if (m < M) epi.at(col, idx + (int64_t)(8 * (r >> 2) + (r & 3)) * ld, acc[0][i][j][r], z);
                 }
             }
     }

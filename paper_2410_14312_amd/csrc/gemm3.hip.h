@@ -309,10 +309,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
         {
             unsigned char* stg = smem + cstage * STAGE;
             // piece p (1 KB = 4 staged rows) of this wave: its p-th copy group
-            int pb[8];
-#pragma unroll
-            for (int p = 0; p < 8; ++p)
-                pb[p] = p < LoaderA::GROUPS ? (wave + p * NW) * 1024 : A_BYTES + (wave + (p - LoaderA::GROUPS) * NW) * 1024;
+            // (computed where it is used: an array of them indexed by the lane's half would live in scratch memory)
+            auto piece = [&](int p) {
+                return p < LoaderA::GROUPS ? (wave + p * NW) * 1024 : A_BYTES + (wave + (p - LoaderA::GROUPS) * NW) * 1024;
+            };
             const int64_t ld = epi.ld;
             const int col_in = lane & 31;
 #pragma unroll
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int base = half ? pb[2 * (r >> 2) + 1] : pb[2 * (r >> 2)];
+                            const int base = half ? piece(2 * (r >> 2) + 1) : piece(2 * (r >> 2));
                             *reinterpret_cast<float*>(stg + base + (r & 3) * 256 + (jj * 32 + col_in) * 4) = acc[i][2 * jp + jj][r];
                         }
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
 #pragma unroll
                     for (int sp = 0; sp < 4; ++sp) {
                         // staged row 8 sp + lane / 8 lies in piece 2 sp + half, at row (lane / 8) % 4 of the piece
-                        const int base = half ? pb[2 * sp + 1] : pb[2 * sp];
+                        const int base = half ? piece(2 * sp + 1) : piece(2 * sp);
                         const unsigned char* src = stg + base + ((lane >> 3) & 3) * 256 + (lane & 7) * 32;
                         const float4 lo = *reinterpret_cast<const float4*>(src), hi = *reinterpret_cast<const float4*>(src + 16);
                         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};

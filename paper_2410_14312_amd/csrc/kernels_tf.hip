@@ -464,6 +464,28 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ o
     if (lane == 0) delta[((bi / S) * H + h) * S + (bi % S)] = a;
 }
 
+// The same for bf16 and 64 features per head: 8 lanes share a (row, head) pair, 16 bytes per lane and operand.
+__global__ __launch_bounds__(256) void attn_delta_bf16x8_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                                float* __restrict__ delta, int64_t BS, int S, int H) {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;   // chunk of 8 features; D = 64 H, so g * 8 is its offset
+    const bool ok = g < BS * H * 8;
+    float a = 0.0f;
+    if (ok) {
+        const bf16x8_t vo = *reinterpret_cast<const bf16x8_t*>(o + g * 8), vd = *reinterpret_cast<const bf16x8_t*>(dout + g * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a += (float)vo[e] * (float)vd[e];
+    }
+    a += __shfl_xor(a, 1, 64);
+    a += __shfl_xor(a, 2, 64);
+    a += __shfl_xor(a, 4, 64);
+    if (ok && (g & 7) == 0) {
+        const int64_t idx = g >> 3;   // (b*S + i)*H + h
+        const int h = (int)(idx % H);
+        const int64_t bi = idx / H;
+        delta[((bi / S) * H + h) * S + (bi % S)] = a;
+    }
+}
+
 // Query gradient, one wave per (b, h, i).  Dynamic LDS: S floats (dS row).
 template <typename T>
 __global__ __launch_bounds__(64) void attn_bwd_q_row_kernel(const T* __restrict__ qkv, const T* __restrict__ dout,
@@ -1095,7 +1117,10 @@ hipError_t attention_backward(int dtype, const void* qkv, const void* o, const v
     const float scale = 1.0f / sqrtf((float)(D / H));
     const int64_t BS = (int64_t)B * S;
     hipError_t e;
-    if (dtype == kBF16)
+    if (attn_mfma_ok(dtype, o, dout, D, H))
+        e = launch_timed(kcAttnBwd, attn_delta_bf16x8_kernel, dim3(cdiv_tf(BS * H * 8, 256)), dim3(256), 0, s, (const bf16_t*)o,
+                         (const bf16_t*)dout, delta, BS, S, H);
+    else if (dtype == kBF16)
         e = launch_timed(kcAttnBwd, attn_delta_kernel<bf16_t>, dim3(cdiv_tf(BS * H, 4)), dim3(256), 0, s, (const bf16_t*)o,
                          (const bf16_t*)dout, delta, BS, S, D, H);
     else
