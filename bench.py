@@ -136,7 +136,12 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=0, help="mini-batches the oracle is timed on (0: about 15 s worth)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy kernel (reference for scaling HBM byte counters)")
+    ap.add_argument("--hw-queues", type=int, default=8,
+                    help="hardware queues HIP may use (GPU_MAX_HW_QUEUES, read when HIP starts): the K stage streams and "
+                         "the default stream share the runtime's default of 4, so two stages would take turns on one queue")
     args = ap.parse_args()
+    if args.hw_queues > 0:   # before anything initialises HIP
+        os.environ["GPU_MAX_HW_QUEUES"] = str(min(args.hw_queues, 32))
     if args.gpus != 1:
         print("bench.py: this build runs the stage-training path on ONE GPU (K stages on K streams of the same "
               "device); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -270,7 +275,8 @@ def main():
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "mini_batch": cfg.M, "micro_batches": cfg.N, "stages": cfg.K,
-                   "version_difference": T.version_diff_simulated(cfg.K, cfg.N)},
+                   "version_difference": T.version_diff_simulated(cfg.K, cfg.N),
+                   "streams": 1 if args.one_stream else cfg.K, "hw_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
         "mfma_frac_of_bf16_peak_end_to_end": flops_step / (dt / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
         "final_loss": float(losses[-1]),

@@ -629,6 +629,46 @@ template <int NT> struct TileFetch {
     }
 };
 
+// exp2 on the hardware unit; scores are kept in units of log 2 (scale * log2(e) folded into one factor), so that a
+// probability costs one fused multiply-add and one exp2.
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+
+// One 32-key block of the running softmax of 32 queries (one per lane pair; keys along the registers).  st holds the
+// raw scores q.k and leaves as unnormalised probabilities; m_run (in units of log 2) and l_run are the running
+// maximum and sum, ot the running output, rescaled here.  MASK: the block straddles the diagonal (or the end of
+// the sequence): keys after the query are excluded.  Blocks below the diagonal skip the three mask instructions
+// per element.
+template <bool MASK>
+__device__ __forceinline__ void softmax_block(f32x16_t& st, int kb, int q, int half, float scale2, float& m_run, float& l_run,
+                                              f32x16_t (&ot)[2]) {
+    float mt = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if constexpr (MASK) {
+            const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
+            st[r] = key <= q ? st[r] : -INFINITY;
+        }
+        mt = fmaxf(mt, st[r]);
+    }
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    const float m_new = fmaxf(m_run, mt * scale2);       // scale2 > 0: the maximum commutes with the scaling
+    const float m_use = m_new == -INFINITY ? 0.0f : m_new;   // a query with no key yet keeps zeros
+    const float alpha = exp2_hw(m_run - m_use);
+    float ls = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        st[r] = exp2_hw(fmaf(st[r], scale2, -m_use));
+        ls += st[r];
+    }
+    l_run = l_run * alpha + ls;
+    m_run = m_new;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
+}
+
 // Forward.  Block = NW waves = 32*NW query rows of one (batch, head).
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
@@ -653,6 +693,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
 #pragma unroll
         for (int r = 0; r < 16; ++r) ot[i][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
+    const float scale2 = scale * kLog2e;
     const int kv_end = min(S, (qb + 1) * NW * 32);
     fk.put(sKb[0], tid);
     fv.put(sVb[0], tid);
@@ -674,29 +715,8 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag(sK, 32 * sub, t, lane), qf[t], st, 0, 0, 0);
-            float mt = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                st[r] = key <= q ? st[r] * scale : -INFINITY;
-                mt = fmaxf(mt, st[r]);
-            }
-            mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-            const float m_new = fmaxf(m_run, mt);
-            const float m_use = m_new == -INFINITY ? 0.0f : m_new;   // a query with no key yet keeps zeros
-            const float alpha = __expf(m_run - m_use);
-            float ls = 0.0f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                st[r] = __expf(st[r] - m_use);
-                ls += st[r];
-            }
-            l_run = l_run * alpha + ls;
-            m_run = m_new;
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
+            if (kb + 31 <= q0) softmax_block<false>(st, kb, q, half, scale2, m_run, l_run, ot);
+            else softmax_block<true>(st, kb, q, half, scale2, m_run, l_run, ot);
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const bf16x8_t pf = acc_frag(st, t);
@@ -722,7 +742,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __
                 for (int e = 0; e < 4; ++e) pk.hv[e] = (bf16_t)(ot[i][4 * g + e] * inv);
                 *reinterpret_cast<uint2*>(orow + 32 * i + 8 * g + 4 * half) = pk.u;
             }
-        if (half == 0) lse[((int64_t)b * H + h) * S + q] = m_run + logf(l);
+        if (half == 0) lse[((int64_t)b * H + h) * S + q] = m_run * kLn2 + logf(l);
     }
 }
 
@@ -767,6 +787,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* _
 #pragma unroll
         for (int r = 0; r < 16; ++r) ot[i][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
+    const float scale2 = scale * kLog2e;
     for (int j = wave; j <= qb; j += NW) {
         bf16x8_t kf[4];
 #pragma unroll
@@ -786,29 +807,8 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* _
         for (int r = 0; r < 16; ++r) st[r] = 0.0f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], st, 0, 0, 0);
-        float mt = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
-            st[r] = key <= q ? st[r] * scale : -INFINITY;
-            mt = fmaxf(mt, st[r]);
-        }
-        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-        const float m_new = fmaxf(m_run, mt);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        const float alpha = __expf(m_run - m_use);
-        float ls = 0.0f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            st[r] = __expf(st[r] - m_use);
-            ls += st[r];
-        }
-        l_run = l_run * alpha + ls;
-        m_run = m_new;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) ot[i][r] *= alpha;
+        if (kb + 31 <= q0) softmax_block<false>(st, kb, q, half, scale2, m_run, l_run, ot);
+        else softmax_block<true>(st, kb, q, half, scale2, m_run, l_run, ot);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const bf16x8_t pf = acc_frag(st, t);
@@ -834,7 +834,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* _
     float m = m_run;
 #pragma unroll
     for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, sMw[w][lane & 31]);
-    const float f0 = __expf(m_run - m);
+    const float f0 = exp2_hw(m_run - m);
     l *= f0;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -842,7 +842,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* _
         for (int r = 0; r < 16; ++r) ot[i][r] *= f0;
 #pragma unroll
     for (int w = 0; w < NW - 1; ++w) {
-        const float fw = __expf(sMw[w][lane & 31] - m);   // a wave that had no block holds -inf: factor 0
+        const float fw = exp2_hw(sMw[w][lane & 31] - m);   // a wave that had no block holds -inf: factor 0
         l += fw * sLw[w][lane & 31];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -861,7 +861,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* _
                 for (int e = 0; e < 4; ++e) pk.hv[e] = (bf16_t)(ot[i][4 * g + e] * inv);
                 *reinterpret_cast<uint2*>(orow + 32 * i + 8 * g + 4 * half) = pk.u;
             }
-        if (half == 0) lse[((int64_t)b * H + h) * S + q] = m + logf(l);
+        if (half == 0) lse[((int64_t)b * H + h) * S + q] = m * kLn2 + logf(l);
     }
 }
 
@@ -892,7 +892,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
         qf[t] = gfrag(base, ld, q0, S, t, lane);
         dof[t] = gfrag(dob, D, q0, S, t, lane);
     }
-    const float L = lse[((int64_t)b * H + h) * S + qc], dl = delta[((int64_t)b * H + h) * S + qc];
+    const float L2 = lse[((int64_t)b * H + h) * S + qc] * kLog2e, dl = delta[((int64_t)b * H + h) * S + qc];
+    const float scale2 = scale * kLog2e;
     f32x16_t dq[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -919,11 +920,16 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag(sK, 32 * sub, t, lane), qf[t], st, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag(sV, 32 * sub, t, lane), dof[t], dp, 0, 0, 0);
             }
+            if (kb + 31 <= q0) {   // below the diagonal: no key is excluded
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                const float p = key <= q ? __expf(st[r] * scale - L) : 0.0f;
-                st[r] = p * (dp[r] - dl);
+                for (int r = 0; r < 16; ++r) st[r] = exp2_hw(fmaf(st[r], scale2, -L2)) * (dp[r] - dl);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const float p = key <= q ? exp2_hw(fmaf(st[r], scale2, -L2)) : 0.0f;
+                    st[r] = p * (dp[r] - dl);
+                }
             }
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -962,7 +968,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
                                                                    float scale) {
     __shared__ __attribute__((aligned(16))) bf16_t sQb[2][64 * kAP];
     __shared__ __attribute__((aligned(16))) bf16_t sOb[2][64 * kAP];
-    __shared__ float sLb[2][64], sDlb[2][64];
+    __shared__ __attribute__((aligned(16))) float sLb[2][64], sDlb[2][64];   // log-sum-exp (in units of log 2) and delta
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int kblk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t ld = 3 * (int64_t)D;
@@ -970,6 +976,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
     const bf16_t* dob = dout + (int64_t)b * S * D + h * 64;
     const int k0 = (kblk * NW + wave) * 32;
     const int key = k0 + (lane & 31);
+    const float scale2 = scale * kLog2e;
     bf16x8_t kf[4], vf[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -993,7 +1000,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
     };
     auto put_stats = [&](int buf) {
         if (tid < 64) {
-            sLb[buf][tid] = pl;
+            sLb[buf][tid] = pl * kLog2e;
             sDlb[buf][tid] = pd;
         }
     };
@@ -1024,13 +1031,25 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag(sQ, 32 * sub, t, lane), kf[t], st, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lfrag(sO, 32 * sub, t, lane), vf[t], dp, 0, 0, 0);
             }
+            // statistics of the 4 consecutive queries of a register group in one LDS read each
+            float4 l4[4], d4[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                l4[g] = *reinterpret_cast<const float4*>(sL + 32 * sub + 8 * g + 4 * half);
+                d4[g] = *reinterpret_cast<const float4*>(sDl + 32 * sub + 8 * g + 4 * half);
+            }
+            const bool inner = k0 + 31 <= qs && qs + 32 <= S;   // every query of the block sees every key of this wave
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int ql = 32 * sub + 8 * (r >> 2) + 4 * half + (r & 3);
-                const int qq = qb0 + ql;
-                const float p = (key <= qq && qq < S) ? __expf(st[r] * scale - sL[ql]) : 0.0f;
+                const float Lq = (r & 3) == 0 ? l4[r >> 2].x : (r & 3) == 1 ? l4[r >> 2].y : (r & 3) == 2 ? l4[r >> 2].z : l4[r >> 2].w;
+                const float Dq = (r & 3) == 0 ? d4[r >> 2].x : (r & 3) == 1 ? d4[r >> 2].y : (r & 3) == 2 ? d4[r >> 2].z : d4[r >> 2].w;
+                float p = exp2_hw(fmaf(st[r], scale2, -Lq));
+                if (!inner) {
+                    const int qq = qs + 8 * (r >> 2) + 4 * half + (r & 3);
+                    p = (key <= qq && qq < S) ? p : 0.0f;
+                }
                 st[r] = p;
-                dp[r] = p * (dp[r] - sDl[ql]);
+                dp[r] = p * (dp[r] - Dq);
             }
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
