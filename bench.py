@@ -185,44 +185,58 @@ def main():
     assert np.all(np.isfinite(losses)), "non-finite loss in the timed run"
     value = cfg.M * args.steps / dt
 
-    # second pass of the same workload with per-kernel event timing on the kernels' streams
-    T.profile_enable(True)
-    pipe.run_device(xs, ys, args.steps, ls, want_log=False)
-    torch.cuda.synchronize()
-    prof = T.profile_read()
-    T.profile_enable(False)
     work = algorithmic_work(cfg)
-    kernels = []
-    # what an empty pair of timing events measures on these streams; subtracted from every bracket
-    pair_ms, pair_cnt = prof.pop("event_pair", (0.0, 0))
-    pair_us = 1e3 * pair_ms / pair_cnt if pair_cnt else 0.0
-    for k, (ms, cnt) in prof.items():
-        if cnt == 0:
-            continue
-        per = work.get(k)
-        if k not in KERNEL_STAMPED:      # bracketed classes also contain the cost of the event pair
-            ms = max(ms - cnt * pair_us / 1e3, 0.05 * ms)
-        ent = {"class": k, "launches_per_step": cnt / args.steps, "avg_us": 1e3 * ms / cnt, "ms_per_step": ms / args.steps}
-        if per and per[0]:
-            ent["gflop_per_launch"] = per[1] / per[0] / 1e9
-            ent["mbytes_per_launch"] = per[2] / per[0] / 1e6
-            sec = ms / cnt / 1e3
-            ent["tflops"] = per[1] / per[0] / sec / 1e12
-            ent["gbs"] = per[2] / per[0] / sec / 1e9
-        kernels.append(ent)
-    kernels.sort(key=lambda e: -e["ms_per_step"])
-    dom = kernels[0]
-    if dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce", "layernorm", "embedding", "affine", "resadd"):
-        roof = {"kernel": dom["class"], "bound": "hbm", "achieved": dom.get("gbs", 0.0), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": dom.get("gbs", 0.0) / HBM_PEAK_GBS, "traffic": None}
-    else:
-        roof = {"kernel": dom["class"], "bound": "mfma", "achieved": dom.get("tflops", 0.0),
-                "peak": MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3, "unit": "TFLOP/s",
-                "frac": dom.get("tflops", 0.0) / (MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3),
-                "traffic": None}
-    roof["avg_launch_us"] = dom["avg_us"]
-    roof["event_pair_us_subtracted"] = pair_us
-    roof["traffic"] = measured_traffic(cfg.name, dom["class"])
+
+    def timed_pass(one_stream):
+        """The same workload once more with per-kernel timing on the kernels' streams; per-class summary."""
+        T.profile_enable(True)
+        pipe.run_device(xs, ys, args.steps, ls, want_log=False, one_stream=one_stream)
+        torch.cuda.synchronize()
+        prof = T.profile_read()
+        T.profile_enable(False)
+        out = []
+        # what an empty pair of timing events measures on these streams; subtracted from every bracket
+        pair_ms, pair_cnt = prof.pop("event_pair", (0.0, 0))
+        pair_us = 1e3 * pair_ms / pair_cnt if pair_cnt else 0.0
+        for k, (ms, cnt) in prof.items():
+            if cnt == 0:
+                continue
+            per = work.get(k)
+            if k not in KERNEL_STAMPED:      # bracketed classes also contain the cost of the event pair
+                ms = max(ms - cnt * pair_us / 1e3, 0.05 * ms)
+            ent = {"class": k, "launches_per_step": cnt / args.steps, "avg_us": 1e3 * ms / cnt, "ms_per_step": ms / args.steps}
+            if per and per[0]:
+                ent["gflop_per_launch"] = per[1] / per[0] / 1e9
+                ent["mbytes_per_launch"] = per[2] / per[0] / 1e6
+                sec = ms / cnt / 1e3
+                ent["tflops"] = per[1] / per[0] / sec / 1e12
+                ent["gbs"] = per[2] / per[0] / sec / 1e9
+            out.append(ent)
+        out.sort(key=lambda e: -e["ms_per_step"])
+        return out, pair_us
+
+    # Pass 2: the benchmark's own configuration (K streams): while kernels of several stages share the device, each
+    # takes longer than it would alone, so these durations describe the mix, not the kernels.
+    kernels, pair_us = timed_pass(args.one_stream)
+    # Pass 3: every worker on one stream, so each kernel has the device to itself: the per-kernel rates that the
+    # roofline is about.
+    kernels_alone, pair_us_alone = (kernels, pair_us) if args.one_stream else timed_pass(True)
+    dom = kernels_alone[0]
+    hbm_bound = dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce", "layernorm",
+                                 "embedding", "affine", "resadd")
+    peak = HBM_PEAK_GBS if hbm_bound else (MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3)
+    rate = "gbs" if hbm_bound else "tflops"
+    roof = {"kernel": dom["class"], "bound": "hbm" if hbm_bound else "mfma", "achieved": dom.get(rate, 0.0), "peak": peak,
+            "unit": "GB/s" if hbm_bound else "TFLOP/s", "frac": dom.get(rate, 0.0) / peak,
+            "traffic": measured_traffic(cfg.name, dom["class"]), "avg_launch_us": dom["avg_us"],
+            "launches_per_step": dom["launches_per_step"],
+            "timing": "per-launch durations of a pass of the same mini-batches with all workers on one stream (no other "
+                      "kernel on the device); rocprofv3 summary of that command: profiles/%s_one_stream_kernel_trace.txt" % cfg.name,
+            "event_pair_us_subtracted": pair_us_alone}
+    shared = next((e for e in kernels if e["class"] == dom["class"]), None)
+    if shared is not None and not args.one_stream:
+        roof["with_%d_streams" % cfg.K] = {"avg_launch_us": shared["avg_us"], "achieved": shared.get(rate, 0.0),
+                                          "frac": shared.get(rate, 0.0) / peak}
 
     flops_step = sum(v[1] for v in work.values())
     cpu = None
@@ -278,7 +292,7 @@ def main():
                    "version_difference": T.version_diff_simulated(cfg.K, cfg.N),
                    "streams": 1 if args.one_stream else cfg.K, "hw_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
         "mfma_frac_of_bf16_peak_end_to_end": flops_step / (dt / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "kernels_one_stream": kernels_alone,
         "final_loss": float(losses[-1]),
     }
     print(json.dumps(out))

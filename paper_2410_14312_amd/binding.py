@@ -341,6 +341,7 @@ class Pipeline:
             _check(lib().tmps_streams_create(self._raw_streams, n))
         ext = [torch.cuda.ExternalStream(int(self._raw_streams[i]), device=self.device) for i in range(n)]
         self.streams = [ext[0] if one_stream else ext[s] for s in range(K)]
+        self.act_dtype = self.stages[0].act_dtype
 
     def __del__(self):
         raw = getattr(self, "_raw_streams", None)
@@ -351,7 +352,6 @@ class Pipeline:
             except Exception:
                 pass
             self._raw_streams = None
-        self.act_dtype = self.stages[0].act_dtype
 
     def upload(self, batches):
         """Concatenate mini-batches and place them in HBM (inputs in the activation dtype, labels int32)."""
@@ -360,11 +360,12 @@ class Pipeline:
         y = torch.from_numpy(np.concatenate([b[1] for b in batches], axis=0).astype(np.int32))
         return x.contiguous(), y.to(self.device).contiguous()
 
-    def run_device(self, x_dev, y_dev, n_minibatches, losses_dev, want_log=True):
-        """Launch on resident inputs.  Returns the version log (n_tasks x 7 int32) or None."""
+    def run_device(self, x_dev, y_dev, n_minibatches, losses_dev, want_log=True, one_stream=False):
+        """Launch on resident inputs.  Returns the version log (n_tasks x 7 int32) or None.
+        one_stream: this run issues every worker on the first stream (kernels never share the device)."""
         K, N = self.cfg.K, self.cfg.N
         handles = (C.c_void_p * K)(*[st.handle for st in self.stages])
-        streams = (C.c_void_p * K)(*[s.cuda_stream for s in self.streams])
+        streams = (C.c_void_p * K)(*[(self.streams[0] if one_stream else s).cuda_stream for s in self.streams])
         log = None
         logp = None
         if want_log:

@@ -315,6 +315,39 @@ template <typename TOut> struct EpiConvAffine {
         if (relu) a = a > 0.0f ? a : 0.0f;
         yout[idx] = from_f32<TOut>(a);
     }
+    // 8 consecutive columns n..n+7 of one row (n and idx multiples of 8; every tensor and vector 16-byte aligned)
+    __device__ __forceinline__ void at8(int n, int64_t idx, float (&v)[8], int) const {
+        float g[8], sh[8];
+        load8(gain + n, g);
+        load8(shift + n, sh);
+        if (bias) {
+            float b[8];
+            load8(bias + n, b);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += b[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = to_f32(from_f32<TOut>(v[e]));
+        store8(out + idx, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = g[e] * v[e] + sh[e];
+        if (aout) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = to_f32(from_f32<TOut>(v[e]));
+            store8(aout + idx, v);
+        }
+        if (res) {
+            float r[8];
+            load8(res + idx, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += r[e];
+        }
+        if (relu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+        }
+        store8(yout + idx, v);
+    }
     __device__ __forceinline__ void operator()(int m, int n, float v, int z) const { at(column(n), (int64_t)m * ld + n, v, z); }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };

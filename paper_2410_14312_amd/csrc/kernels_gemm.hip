@@ -224,35 +224,42 @@ static hipError_t wgrad_fallback(int kc, const AOp& A, const BOp& B, float* gw, 
 }
 
 // ---------------------------------------------------------------------------------------- dense
-hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B, int Din,
-                         int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
+// The dense contractions with the kernel class they are accounted under as a parameter: a 1x1 convolution with unit
+// stride and no padding is the same contraction over its positions.
+static hipError_t dense_forward_as(int kc, int dtype, const void* x, const void* w, const float* bias, void* y, int B, int Din,
+                                   int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
     if (dtype == kBF16) {
         const bool fast = (Din % 8 == 0) && aligned16(x) && aligned16(w);
         if (fast && g3_forward_ok(B, Dout, Din) && aligned16(y) && aligned16(bias) && aligned16(res) && aligned16(zout)) {
             G3Operand<true> A{(const bf16_t*)x, B, Din};
             G3Operand<true> Bv{(const bf16_t*)w, Dout, Din};
             const G3Plan plan = g3_plan(B, Dout, Din, 1);
-            if (out_f32) return launch3<true, true, false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, plan, s);
-            return launch3<true, true, false>(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, plan, s);
+            if (out_f32) return launch3<true, true, false>(kc, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, plan, s);
+            return launch3<true, true, false>(kc, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, plan, s);
         }
         if (fast) {
             DenseKC A{(const bf16_t*)x, B, Din, Din};
             DenseKC Bv{(const bf16_t*)w, Dout, Din, Din};
-            if (out_f32) return run2(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
-            return run2(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, ws, s);
+            if (out_f32) return run2(kc, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, ws, s);
+            return run2(kc, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, ws, s);
         }
         DenseView<bf16_t, true> A{(const bf16_t*)x, B, Din, Din, 0};
         DenseView<bf16_t, true> Bv{(const bf16_t*)w, Dout, Din, Din, 0};
-        if (out_f32) return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
-        return launch_bf16<false>(kcDenseFwd, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, one_slice(Din, kBK), 1, s);
+        if (out_f32) return launch_bf16<false>(kc, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu}, B, Dout, Din, one_slice(Din, kBK), 1, s);
+        return launch_bf16<false>(kc, A, Bv, EpiBiasAct<bf16_t>{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout}, B, Dout, Din, one_slice(Din, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)x, B, Din, Din, 0};
     DenseView<float, true> Bv{(const float*)w, Dout, Din, Din, 0};
-    return launch_f32<false>(kcDenseFwd, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu, (const float*)res, (float*)zout}, B, Dout, Din, one_slice(Din, 16), 1, s);
+    return launch_f32<false>(kc, A, Bv, EpiBiasAct<float>{(float*)y, bias, Dout, relu, (const float*)res, (float*)zout}, B, Dout, Din, one_slice(Din, 16), 1, s);
 }
 
-hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode,
-                       const void* add, int B, int Din, int Dout, float* ws, hipStream_t s) {
+hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B, int Din,
+                         int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
+    return dense_forward_as(tmps::kcDenseFwd, dtype, x, w, bias, y, B, Din, Dout, relu, out_f32, res, zout, ws, s);
+}
+
+static hipError_t dense_dgrad_as(int kc, int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode,
+                                 const void* add, int B, int Din, int Dout, float* ws, hipStream_t s) {
     // dx[m, n] = sum_k dy[m, k] * w[k, n]:  A = dy (k-contiguous), B(n, k) = w[k*Din + n] (row-contiguous)
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode, (const bf16_t*)add};
@@ -260,24 +267,29 @@ hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const
         if (fast && g3_forward_ok(B, Din, Dout) && aligned16(dx) && aligned16(mask) && aligned16(add)) {
             G3Operand<true> A{(const bf16_t*)dy, B, Dout};
             G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
-            return launch3<true, false, false>(kcDenseDgrad, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1), s);
+            return launch3<true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1), s);
         }
         if (fast) {
             DenseKC A{(const bf16_t*)dy, B, Dout, Dout};
             DenseRC Bv{(const bf16_t*)w, Din, Dout, Din};
-            return run2(kcDenseDgrad, A, Bv, epi, B, Din, Dout, ws, s);
+            return run2(kc, A, Bv, epi, B, Din, Dout, ws, s);
         }
         DenseView<bf16_t, true> A{(const bf16_t*)dy, B, Dout, Dout, 0};
         DenseView<bf16_t, false> Bv{(const bf16_t*)w, Din, Dout, Din, 0};
-        return launch_bf16<false>(kcDenseDgrad, A, Bv, epi, B, Din, Dout, one_slice(Dout, kBK), 1, s);
+        return launch_bf16<false>(kc, A, Bv, epi, B, Din, Dout, one_slice(Dout, kBK), 1, s);
     }
     DenseView<float, true> A{(const float*)dy, B, Dout, Dout, 0};
     DenseView<float, false> Bv{(const float*)w, Din, Dout, Din, 0};
-    return launch_f32<false>(kcDenseDgrad, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din, mask_mode, (const float*)add}, B, Din, Dout, one_slice(Dout, 16), 1, s);
+    return launch_f32<false>(kc, A, Bv, EpiMask<float, float>{(float*)dx, (const float*)mask, Din, mask_mode, (const float*)add}, B, Din, Dout, one_slice(Dout, 16), 1, s);
 }
 
-hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout, float* ws,
-                       hipStream_t s) {
+hipError_t dense_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, int mask_mode,
+                       const void* add, int B, int Din, int Dout, float* ws, hipStream_t s) {
+    return dense_dgrad_as(tmps::kcDenseDgrad, dtype, dy, w, dx, mask, mask_mode, add, B, Din, Dout, ws, s);
+}
+
+static hipError_t dense_wgrad_as(int kc, int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout,
+                                 float* ws, hipStream_t s) {
     // gw[m, n] = sum_k dy[k, m] * x[k, n]: both operands row-contiguous, contraction over the batch
     if (dtype == kBF16) {
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(x);
@@ -288,7 +300,7 @@ hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int 
             const G3Plan plan = g3_plan(Dout, Din, B, s3);
             const int64_t count = (int64_t)Dout * Din + Dout;
             EpiWgrad epi{plan.slices > 1 ? ws : gw, Din, (int64_t)Dout * Din, count};
-            hipError_t e = launch3<false, false, true>(kcDenseWgrad, A, Bv, epi, Dout, Din, B, plan, s);
+            hipError_t e = launch3<false, false, true>(kc, A, Bv, epi, Dout, Din, B, plan, s);
             if (e != hipSuccess || plan.slices <= 1) return e;
             return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw, count,
                                 plan.slices);
@@ -296,15 +308,20 @@ hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int 
         if (fast) {
             DenseRC A{(const bf16_t*)dy, Dout, B, Dout};
             DenseRC Bv{(const bf16_t*)x, Din, B, Din};
-            return run2_wgrad(kcDenseWgrad, A, Bv, gw, Dout, Din, B, ws, s);
+            return run2_wgrad(kc, A, Bv, gw, Dout, Din, B, ws, s);
         }
         DenseView<bf16_t, false> A{(const bf16_t*)dy, Dout, B, Dout, 0};
         DenseView<bf16_t, false> Bv{(const bf16_t*)x, Din, B, Din, 0};
-        return wgrad_fallback<bf16_t>(kcDenseWgrad, A, Bv, gw, Dout, Din, B, ws, s);
+        return wgrad_fallback<bf16_t>(kc, A, Bv, gw, Dout, Din, B, ws, s);
     }
     DenseView<float, false> A{(const float*)dy, Dout, B, Dout, 0};
     DenseView<float, false> Bv{(const float*)x, Din, B, Din, 0};
-    return wgrad_fallback<float>(kcDenseWgrad, A, Bv, gw, Dout, Din, B, ws, s);
+    return wgrad_fallback<float>(kc, A, Bv, gw, Dout, Din, B, ws, s);
+}
+
+hipError_t dense_wgrad(int dtype, const void* dy, const void* x, float* gw, int B, int Din, int Dout, float* ws,
+                       hipStream_t s) {
+    return dense_wgrad_as(tmps::kcDenseWgrad, dtype, dy, x, gw, B, Din, Dout, ws, s);
 }
 
 // ---------------------------------------------------------------------------------- convolution
@@ -332,9 +349,19 @@ static ConvGeom2 geom2(const ConvShape& c) {
     return g;
 }
 
+// A 1x1 convolution with unit stride and no padding on NHWC tensors IS a dense layer over the B*H*W positions
+// (weights [Cout][Cin]); bf16 ones take the dense paths, which have plain loaders and the persistent kernel.
+static bool pointwise(int dtype, const ConvShape& c) {
+    return dtype == kBF16 && c.R == 1 && c.S == 1 && c.stride == 1 && c.pad == 0 &&
+           (int64_t)c.B * c.H * c.W < (int64_t(1) << 31);
+}
+
 hipError_t conv_forward(int dtype, const void* x, const void* w, const float* bias, void* y, const ConvShape& c,
                         int relu, float* ws, hipStream_t s) {
     int M = c.B * c.Ho * c.Wo, K = c.R * c.S * c.Cin;
+    if (pointwise(dtype, c))
+        return dense_forward_as(kcConvFwd, dtype, x, w, bias, y, M, c.Cin, c.Cout, relu ? kActRelu : kActNone, 0, nullptr, nullptr,
+                                ws, s);
     if (dtype == kBF16) {
         EpiBiasAct<bf16_t> epi{(bf16_t*)y, bias, c.Cout, relu};
         if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w) && small_enough(c)) {
@@ -357,6 +384,17 @@ hipError_t conv_affine_forward(int dtype, const void* x, const void* w, const fl
     int M = c.B * c.Ho * c.Wo, K = c.R * c.S * c.Cin;
     if (dtype == kBF16) {
         EpiConvAffine<bf16_t> epi{(bf16_t*)z, bias, c.Cout, gain, shift, (bf16_t*)aout, (const bf16_t*)res, (bf16_t*)yout, relu};
+        if (pointwise(dtype, c) && c.Cin % 8 == 0 && aligned16(x) && aligned16(w)) {
+            if (g3_forward_ok(M, c.Cout, K) && aligned16(z) && aligned16(bias) && aligned16(gain) && aligned16(shift) &&
+                aligned16(aout) && aligned16(res) && aligned16(yout)) {
+                G3Operand<true> A{(const bf16_t*)x, M, K};
+                G3Operand<true> Bv{(const bf16_t*)w, c.Cout, K};
+                return launch3<true, true, false>(kcConvFwd, A, Bv, epi, M, c.Cout, K, g3_plan(M, c.Cout, K, 1), s);
+            }
+            DenseKC A{(const bf16_t*)x, M, K, K};
+            DenseKC Bv{(const bf16_t*)w, c.Cout, K, K};
+            return run2(kcConvFwd, A, Bv, epi, M, c.Cout, K, ws, s);
+        }
         if (c.Cin % 8 == 0 && aligned16(x) && aligned16(w) && small_enough(c)) {
             ConvFwdA2 A{(const bf16_t*)x, geom2(c), M, K};
             DenseKC Bv{(const bf16_t*)w, c.Cout, K, K};
@@ -375,6 +413,7 @@ hipError_t conv_affine_forward(int dtype, const void* x, const void* w, const fl
 hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const void* mask, const void* add,
                       const ConvShape& c, float* ws, hipStream_t s) {
     int M = c.B * c.H * c.W, K = c.R * c.S * c.Cout;
+    if (pointwise(dtype, c)) return dense_dgrad_as(kcConvDgrad, dtype, dy, w, dx, mask, kActRelu, add, M, c.Cin, c.Cout, ws, s);
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, c.Cin, kActRelu, (const bf16_t*)add};
         if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w) && small_enough(c)) {
@@ -395,6 +434,7 @@ hipError_t conv_wgrad(int dtype, const void* dy, const void* x, float* gw, const
                       hipStream_t s) {
     int rows = c.Cout, cols = c.R * c.S * c.Cin;
     int64_t K = (int64_t)c.B * c.Ho * c.Wo;
+    if (pointwise(dtype, c)) return dense_wgrad_as(kcConvWgrad, dtype, dy, x, gw, (int)K, c.Cin, c.Cout, ws, s);
     if (dtype == kBF16) {
         if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(x) && small_enough(c)) {
             DenseRC A{(const bf16_t*)dy, rows, (int)K, c.Cout};

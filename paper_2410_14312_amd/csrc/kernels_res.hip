@@ -124,18 +124,23 @@ __global__ __launch_bounds__(256) void affine_bwd_bf16x8_kernel(const bf16_t* __
     }
 }
 
-// out[i] = sum over the slabs of part[slab][i]: 64 outputs per workgroup, four lanes of slabs each, combined through LDS
-__global__ __launch_bounds__(256) void affine_slab_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int count,
-                                                              int slabs) {
-    __shared__ float sp[4][64];
+// out[i] = sum over the slabs of part[slab][i]: 64 outputs per workgroup, sixteen lanes of slabs each, combined through LDS
+__global__ __launch_bounds__(1024) void affine_slab_sum_kernel(const float* __restrict__ part, float* __restrict__ out, int count,
+                                                               int slabs) {
+    __shared__ float sp[16][64];
     const int cl = threadIdx.x & 63, sl = threadIdx.x >> 6;
     const int i = blockIdx.x * 64 + cl;
     float a = 0.0f;
     if (i < count)
-        for (int z = sl; z < slabs; z += 4) a += part[(int64_t)z * count + i];
+        for (int z = sl; z < slabs; z += 16) a += part[(int64_t)z * count + i];
     sp[sl][cl] = a;
     __syncthreads();
-    if (sl == 0 && i < count) out[i] = (sp[0][cl] + sp[1][cl]) + (sp[2][cl] + sp[3][cl]);
+    if (sl == 0 && i < count) {
+        float t = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += sp[k][cl];
+        out[i] = t;
+    }
 }
 
 static int affine_slab_rows(int64_t rows) {
@@ -185,7 +190,7 @@ hipError_t affine_backward(int dtype, const void* dy, const void* x, const float
         e = launch_timed(kcAffine, affine_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)dy, (const float*)x, gain,
                          (float*)dx, ws, rows, C, slab);
     if (e != hipSuccess) return e;
-    return launch_timed(kcAffine, affine_slab_sum_kernel, dim3(cdiv_res(2 * C, 64)), dim3(256), 0, s, (const float*)ws,
+    return launch_timed(kcAffine, affine_slab_sum_kernel, dim3(cdiv_res(2 * C, 64)), dim3(1024), 0, s, (const float*)ws,
                         dgain_dshift, 2 * C, slabs);
 }
 
