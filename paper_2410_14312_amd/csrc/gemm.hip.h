@@ -232,6 +232,10 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
+// Host-side test for the 8-wide (16-byte) form of an epilogue: every tensor it touches is 16-byte aligned and a row
+// start keeps that alignment.
+static inline bool epi_al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 // out[m, n] = act(v + bias[n]) + res[m, n].  With GELU the pre-activation is also stored (zout), for the
 // derivative in the backward pass.  res: a residual connection's source, same shape as out.
 template <typename TOut> struct EpiBiasAct {
@@ -254,6 +258,7 @@ template <typename TOut> struct EpiBiasAct {
         if (bias) v += bias[n];
         finish((int64_t)m * ld + n, v);
     }
+    bool wide_ok() const { return ld % 8 == 0 && epi_al16(out) && epi_al16(bias) && epi_al16(res) && epi_al16(zout); }
     // the same in two steps: column(n) fetches the bias once, at() finishes element idx = m*ld + n
     __device__ __forceinline__ float column(int n) const { return bias ? bias[n] : 0.0f; }
     __device__ __forceinline__ void at(float b, int64_t idx, float v, int) const { finish(idx, v + b); }
@@ -301,6 +306,10 @@ template <typename TOut> struct EpiConvAffine {
     TOut* yout;
     int relu;
     struct Col { float b, g, s; };
+    bool wide_ok() const {
+        return ld % 8 == 0 && epi_al16(out) && epi_al16(bias) && epi_al16(gain) && epi_al16(shift) && epi_al16(aout) &&
+               epi_al16(res) && epi_al16(yout);
+    }
     __device__ __forceinline__ Col column(int n) const { return Col{bias ? bias[n] : 0.0f, gain[n], shift[n]}; }
     __device__ __forceinline__ void at(const Col& c, int64_t idx, float v, int) const {
         const TOut z = from_f32<TOut>(v + c.b);
@@ -372,6 +381,7 @@ template <typename TOut, typename TMask> struct EpiMask {
         out[i] = from_f32<TOut>(v);
     }
     __device__ __forceinline__ void operator()(int m, int n, float v, int) const { finish((int64_t)m * ld + n, v); }
+    bool wide_ok() const { return ld % 8 == 0 && epi_al16(out) && epi_al16(mask) && epi_al16(add); }
     __device__ __forceinline__ int column(int) const { return 0; }
     __device__ __forceinline__ void at(int, int64_t i, float v, int) const { finish(i, v); }
     __device__ __forceinline__ void at8(int, int64_t i, float (&v)[8], int) const {
@@ -405,6 +415,7 @@ struct EpiWgrad {
     __device__ __forceinline__ void operator()(int m, int n, float v, int z) const {
         out[z * slice_stride + (int64_t)m * ld + n] = v;
     }
+    bool wide_ok() const { return ld % 8 == 0 && slice_stride % 4 == 0 && epi_al16(out); }
     __device__ __forceinline__ int column(int) const { return 0; }
     __device__ __forceinline__ void at(int, int64_t idx, float v, int z) const {
         out[z * slice_stride + idx] = v;

@@ -331,7 +331,8 @@ template <int BM, int BN, class AOp, class BOp> constexpr int gemm2_lds_bytes() 
 
 // D = number of k-tiles whose global loads are in flight per thread (register ring).
 template <int BM, int BN, int D, bool ROWSUM, class AOp, class BOp, class Epi>
-__global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M, int N, int K, int k_per_slice) {
+__global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M, int N, int K, int k_per_slice,
+                                                    int col_major, int wide) {
     constexpr bool AKC = AOp::kContig, BKC = BOp::kContig;
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int A_CH = BM * (kBK2 / 8) / 256, B_CH = BN * (kBK2 / 8) / 256;
@@ -343,18 +344,24 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin in launch order.  Renumber the tiles
-    // of a k-slice so that the workgroups of one XCD own a contiguous run of tiles in row-major order: the tiles of
-    // a row share their A panel and then find it in their own L2, instead of every XCD fetching every panel.
+    // of a k-slice so that the workgroups of one XCD own a contiguous run of tiles: in row-major order the tiles of
+    // a row share their A panel and find it in their own L2, but every XCD fetches all of B; in column-major order
+    // (col_major, chosen by the host when B is the larger operand) it is the other way round.
     int tile_x = blockIdx.x, tile_y = blockIdx.y;
     {
-        const int gx = gridDim.x, nb = gridDim.x * gridDim.y;
+        const int gx = gridDim.x, gy = gridDim.y, nb = gx * gy;
         if (nb >= 16) {
             const int lin = tile_y * gx + tile_x;
             const int xcd = lin & 7, idx = lin >> 3;
             const int q = nb >> 3, r = nb & 7;
             const int moved = xcd * q + min(xcd, r) + idx;
-            tile_y = moved / gx;
-            tile_x = moved - tile_y * gx;
+            if (col_major) {
+                tile_x = moved / gy;
+                tile_y = moved - tile_x * gy;
+            } else {
+                tile_y = moved / gx;
+                tile_x = moved - tile_y * gx;
+            }
         }
     }
     const int m0 = tile_y * BM, n0 = tile_x * BN, z = blockIdx.z;
@@ -492,7 +499,35 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
     // row 8*(r/4) + 4*(lane/32) + r%4.  Output offsets advance by additions only.
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
     const int64_t ld = epi.ld;
-    if (m0 + BM <= M && n0 + BN <= N) {
+    if (wide) {
+        // 8-wide form (N a multiple of 8, every tensor of the epilogue 16-byte aligned): each wave transposes a 32x32
+        // block of results through LDS (the k-loop ended with a barrier, the tiles are free; a wave uses a region of
+        // its own) and leaves with 8 consecutive columns of one row per lane, so that the epilogue reads and writes
+        // 16 bytes per lane where the element-wise form below moves 2.  Rows are 40 floats apart: the two half-waves,
+        // 4 rows apart, then write to disjoint banks.
+        constexpr int SP = 40;
+        float* const stage = reinterpret_cast<float*>(smem_raw) + wave * (32 * SP);
+        static_assert(4 * 32 * SP * 4 <= gemm2_lds_bytes<BM, BN, AOp, BOp>(), "staging area exceeds the tile buffers");
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + row_in + (r & 3)) * SP + col_in] = acc[0][i][j][r];
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 3) * 8;
+#pragma unroll
+                for (int ps = 0; ps < 2; ++ps) {
+                    const int row = ps * 16 + (lane >> 2);
+                    const float4 lo = *reinterpret_cast<const float4*>(stage + row * SP + (lane & 3) * 8);
+                    const float4 hi = *reinterpret_cast<const float4*>(stage + row * SP + (lane & 3) * 8 + 4);
+                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    const int m = m0 + wm * (BM / 2) + i * 32 + row;
+                    if (m < M && n < N) epi.at8(n, (int64_t)m * ld + n, v, z);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten
+            }
+    } else if (m0 + BM <= M && n0 + BN <= N) {
         // Interior block: no bounds tests, hence no branch between the stores (a branch makes the
         // compiler wait for every earlier store before the next one).
 #pragma unroll
@@ -531,6 +566,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
 struct EpiPartial {
     float* part;
     int64_t ld, slice_stride;
+    bool wide_ok() const { return ld % 8 == 0 && slice_stride % 4 == 0 && epi_al16(part); }
     __device__ __forceinline__ int column(int) const { return 0; }
     __device__ __forceinline__ void at(int, int64_t idx, float v, int z) const {
         part[z * slice_stride + idx] = v;

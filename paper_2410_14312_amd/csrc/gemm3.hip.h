@@ -130,7 +130,8 @@ template <int ROWS, int BK, int T, bool KC> struct G3Frags {
 struct G3Plan {
     int tiles_m, tiles_n, slices, k_per_slice;  // k_per_slice a multiple of the kernel's BK
     int units;                                  // tiles_m * tiles_n * slices
-    FastDiv d_tn, d_tiles;                      // by tiles_n and by tiles_m * tiles_n
+    int col_major;                              // consecutive units walk down a column of tiles (share B) instead of along a row (share A)
+    FastDiv d_tn, d_tiles;                      // by tiles_n (tiles_m when col_major) and by tiles_m * tiles_n
 };
 
 // ROWSUM: units of the first tile column also sum A over k (bias gradient of a weight-gradient GEMM, whose
@@ -166,7 +167,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     auto unit_coords = [&](int u, int& tm, int& tn, int& z) {
         uint32_t zz, rem, m_, n_;
         plan.d_tiles.divmod((uint32_t)u, zz, rem);
-        plan.d_tn.divmod(rem, m_, n_);
+        if (plan.col_major) plan.d_tn.divmod(rem, n_, m_);
+        else plan.d_tn.divmod(rem, m_, n_);
         z = (int)zz; tm = (int)m_; tn = (int)n_;
     };
     auto unit_nk = [&](int z) {

@@ -89,7 +89,9 @@ static hipError_t launch2_inst(int kc, const AOp& A, const BOp& B, const Epi& ep
         if (attr != hipSuccess) return attr;
     }
     dim3 grid(cdiv(N, BN), cdiv(M, BM), nz);
-    return launch_timed(kc, kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per);
+    // the XCDs split the operand with more rows between them and each reads the other one whole
+    return launch_timed(kc, kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per, N > M ? 1 : 0,
+                        (N % 8 == 0 && epi.wide_ok()) ? 1 : 0);
 }
 
 template <bool ROWSUM, class AOp, class BOp, class Epi>
@@ -169,7 +171,8 @@ static G3Plan g3_plan(int M, int N, int K, int slices) {
     p.k_per_slice = per;
     p.slices = cdiv(K, per);
     p.units = p.tiles_m * p.tiles_n * p.slices;
-    p.d_tn = FastDiv(p.tiles_n);
+    p.col_major = N > M ? 1 : 0;   // the XCDs split the operand with more rows between them and each reads the other one whole
+    p.d_tn = FastDiv(p.col_major ? p.tiles_m : p.tiles_n);
     p.d_tiles = FastDiv(p.tiles_m * p.tiles_n);
     return p;
 }
