@@ -397,6 +397,114 @@ __global__ __launch_bounds__(256) void maxpool_bwd_bf16x8_kernel(const bf16_t* _
     *reinterpret_cast<uint4*>(dx + i * 8) = out.u;
 }
 
+// Large feature maps: a workgroup owns an 8 x 16 tile of input positions of one image and up to 64 channels.
+//   1. Every input position that shares a window with the tile (at most k-1 more rows and columns on each side) is
+//      copied into LDS, 128 bytes per position: x is read from memory once (plus the halo).
+//   2. Every window that touches the tile is scanned ONCE (per 8 channels) in row-major order for its first maximum;
+//      the winner's place in the window (r * k + q) is kept in LDS, one byte per channel.
+//   3. Every position of the tile looks up the (at most ceil(k / stride)^2) windows that contain it and adds dy where the
+//      stored place is its own.
+// Scanning a window once instead of once per element it contains is what makes the difference: the per-element gather
+// above spends 4 k^2 comparisons per element and channel and is bound by the vector ALUs on large maps.
+constexpr int kPoolTH = 8, kPoolTW = 16;
+__global__ __launch_bounds__(256) void maxpool_bwd_tiled_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
+                                                                     bf16_t* __restrict__ dx, int H, int W, int C, int Ho,
+                                                                     int Wo, int k, int stride, int pad, int relu_mask,
+                                                                     int groups, int patch_bytes) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char pool_smem[];
+    uint4* const patch = reinterpret_cast<uint4*>(pool_smem);                 // [rows][cols][8 chunks of 8 channels]
+    uint2* const place = reinterpret_cast<uint2*>(pool_smem + patch_bytes);   // [windows][8 chunks]: 8 bytes = 8 channels
+    const int C8 = C >> 3;
+    const int n = blockIdx.z / groups, c8base = (blockIdx.z % groups) * 8;
+    const int h0 = blockIdx.y * kPoolTH, w0 = blockIdx.x * kPoolTW;
+    const int h1 = min(h0 + kPoolTH, H) - 1, w1 = min(w0 + kPoolTW, W) - 1;   // last position of the tile
+    // windows that contain a position of the tile, and the input positions they cover
+    const int ho_lo = h0 + pad - k + 1 > 0 ? (h0 + pad - k + 1 + stride - 1) / stride : 0;
+    const int wo_lo = w0 + pad - k + 1 > 0 ? (w0 + pad - k + 1 + stride - 1) / stride : 0;
+    const int ho_hi = min(Ho - 1, (h1 + pad) / stride), wo_hi = min(Wo - 1, (w1 + pad) / stride);
+    const int nwh = max(0, ho_hi - ho_lo + 1), nww = max(0, wo_hi - wo_lo + 1);
+    const int ph0 = max(0, ho_lo * stride - pad), pw0 = max(0, wo_lo * stride - pad);
+    const int ph1 = min(H - 1, ho_hi * stride - pad + k - 1), pw1 = min(W - 1, wo_hi * stride - pad + k - 1);
+    const int nph = max(0, ph1 - ph0 + 1), npw = max(0, pw1 - pw0 + 1);
+    const bf16_t* xn = x + (int64_t)n * H * W * C;
+    for (int idx = threadIdx.x; idx < nph * npw * 8; idx += 256) {
+        const int pos = idx >> 3, ch = idx & 7;
+        const int pr = pos / npw, pc = pos - pr * npw;
+        if (c8base + ch < C8)
+            patch[idx] = *reinterpret_cast<const uint4*>(xn + (((int64_t)(ph0 + pr) * W + pw0 + pc) * C8 + c8base + ch) * 8);
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < nwh * nww * 8; idx += 256) {
+        const int wi = idx >> 3, ch = idx & 7;
+        if (c8base + ch >= C8) continue;
+        const int wr = wi / nww, wc = wi - wr * nww;
+        const int hb = (ho_lo + wr) * stride - pad, wb = (wo_lo + wc) * stride - pad;
+        float best[8];
+        unsigned where[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            best[e] = -INFINITY;
+            where[e] = 255u;
+        }
+        for (int r = 0; r < k; ++r)
+            for (int q = 0; q < k; ++q) {
+                const int hh = hb + r, ww = wb + q;
+                if ((unsigned)hh >= (unsigned)H || (unsigned)ww >= (unsigned)W) continue;
+                Pack8 o;
+                o.u = patch[((hh - ph0) * npw + (ww - pw0)) * 8 + ch];
+                const unsigned me = (unsigned)(r * k + q);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float v = (float)o.h[e];
+                    if (v > best[e]) {   // strict: the first maximum in row-major order stays
+                        best[e] = v;
+                        where[e] = me;
+                    }
+                }
+            }
+        uint2 pk;
+        pk.x = where[0] | (where[1] << 8) | (where[2] << 16) | (where[3] << 24);
+        pk.y = where[4] | (where[5] << 8) | (where[6] << 16) | (where[7] << 24);
+        place[idx] = pk;
+    }
+    __syncthreads();
+    for (int it = threadIdx.x; it < kPoolTH * kPoolTW * 8; it += 256) {
+        const int pos = it >> 3, ch = it & 7;
+        const int h = h0 + pos / kPoolTW, w = w0 + pos % kPoolTW, c8 = c8base + ch;
+        if (h >= H || w >= W || c8 >= C8) continue;
+        const int64_t i = (((int64_t)n * H + h) * W + w) * C8 + c8;
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+        const int hp = h + pad, wp = w + pad;
+        const int a_lo = hp - k + 1 > 0 ? (hp - k + 1 + stride - 1) / stride : 0;
+        const int b_lo = wp - k + 1 > 0 ? (wp - k + 1 + stride - 1) / stride : 0;
+        for (int ho = a_lo; ho < Ho && ho * stride <= hp; ++ho)
+            for (int wo = b_lo; wo < Wo && wo * stride <= wp; ++wo) {
+                const unsigned me = (unsigned)((hp - ho * stride) * k + (wp - wo * stride));
+                const uint2 pk = place[((ho - ho_lo) * nww + (wo - wo_lo)) * 8 + ch];
+                Pack8 g;
+                g.u = *reinterpret_cast<const uint4*>(dy + ((((int64_t)n * Ho + ho) * Wo + wo) * C8 + c8) * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned wv = ((e < 4 ? pk.x : pk.y) >> (8 * (e & 3))) & 255u;
+                    if (wv == me) acc[e] += (float)g.h[e];
+                }
+            }
+        Pack8 out;
+        if (relu_mask) {
+            Pack8 mine;
+            mine.u = *reinterpret_cast<const uint4*>(x + i * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (!((float)mine.h[e] > 0.0f)) acc[e] = 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out.h[e] = (bf16_t)acc[e];
+        *reinterpret_cast<uint4*>(dx + i * 8) = out.u;
+    }
+}
+
 // 2x2 windows with stride 2 on even H, W and C % 8 == 0 (bf16): one thread per window and 8 channels,
 // 16-byte loads of the 4 inputs and of dy, 16-byte stores of the 4 gradients.
 __global__ __launch_bounds__(256) void maxpool2x2_bwd_bf16_kernel(const bf16_t* __restrict__ x,
@@ -465,6 +573,18 @@ hipError_t maxpool_backward(int dtype, const void* x, const void* dy, void* dx, 
     }
     if (dtype == kBF16 && C % 8 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(dx) & 15) == 0) {
+        // large maps: the LDS-tiled form (its patch of (8 + 2(k-1)) x (16 + 2(k-1)) positions x 128 bytes and the
+        // winners of at most (8 + k-1) x (16 + k-1) windows x 64 bytes must fit; a window has at most 255 places)
+        const int groups = (C / 8 + 7) / 8;
+        const int64_t patch_bytes = (int64_t)(kPoolTH + 2 * (k - 1)) * (kPoolTW + 2 * (k - 1)) * 128;
+        const int64_t lds = patch_bytes + (int64_t)(kPoolTH + k - 1) * (kPoolTW + k - 1) * 64;
+        const int64_t blocks_z = (int64_t)B * groups;
+        if (H >= 2 * kPoolTH && W >= 2 * kPoolTW && lds <= 64 * 1024 && blocks_z <= 65535 && k * k <= 255) {
+            dim3 grid((W + kPoolTW - 1) / kPoolTW, (H + kPoolTH - 1) / kPoolTH, (unsigned)blocks_z);
+            hipLaunchKernelGGL(maxpool_bwd_tiled_bf16_kernel, grid, dim3(256), (unsigned)lds, s, (const bf16_t*)x, (const bf16_t*)dy,
+                               (bf16_t*)dx, H, W, C, Ho, Wo, k, stride, pad, relu_mask, groups, (int)patch_bytes);
+            return hipGetLastError();
+        }
         hipLaunchKernelGGL(maxpool_bwd_bf16x8_kernel, dim3(cdiv64(total / 8, 256)), dim3(256), 0, s, (const bf16_t*)x,
                            (const bf16_t*)dy, (bf16_t*)dx, B, H, W, C, Ho, Wo, k, stride, pad, relu_mask);
         return hipGetLastError();

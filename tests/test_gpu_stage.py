@@ -264,6 +264,19 @@ def test_pool_first_and_overlapping_windows(dtype):
     run_stage_case([maxpool(9, 9, 8, k=3, stride=2), conv(4, 4, 8, 8)], dtype, 3, 2, seed=10, has_pool=True)
 
 
+@pytest.mark.parametrize("h,w,c,k,stride,pad", [
+    (37, 45, 72, 3, 2, 1),   # the LDS-tiled gather: ragged tiles at both edges, a ragged last group of channels
+    (24, 32, 16, 3, 1, 1),   # every element in nine windows
+    (33, 40, 8, 2, 2, 0),    # odd height: the last row belongs to no window
+    (20, 36, 64, 5, 3, 2),   # wide windows
+])
+def test_pool_on_large_maps(h, w, c, k, stride, pad):
+    # the pooling layer comes first, so both sides pick their winners on identical inputs: the strict bar applies
+    ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+    run_stage_case([maxpool(h, w, c, k, stride, pad), conv(ho, wo, c, 8, 1, 1, 0, False)], "bf16", 2, 2,
+                   seed=h + w + c + k)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_conv_pool_fc_loss_stage(dtype):
     specs = [conv(4, 4, 16, 32), maxpool(4, 4, 32), linear(2 * 2 * 32, 64, True), linear(64, 10, False), softmax_ce(10)]
