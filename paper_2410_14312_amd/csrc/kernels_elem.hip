@@ -212,8 +212,27 @@ __global__ void relu_mask_kernel(const T* __restrict__ dy, const T* __restrict__
     for (; i < n; i += stride) dz[i] = to_f32(y[i]) > 0.0f ? dy[i] : T(0.0f);
 }
 
+// bf16, 8 elements (16 bytes) per thread and access
+__global__ __launch_bounds__(256) void relu_mask_bf16x8_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ y,
+                                                               bf16_t* __restrict__ dz, int64_t n8) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n8) return;
+    Pack8 g, v;
+    g.u = reinterpret_cast<const uint4*>(dy)[i];
+    v.u = reinterpret_cast<const uint4*>(y)[i];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (!((float)v.h[e] > 0.0f)) g.h[e] = (bf16_t)0.0f;
+    reinterpret_cast<uint4*>(dz)[i] = g.u;
+}
+
 hipError_t relu_mask(int dtype, const void* dy, const void* y, void* dz, int64_t n, hipStream_t s) {
     if (n <= 0) return hipSuccess;
+    if (dtype == kBF16 && n % 8 == 0 && ((reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(dz)) & 15) == 0) {
+        hipLaunchKernelGGL(relu_mask_bf16x8_kernel, dim3(cdiv64(n / 8, 256)), dim3(256), 0, s, (const bf16_t*)dy, (const bf16_t*)y,
+                           (bf16_t*)dz, n / 8);
+        return hipGetLastError();
+    }
     int blocks = cdiv64(n, 256);
     if (blocks > 4096) blocks = 4096;
     if (dtype == kBF16)
@@ -305,6 +324,36 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, i
             if (v > best) best = v;
         }
     y[i] = from_f32<T>(best);
+}
+
+// The same with 8 channels (16 bytes) per thread and access, bf16, C % 8 == 0.
+__global__ __launch_bounds__(256) void maxpool_fwd_bf16x8_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y, int B, int H,
+                                                                 int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+    const int C8 = C >> 3;
+    const int64_t total = (int64_t)B * Ho * Wo * C8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c8 = (int)(i % C8);
+    int64_t t = i / C8;
+    const int wo = (int)(t % Wo); t /= Wo;
+    const int ho = (int)(t % Ho);
+    const int n = (int)(t / Ho);
+    float best[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+    for (int r = 0; r < k; ++r)
+        for (int q = 0; q < k; ++q) {
+            const int hh = ho * stride - pad + r, ww = wo * stride - pad + q;
+            if ((unsigned)hh >= (unsigned)H || (unsigned)ww >= (unsigned)W) continue;   // padding never wins
+            Pack8 o;
+            o.u = *reinterpret_cast<const uint4*>(x + ((((int64_t)n * H + hh) * W + ww) * C8 + c8) * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], (float)o.h[e]);
+        }
+    Pack8 out;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out.h[e] = (bf16_t)best[e];
+    *reinterpret_cast<uint4*>(y + i * 8) = out.u;
 }
 
 // Gather form, one thread per INPUT element: sum dy over the windows whose winner (first maximum in
@@ -548,6 +597,11 @@ hipError_t maxpool_forward(int dtype, const void* x, void* y, int B, int H, int 
     int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     int64_t total = (int64_t)B * Ho * Wo * C;
     if (total <= 0) return hipSuccess;
+    if (dtype == kBF16 && C % 8 == 0 && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0) {
+        hipLaunchKernelGGL(maxpool_fwd_bf16x8_kernel, dim3(cdiv64(total / 8, 256)), dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y,
+                           B, H, W, C, Ho, Wo, k, stride, pad);
+        return hipGetLastError();
+    }
     dim3 grid(cdiv64(total, 256));
     if (dtype == kBF16)
         hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, B, H,
