@@ -291,7 +291,8 @@ template <typename TOut> struct EpiBiasAct {
 
 // Convolution followed by a per-channel affine layer and, optionally, a residual join, in one epilogue:
 //   z = v + bias[n]                        -> out   (the convolution's result, kept for the affine layer's gradient)
-//   a = gain[n] * z + shift[n]             -> aout  (may be null when no later layer reads it... the join case stores it)
+//   a = gain[n] * z + shift[n]             -> aout  (null when nothing reads it: the backward pass of the affine layer
+//                                                    needs z, that of the join only y)
 //   y = act(a + res[m, n])                 -> yout  (res may be null)
 // Every stored tensor is rounded to its storage type before the next step reads it, exactly as if the three layers
 // had run one after the other.
@@ -301,7 +302,7 @@ template <typename TOut> struct EpiConvAffine {
     int64_t ld;
     const float* gain;
     const float* shift;
-    TOut* aout;          // affine result; null when the affine layer itself applies the activation and writes yout
+    TOut* aout;          // affine result; null when the affine layer itself writes yout, or when only the join reads it
     const TOut* res;     // second source of the residual join; may be null
     TOut* yout;
     int relu;
@@ -314,12 +315,9 @@ template <typename TOut> struct EpiConvAffine {
     __device__ __forceinline__ void at(const Col& c, int64_t idx, float v, int) const {
         const TOut z = from_f32<TOut>(v + c.b);
         out[idx] = z;
-        float a = c.g * to_f32(z) + c.s;
-        if (aout) {
-            const TOut ar = from_f32<TOut>(a);
-            aout[idx] = ar;
-            a = to_f32(ar);
-        }
+        const TOut ar = from_f32<TOut>(c.g * to_f32(z) + c.s);   // rounded as the stored tensor would be, stored or not
+        if (aout) aout[idx] = ar;
+        float a = to_f32(ar);
         if (res) a += to_f32(res[idx]);
         if (relu) a = a > 0.0f ? a : 0.0f;
         yout[idx] = from_f32<TOut>(a);
@@ -340,11 +338,9 @@ template <typename TOut> struct EpiConvAffine {
         store8(out + idx, v);
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = g[e] * v[e] + sh[e];
-        if (aout) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = to_f32(from_f32<TOut>(v[e]));
-            store8(aout + idx, v);
-        }
+        for (int e = 0; e < 8; ++e) v[e] = to_f32(from_f32<TOut>(v[e]));   // rounded as the stored tensor would be
+        if (aout) store8(aout + idx, v);
         if (res) {
             float r[8];
             load8(res + idx, r);

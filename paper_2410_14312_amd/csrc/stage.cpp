@@ -412,10 +412,11 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
                                       st->readers[li + 2] == 1;
                     void* aout = st->out_ptr(A, row0);
                     if (join) {
+                        // the affine result itself is not stored: only the join reads it, and no gradient needs it
                         const LayerRT& J = st->layers[li + 2];
                         const void* b = J.in_b < 0 ? x0 : (const void*)st->out_ptr(st->layers[J.in_b], row0);
                         TMPS_GEMM(conv_affine_forward(dt, in, st->wptr(L), st->bptr(L), out, st->master + A.w_off, st->master + A.b_off,
-                                                      aout, b, st->out_ptr(J, row0), J.relu, conv_shape(L.d, mb), ws, s));
+                                                      nullptr, b, st->out_ptr(J, row0), J.relu, conv_shape(L.d, mb), ws, s));
                         li += 2;
                     } else {
                         TMPS_GEMM(conv_affine_forward(dt, in, st->wptr(L), st->bptr(L), out, st->master + A.w_off, st->master + A.b_off,
