@@ -90,21 +90,25 @@ __global__ __launch_bounds__(256) void softmax_ce_wide_kernel(const float* __res
     if (tid == 0) row_loss[row] = label_ok ? logf(bs) - (z[label] - bm) : NAN;
 }
 
-// Wide rows that fit in LDS (C fp32 values, C % 4 == 0): one 256-thread block per row reads the row from HBM ONCE,
+// Wide rows that fit in LDS (C fp32 values, C % 4 == 0): one 1024-thread block per row reads the row from HBM ONCE,
 // keeps it in LDS for the maximum, the sum and the gradient, and writes the gradient: algorithmic traffic exactly.
+// A row of a large vocabulary takes most of a compute unit's LDS, so one workgroup is all a unit holds: 16 waves
+// (not 4) keep enough loads in flight.  Exponentials on the hardware exp2 (a few ulp of fp32).
+constexpr int kCeThreads = 1024;
 template <typename TG>
-__global__ __launch_bounds__(256) void softmax_ce_lds_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
-                                                             TG* __restrict__ dlogits, float* __restrict__ row_loss, int C,
-                                                             float inv_M) {
+__global__ __launch_bounds__(kCeThreads) void softmax_ce_lds_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                                    TG* __restrict__ dlogits, float* __restrict__ row_loss, int C,
+                                                                    float inv_M) {
     extern __shared__ __attribute__((aligned(16))) float srow[];
-    __shared__ float sm[4], ss[4];
+    constexpr int NWV = kCeThreads / 64;
+    __shared__ float sm[NWV], ss[NWV];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
     const float4* z4 = reinterpret_cast<const float4*>(logits + row * C);
     float4* s4 = reinterpret_cast<float4*>(srow);
     const int C4 = C >> 2;
     float mx = -INFINITY;
-    for (int c = tid; c < C4; c += 256) {
+    for (int c = tid; c < C4; c += kCeThreads) {
         const float4 v = z4[c];
         s4[c] = v;
         mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
@@ -112,23 +116,27 @@ __global__ __launch_bounds__(256) void softmax_ce_lds_kernel(const float* __rest
     mx = wave_max(mx);
     if (lane == 0) sm[wave] = mx;
     __syncthreads();
-    const float bm = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    float bm = sm[0];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) bm = fmaxf(bm, sm[w]);
     float sum = 0.0f;
-    for (int c = tid; c < C4; c += 256) {
+    for (int c = tid; c < C4; c += kCeThreads) {
         float4 v = s4[c];
-        v.x = expf(v.x - bm); v.y = expf(v.y - bm); v.z = expf(v.z - bm); v.w = expf(v.w - bm);
+        v.x = __expf(v.x - bm); v.y = __expf(v.y - bm); v.z = __expf(v.z - bm); v.w = __expf(v.w - bm);
         s4[c] = v;   // keep the exponentials: the gradient needs them again
         sum += (v.x + v.y) + (v.z + v.w);
     }
     sum = wave_sum(sum);
     if (lane == 0) ss[wave] = sum;
     __syncthreads();
-    const float bs = (ss[0] + ss[1]) + (ss[2] + ss[3]);
+    float bs = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) bs += ss[w];
     const float inv = 1.0f / bs;
     const int label = labels[row];
     const bool label_ok = label >= 0 && label < C;
     TG* g = dlogits + row * C;
-    for (int c = tid; c < C4; c += 256) {
+    for (int c = tid; c < C4; c += kCeThreads) {
         const float4 e = s4[c];
         float p[4] = {e.x * inv, e.y * inv, e.z * inv, e.w * inv};
         const int c0 = c * 4;
@@ -143,7 +151,6 @@ __global__ __launch_bounds__(256) void softmax_ce_lds_kernel(const float* __rest
             *reinterpret_cast<float4*>(g + c0) = make_float4(p[0], p[1], p[2], p[3]);
         }
     }
-    // exp(z[label] - bm) = srow[label] after the second pass: loss = log(sum) - (z[label] - bm) = log(sum) - log(srow[label])
     if (tid == 0) row_loss[row] = label_ok ? logf(bs) - (logits[row * C + label] - bm) : NAN;
 }
 
@@ -157,13 +164,13 @@ hipError_t softmax_ce(int dtype, const float* logits, const int32_t* labels, voi
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_ce_lds_kernel<bf16_t>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
             if (attr != hipSuccess) return attr;
-            hipLaunchKernelGGL(softmax_ce_lds_kernel<bf16_t>, dim3(rows), dim3(256), lds, s, logits, labels, (bf16_t*)dlogits,
+            hipLaunchKernelGGL(softmax_ce_lds_kernel<bf16_t>, dim3(rows), dim3(kCeThreads), lds, s, logits, labels, (bf16_t*)dlogits,
                                row_loss, C, inv_M);
         } else {
             static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_ce_lds_kernel<float>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
             if (attr != hipSuccess) return attr;
-            hipLaunchKernelGGL(softmax_ce_lds_kernel<float>, dim3(rows), dim3(256), lds, s, logits, labels, (float*)dlogits,
+            hipLaunchKernelGGL(softmax_ce_lds_kernel<float>, dim3(rows), dim3(kCeThreads), lds, s, logits, labels, (float*)dlogits,
                                row_loss, C, inv_M);
         }
         return hipGetLastError();
