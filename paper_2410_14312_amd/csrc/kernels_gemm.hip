@@ -26,14 +26,15 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const bool wide = N > 64 && M > 64;
     // A short output (a micro-batch's rows) with fewer 128-tiles than compute units is latency-bound: more, smaller
     // workgroups finish sooner (measured on 1024-row transformer GEMMs: 13 us against 16 us).
-    const bool short_rows = M <= 2048 && t128 < 256;
-    p.tile = (wide && t128 >= 64 && !short_rows) ? 128 : 64;
+    const bool short_rows = M <= 2048 && t128 < 256 && K <= 4096;
+    // (a long contraction is cut into slices anyway: then a dozen 128-tiles suffice to fill the device)
+    p.tile = (wide && !short_rows && (t128 >= 64 || (K > 4096 && t128 >= 8))) ? 128 : 64;
     const int64_t tiles = p.tile == 128 ? t128 : t64;
     const int64_t target = 384;  // swept 32..2048 on the VGG workload: flat optimum around 384-512
     int64_t s = 1;
     // (short outputs with a hundred tiles or more and a short contraction are not split: the finishing kernel costs
     // more than the split saves)
-    if (tiles < target && !(short_rows && tiles >= 128 && K <= 4096)) {
+    if (tiles < target && !(short_rows && tiles >= 128)) {
         s = (target + tiles - 1) / tiles;
         const int64_t by_k = K / 128;
         const int64_t by_bytes = ((M + N) * K) / (2 * M * N);
