@@ -3,6 +3,7 @@
 // with aligned 16-byte loads (channel / feature counts that are multiples of 8), and the
 // element-wise skeleton of gemm.hip.h otherwise (3-channel input layer, 10-way logits layer);
 // fp32 stages use the fp32 skeleton.
+#include <cstdlib>
 #include <hip/hip_ext.h>
 
 #include "gemm3.hip.h"
@@ -162,7 +163,12 @@ static int g3_wgrad_slices(int64_t M, int64_t N, int64_t K) {
     if (s < 1) s = 1;
     return tiles * s >= 144 ? (int)s : 0;
 }
-static bool g3_forward_ok(int64_t M, int64_t N, int64_t K) { return K % 64 == 0 && N % 8 == 0 && g3_tiles(M, N) >= 192; }
+// Not for a contraction of a single k-tile, which is all epilogue (many small workgroups keep more memory requests in
+// flight than one persistent workgroup per compute unit), nor when more than a quarter of the 256-wide tiles would be
+// padding (measured on the 1x1 convolutions of the residual networks).
+static bool g3_forward_ok(int64_t M, int64_t N, int64_t K) {
+    return K % 64 == 0 && K >= 128 && N % 8 == 0 && g3_tiles(M, N) >= 192 && (int64_t)cdiv(N, 256) * 256 * 3 <= N * 4;
+}
 
 static G3Plan g3_plan(int M, int N, int K, int slices) {
     G3Plan p;
