@@ -206,7 +206,9 @@ int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, cons
 /* Streams for tmps_schedule_run.  The runtime spreads streams over a small number of hardware queues in creation
  * order; streams that land on the same queue run one after the other.  tmps_streams_create makes n streams back to
  * back (default priority, non-blocking with respect to the null stream), which puts up to as many of them as there are
- * hardware queues on distinct queues.  out: host array of n stream handles.  The caller destroys them with
+ * hardware queues on distinct queues (the runtime uses 4 hardware queues unless the environment variable
+ * GPU_MAX_HW_QUEUES, read when HIP starts, says otherwise; K stage streams beside the default stream need K + 1, or two
+ * stages take turns on one queue).  out: host array of n stream handles.  The caller destroys them with
  * tmps_streams_destroy once no work is pending on them.  Returns TMPS_OK or TMPS_EHIP. */
 int tmps_streams_create(void** out, int n);
 int tmps_streams_destroy(void** streams, int n);
