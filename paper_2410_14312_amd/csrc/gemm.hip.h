@@ -207,6 +207,13 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
     gelu_parts(z, Phi, E);
     return Phi + z * 0.3989422804014327f * E;
 }
+// both at once: y = gelu(z), d = gelu'(z)
+__device__ __forceinline__ void gelu_both(float z, float& y, float& d) {
+    float Phi, E;
+    gelu_parts(z, Phi, E);
+    y = z * Phi;
+    d = Phi + z * 0.3989422804014327f * E;
+}
 
 enum { kActNone = 0, kActRelu = 1, kActGelu = 2 };
 
@@ -236,8 +243,10 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
 // start keeps that alignment.
 static inline bool epi_al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-// out[m, n] = act(v + bias[n]) + res[m, n].  With GELU the pre-activation is also stored (zout), for the
-// derivative in the backward pass.  res: a residual connection's source, same shape as out.
+// out[m, n] = act(v + bias[n]) + res[m, n].  With GELU the DERIVATIVE gelu'(v + bias[n]) is stored as well (zout): the
+// backward pass then multiplies by a stored factor, as it does for ReLU, instead of evaluating an erf and an
+// exponential per element in the epilogue of the input-gradient GEMM (where that cost more than the GEMM's k-loop).
+// res: a residual connection's source, same shape as out.
 template <typename TOut> struct EpiBiasAct {
     TOut* out;
     const float* bias;  // may be null
@@ -248,8 +257,9 @@ template <typename TOut> struct EpiBiasAct {
     __device__ __forceinline__ void finish(int64_t idx, float v) const {
         if (relu == kActRelu) v = v > 0.0f ? v : 0.0f;
         else if (relu == kActGelu) {
-            if (zout) zout[idx] = from_f32<TOut>(v);
-            v = gelu_f(v);
+            float d;
+            gelu_both(v, v, d);
+            if (zout) zout[idx] = from_f32<TOut>(d);
         }
         if (res) v += to_f32(res[idx]);
         out[idx] = from_f32<TOut>(v);
@@ -274,9 +284,10 @@ template <typename TOut> struct EpiBiasAct {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
         } else if (relu == kActGelu) {
-            if (zout) store8(zout + idx, v);
+            float d[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+            for (int e = 0; e < 8; ++e) gelu_both(v[e], v[e], d[e]);
+            if (zout) store8(zout + idx, d);
         }
         if (res) {
             float r[8];
@@ -358,7 +369,7 @@ template <typename TOut> struct EpiConvAffine {
 };
 
 // Gradient through the stored activation of the layer below: mode kActRelu: v where mask[m, n] > 0 else 0
-// (mask = that layer's output); mode kActGelu: v * gelu'(mask[m, n]) (mask = that layer's pre-activation).
+// (mask = that layer's output); mode kActGelu: v * mask[m, n] (mask = the derivative stored by that layer's forward pass).
 // add (may be null, may be out itself): what other readers of the same tensor have already contributed to its
 // gradient; it joins v before the mask is applied.
 template <typename TOut, typename TMask> struct EpiMask {
@@ -371,7 +382,7 @@ template <typename TOut, typename TMask> struct EpiMask {
         if (add) v += to_f32(add[i]);
         if (mask) {
             const float t = to_f32(mask[i]);
-            if (mode == kActGelu) v *= gelu_grad_f(t);
+            if (mode == kActGelu) v *= t;
             else if (!(t > 0.0f)) v = 0.0f;
         }
         out[i] = from_f32<TOut>(v);
@@ -392,7 +403,7 @@ template <typename TOut, typename TMask> struct EpiMask {
             load8(mask + i, t);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                if (mode == kActGelu) v[e] *= gelu_grad_f(t[e]);
+                if (mode == kActGelu) v[e] *= t[e];
                 else if (!(t[e] > 0.0f)) v[e] = 0.0f;
             }
         }

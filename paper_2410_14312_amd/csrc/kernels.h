@@ -28,7 +28,7 @@ size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t K, int with_rowsum);
 
 // y[B, Dout] = act(x[B, Din] w^T + b).  w is the working copy (bf16 or fp32 per dtype), bias fp32.
 // out_f32: write fp32 regardless of dtype (logits).
-// act: 0 none, 1 ReLU, 2 exact GELU (then zout, if not null, receives the pre-activation).  res (may be
+// act: 0 none, 1 ReLU, 2 exact GELU (then zout, if not null, receives the derivative gelu'(pre-activation) for the backward pass).  res (may be
 // null): tensor of y's shape and dtype added after the activation (residual connection).
 hipError_t dense_forward(int dtype, const void* x, const void* w, const float* bias, void* y, int B,
                          int Din, int Dout, int act, int out_f32, const void* res, void* zout, float* ws,

@@ -12,7 +12,7 @@ struct LayerRT {
     size_t out_off = 0;    // stash byte offset of this layer's output array (all slots)
     size_t out_esize = 0;  // bytes per element of that array
     size_t aux_off = 0;    // softmax-CE: stash byte offset of the per-row losses (fp32)
-    size_t z_off = 0;      // GELU linear: stash byte offset of the stored pre-activations
+    size_t z_off = 0;      // GELU linear: stash byte offset of the stored derivatives gelu'(pre-activation)
     bool relu = false;
     int act = 0;           // 0 none, 1 ReLU, 2 GELU (linear / convolution epilogue)
     int rps = 1;           // rows per sample the layer works on (sequence positions)
