@@ -83,6 +83,16 @@ def test_v_greater_than_one_schedule_runs_and_logs():
     _compare(cfg, 9, bias_std=0.05)
 
 
+def test_version_difference_three_on_seven_streams():
+    # W=7 stages, N=2: three interleaved update sequences; the forward passes of worker 0 run on weights 6 updates old
+    layers = [linear(32, 32, True) for _ in range(6)] + [linear(32, 10, False), softmax_ce(10)]
+    stages = [[l] for l in layers[:6]] + [layers[6:]]
+    cfg = Config(name="t", dtype="f32", M=8, N=2, stages=stages, in_shape=(32,), classes=10, seed=11, lr=0.005)
+    from paper_2410_14312_amd import version_diff_simulated
+    assert version_diff_simulated(7, 2) == 3
+    _compare(cfg, 24, bias_std=0.05)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_small_conv_net_three_stages(dtype):
     stages = [[conv(8, 8, 3, 16), conv(8, 8, 16, 16), maxpool(8, 8, 16)],
