@@ -144,6 +144,13 @@ int tmps_stage_sync_params(tmps_stage* stage, void* hip_stream);
 void* tmps_stage_output_ptr(const tmps_stage* stage, int slot);
 /* Number of weight updates applied so far (the stage's weight version). */
 long tmps_stage_version(const tmps_stage* stage);
+/* Stage-wise checkpoints (section "Checkpointing": every stage saves its own parameters after the backward pass of
+ * an epoch's last mini-batch, and a run that ended abnormally resumes from the latest epoch all stages completed).
+ * The parameters and the optimizer state live in the caller's `params` / `state` regions and are copied by the caller;
+ * this call restores the third piece of a stage's state, its update counter (version >= 0; TMPS_EINVAL otherwise, or
+ * TMPS_ESLOT while a stash slot is in use: checkpoints are taken between mini-batches).  After writing master
+ * parameters into `params`, call tmps_stage_sync_params to refresh the working copy. */
+int tmps_stage_set_version(tmps_stage* stage, long version);
 
 /* ---- the three steps of a stage's training step ----
  *

@@ -13,13 +13,17 @@ from . import schedule as S
 from .stage import Stage
 
 
-def run(cfg, params, batches, trace=None, precision=None):
+def run(cfg, params, batches, trace=None, precision=None, momentum=None, versions=None):
     """Train `len(batches)` mini-batches.
 
     cfg: a workloads.Config (shape tables only); params: per stage, per layer dicts of arrays;
     batches: list of (x [M, ...], labels [M]).  precision: storage policy ("f64" or "bf16", see
     oracle/precision.py); by default the one the configuration names.  trace: optional dict that receives every task's
     tensors under (kind, b, j, stage) keys.
+    momentum, versions: state to resume from (section "Checkpointing": a run restarts from the parameters every
+    stage saved at the end of an epoch; with momentum the buffers and the update counters belong to that state):
+    per stage, per layer dicts like params, and per stage update counts.  The version log of a resumed run counts
+    from zero again.
     Returns dict(losses=[per mini-batch mean of the micro-batch losses], ops=version log,
     stages=[Stage]).
     """
@@ -28,13 +32,19 @@ def run(cfg, params, batches, trace=None, precision=None):
     if precision is None:
         precision = "bf16" if cfg.dtype == "bf16" else "f64"
     stages = [Stage(cfg.stages[s], params[s], cfg.lr, cfg.momentum, M, N, precision) for s in range(K)]
+    if momentum is not None:
+        for st, bufs in zip(stages, momentum):
+            st.bufs = [{k: np.array(v, dtype=np.float64) for k, v in b.items()} for b in bufs]
+    base = [0] * K if versions is None else [int(v) for v in versions]
+    for st, v in zip(stages, base):
+        st.version = v
     sim = S.simulate(K, N, len(batches))
     fwd_out = {}
     bwd_out = {}
     micro_losses = {}
     for (t, s, kind, b, j, sv, nv) in sim["ops"]:
         st = stages[s]
-        assert st.version == sv, "worker version differs from the simulated log"
+        assert st.version - base[s] == sv, "worker version differs from the simulated log"
         if kind == S.FWD:
             x_all, y_all = batches[b - 1]
             if s == 0:

@@ -43,6 +43,7 @@ EXPORTS = {
     "tmps_stage_sync_params": (C.c_int, [C.c_void_p, C.c_void_p]),
     "tmps_stage_output_ptr": (C.c_void_p, [C.c_void_p, C.c_int]),
     "tmps_stage_version": (C.c_long, [C.c_void_p]),
+    "tmps_stage_set_version": (C.c_int, [C.c_void_p, C.c_long]),
     "tmps_forward_micro": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_backward": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_update": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -296,6 +297,28 @@ class Stage:
     def version(self):
         return lib().tmps_stage_version(self.handle)
 
+    # ---- stage-wise checkpoints (section "Checkpointing") ----
+    def save_checkpoint(self, directory, stage_index, epoch):
+        """Write this stage's master parameters, momentum and version to its own file (no other stage is involved)."""
+        from . import checkpoint
+        self.torch.cuda.synchronize(self.device)
+        return checkpoint.write_stage(directory, stage_index, epoch, self.version(), self._flat(0, 0).cpu().numpy(),
+                                      self._flat(1, 0).cpu().numpy())
+
+    def load_checkpoint(self, directory, stage_index, epoch, stream=None):
+        from . import checkpoint
+        torch = self.torch
+        ck = checkpoint.read_stage(directory, stage_index, epoch)
+        if ck["params"].size != self.P:
+            raise checkpoint.CheckpointError("stage %d: %d parameters in the file, %d in the stage"
+                                             % (stage_index, ck["params"].size, self.P))
+        self._flat(0, 0).copy_(torch.from_numpy(ck["params"]))
+        self._flat(1, 0).copy_(torch.from_numpy(ck["momentum"]))
+        torch.cuda.synchronize(self.device)
+        _check(lib().tmps_stage_sync_params(self.handle, C.c_void_p(self._stream(stream))))
+        _check(lib().tmps_stage_set_version(self.handle, int(ck["version"])))
+        torch.cuda.synchronize(self.device)
+
     def output_ptr(self, slot):
         return lib().tmps_stage_output_ptr(self.handle, slot)
 
@@ -390,3 +413,17 @@ class Pipeline:
 
     def get_params(self, s):
         return self.stages[s].get_params()
+
+    def save_checkpoint(self, directory, epoch):
+        """Every stage writes its own file for `epoch` (call between runs: the pipeline is drained)."""
+        return [st.save_checkpoint(directory, s, epoch) for s, st in enumerate(self.stages)]
+
+    def resume(self, directory):
+        """Load the latest epoch whose checkpoints of ALL stages are intact; returns that epoch, or None."""
+        from . import checkpoint
+        epoch = checkpoint.last_complete_epoch(directory, self.cfg.K)
+        if epoch is None:
+            return None
+        for s, st in enumerate(self.stages):
+            st.load_checkpoint(directory, s, epoch)
+        return epoch

@@ -350,6 +350,15 @@ extern "C" int64_t tmps_stage_input_elems(const tmps_stage* stage) { return stag
 extern "C" int64_t tmps_stage_output_elems(const tmps_stage* stage) { return stage ? stage->out_elems : 0; }
 extern "C" long tmps_stage_version(const tmps_stage* stage) { return stage ? stage->version : -1; }
 
+extern "C" int tmps_stage_set_version(tmps_stage* stage, long version) {
+    if (!stage) return fail(TMPS_EINVAL, "stage is null");
+    if (version < 0) return fail(TMPS_EINVAL, "version %ld is negative", version);
+    for (char u : stage->slot_used)
+        if (u) return fail(TMPS_ESLOT, "a stash slot is in use: the version is restored between mini-batches");
+    stage->version = version;
+    return TMPS_OK;
+}
+
 extern "C" int tmps_stage_sync_params(tmps_stage* stage, void* hip_stream) {
     if (!stage) return fail(TMPS_EINVAL, "stage is null");
     if (stage->wcopy) TMPS_HIP(cast_f32_to_bf16(stage->master, stage->wcopy, stage->P, (hipStream_t)hip_stream));

@@ -131,3 +131,46 @@ def test_run_rejects_small_stash_and_mismatched_stages():
     with pytest.raises(TmpsError) as e:
         _check(lib().tmps_schedule_run(handles, 2, 4, 2, x.data_ptr(), y.data_ptr(), streams, losses.data_ptr(), None))
     assert e.value.code == -3
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp_f32", "tiny_transformer_bf16"])
+def test_resume_from_stage_checkpoints(name, tmp_path):
+    """Section "Checkpointing": a pipeline restored from the files every stage wrote at the end of an epoch goes on
+    exactly (bit for bit) as the pipeline that wrote them, and a damaged file of one stage pulls all stages back."""
+    import torch
+    from paper_2410_14312_amd import Pipeline, checkpoint
+    cfg = get_config(name)
+    params = init_params(cfg, bias_std=0.05)
+    batches = [make_batch(cfg, i) for i in range(9)]
+    d = str(tmp_path)
+    a = Pipeline(cfg, params)
+    a.run(batches[:3]); a.save_checkpoint(d, 1)
+    a.run(batches[3:6]); a.save_checkpoint(d, 2)
+    losses_a, _ = a.run(batches[6:])
+    # resume in a new pipeline from epoch 2 and train the third epoch
+    b = Pipeline(cfg, params)
+    assert b.resume(d) == 2
+    assert [st.version() for st in b.stages] == [6] * cfg.K
+    losses_b, log_b = b.run(batches[6:])
+    assert losses_b == losses_a
+    assert [st.version() for st in b.stages] == [9] * cfg.K
+    assert int(log_b[:, 5].min()) == 6       # the version log goes on from the restored counters
+    for s in range(cfg.K):
+        for pa, pb in zip(a.get_params(s), b.get_params(s)):
+            for k in pa:
+                assert np.array_equal(pa[k], pb[k]), (s, k)
+        for ma, mb in zip(a.stages[s].get_momentum(), b.stages[s].get_momentum()):
+            for k in ma:
+                assert np.array_equal(ma[k], mb[k]), (s, k)
+    # stage 1's epoch-2 file is cut short: every stage goes back to epoch 1
+    path = checkpoint.stage_file(d, cfg.K - 1, 2)
+    data = open(path, "rb").read()
+    open(path, "wb").write(data[:len(data) // 2])
+    c = Pipeline(cfg, params)
+    assert c.resume(d) == 1
+    assert [st.version() for st in c.stages] == [3] * cfg.K
+    c.run(batches[3:6])
+    losses_c, _ = c.run(batches[6:])
+    assert losses_c == losses_a
+    # nothing to resume from
+    assert Pipeline(cfg, params).resume(str(tmp_path / "empty")) is None
