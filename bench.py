@@ -136,6 +136,8 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=0, help="mini-batches the oracle is timed on (0: about 15 s worth)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy kernel (reference for scaling HBM byte counters)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short throughput runs of the other benchmark configurations (reported under other_workloads)")
     ap.add_argument("--hw-queues", type=int, default=8,
                     help="hardware queues HIP may use (GPU_MAX_HW_QUEUES, read when HIP starts): the K stage streams and "
                          "the default stream share the runtime's default of 4, so two stages would take turns on one queue")
@@ -283,6 +285,38 @@ def main():
             cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
                    "sample": "%d mini-batches of the same workload through the numpy fp64 oracle pipeline (%.1f s)" % (n_cpu, dc)}
 
+    # The other benchmark configurations, for context: the same measurement (resident inputs, K streams, wall time
+    # between device synchronisations) on a short run each, without per-kernel timing.
+    others = []
+    if not args.no_other_workloads and not args.one_stream and not args.calibrate_copy:
+        del pipe, xw, yw, lw, xs, ys, ls
+        torch.cuda.empty_cache()
+        for name in ("tiny_mlp_f32", "mlp4x1024_bf16", "vgg16_bf16", "resnet50_bf16", "gpt2_small_bf16"):
+            if name == cfg.name:
+                continue
+            ocfg = get_config(name)
+            opipe_ = T.Pipeline(ocfg, init_params(ocfg))
+            n = 20 if name in ("resnet50_bf16", "gpt2_small_bf16") else 60
+            ob = [make_batch(ocfg, i) for i in range(min(n, 8))]
+            ox, oy = opipe_.upload([ob[i % len(ob)] for i in range(n)])
+            ol = torch.zeros(n, dtype=torch.float32, device=opipe_.device)
+            torch.cuda.synchronize()
+            opipe_.run_device(ox, oy, n, ol, want_log=False)   # warm-up pass
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            opipe_.run_device(ox, oy, n, ol, want_log=False)
+            torch.cuda.synchronize()
+            od = time.perf_counter() - t1
+            assert np.all(np.isfinite(ol.cpu().numpy())), "non-finite loss in %s" % name
+            ow = algorithmic_work(ocfg)
+            others.append({"workload": name, "value": ocfg.M * n / od, "unit": "samples/s", "ms_per_step": 1e3 * od / n,
+                           "steps": n, "mini_batch": ocfg.M, "micro_batches": ocfg.N, "stages": ocfg.K,
+                           "dtype": "bf16" if ocfg.dtype == "bf16" else "f32",
+                           "mfma_frac_of_bf16_peak_end_to_end": (sum(v[1] for v in ow.values()) / (od / n) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+                           if ocfg.dtype == "bf16" else None})
+            del opipe_, ox, oy, ol
+            torch.cuda.empty_cache()
+
     out = {
         "metric": "training samples/sec (all K stages, nF1B) on 1 MI355X",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -293,7 +327,7 @@ def main():
                    "streams": 1 if args.one_stream else cfg.K, "hw_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
         "mfma_frac_of_bf16_peak_end_to_end": flops_step / (dt / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "kernels_one_stream": kernels_alone,
-        "final_loss": float(losses[-1]),
+        "final_loss": float(losses[-1]), "other_workloads": others,
     }
     print(json.dumps(out))
 
