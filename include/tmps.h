@@ -173,6 +173,31 @@ int tmps_forward_micro(tmps_stage* stage, int slot, const void* x, void* y, cons
 int tmps_backward(tmps_stage* stage, const int* slots, int n_slots, const void* dy, void* dx,
                   void* hip_stream);
 
+/* ---- vertical weight stashing (Methodology, first paragraph; "GPU Memory Overhead") ----
+ *
+ * The paper keeps every forward pass on one weight version across the workers: a micro-batch is tagged with the
+ * number of whole-network updates completed when it enters worker 1, and a later worker, which may have applied newer
+ * updates by the time the micro-batch reaches it, runs it on ITS weights after that many updates, which it keeps aside
+ * until no forward pass needs them.  Backward passes read the live weights either way.  The calls above implement the
+ * in-place reading (every task reads the live weights, nothing is kept); these add the paper's own policy:
+ *
+ * tmps_stage_set_shadow hands the stage a caller-owned device region (256-byte aligned) for n_versions copies of its
+ * `params` region (param_bytes of tmps_stage_bytes each); from then on tmps_update copies the superseded parameters
+ * there (one device-to-device copy per update) before it changes them.  n_versions = 0 switches it off.
+ * tmps_forward_micro_at is tmps_forward_micro on the weights as they were after `version` updates: the live ones when
+ * version is the stage's current version, a kept copy otherwise (TMPS_EINVAL if that version is not kept).
+ * tmps_schedule_shadow_versions (host only) tells how many older versions worker `stage` needs under the schedule of
+ * W workers and N micro-batches (0 for worker 0, 1 per later worker at W = 4, N = 8).
+ * tmps_schedule_run_vsync is tmps_schedule_run with every forward pass on the version it is tagged with (field 6 of
+ * the version log, counted from the stages' versions at the start of the run); TMPS_ESTASH if a stage keeps too few. */
+int tmps_stage_set_shadow(tmps_stage* stage, void* shadow, size_t bytes, int n_versions);
+int tmps_forward_micro_at(tmps_stage* stage, long version, int slot, const void* x, void* y, const int32_t* labels,
+                          float* loss_out, void* hip_stream);
+int tmps_schedule_shadow_versions(int W, int N, int stage);
+int tmps_schedule_run_vsync(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
+                            const int32_t* labels, void** hip_streams, float* losses_out,
+                            int32_t* version_log_out);
+
 /* In-place update (the update rule for TiMePReSt, with momentum): buf <- mu*buf + g,
  * w <- w - lr*buf on the fp32 master values, refreshes the bf16 working copy, version += 1. */
 int tmps_update(tmps_stage* stage, void* hip_stream);

@@ -13,13 +13,19 @@ from . import schedule as S
 from .stage import Stage
 
 
-def run(cfg, params, batches, trace=None, precision=None, momentum=None, versions=None):
+def run(cfg, params, batches, trace=None, precision=None, momentum=None, versions=None, vertical_sync=False):
     """Train `len(batches)` mini-batches.
 
     cfg: a workloads.Config (shape tables only); params: per stage, per layer dicts of arrays;
     batches: list of (x [M, ...], labels [M]).  precision: storage policy ("f64" or "bf16", see
     oracle/precision.py); by default the one the configuration names.  trace: optional dict that receives every task's
     tensors under (kind, b, j, stage) keys.
+    vertical_sync: the paper's own weight policy for forward passes (Methodology, first paragraph: vertical weight
+    stashing keeps a forward pass on one weight version across all workers).  A micro-batch is tagged with the
+    number of whole-network updates completed when it enters worker 1 (the log's last field), and every later worker
+    runs its forward pass on ITS weights after that many updates, which it keeps until no forward pass needs them
+    ("GPU Memory Overhead").  Backward passes read the live weights either way.  False: every task reads the live
+    weights of its worker (no stashed versions).
     momentum, versions: state to resume from (section "Checkpointing": a run restarts from the parameters every
     stage saved at the end of an epoch; with momentum the buffers and the update counters belong to that state):
     per stage, per layer dicts like params, and per stage update counts.  The version log of a resumed run counts
@@ -39,6 +45,9 @@ def run(cfg, params, batches, trace=None, precision=None, momentum=None, version
     for st, v in zip(stages, base):
         st.version = v
     sim = S.simulate(K, N, len(batches))
+    if vertical_sync:
+        for s_, st in enumerate(stages):
+            st.keep_versions = max([sv - nv for (t, w, kind, b, j, sv, nv) in sim["ops"] if kind == S.FWD and w == s_] + [0])
     fwd_out = {}
     bwd_out = {}
     micro_losses = {}
@@ -51,12 +60,13 @@ def run(cfg, params, batches, trace=None, precision=None, momentum=None, version
                 x = x_all[j * micro:(j + 1) * micro]
             else:
                 x = fwd_out.pop((b, j, s - 1))
+            ver = base[s] + nv if vertical_sync else None
             if s == K - 1:
-                logits, loss = st.forward_micro((b, j), x, y_all[j * micro:(j + 1) * micro])
+                logits, loss = st.forward_micro((b, j), x, y_all[j * micro:(j + 1) * micro], version=ver)
                 micro_losses.setdefault(b, []).append(loss)
                 out = logits
             else:
-                out = st.forward_micro((b, j), x)
+                out = st.forward_micro((b, j), x, version=ver)
                 fwd_out[(b, j, s)] = out
             if trace is not None:
                 trace[("F", b, j, s)] = np.array(out)

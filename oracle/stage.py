@@ -32,11 +32,15 @@ class Stage:
         self.is_last = layer_specs[-1]["kind"] == "softmax_ce"
         self.stash = {}
         self.version = 0
+        self.keep_versions = 0   # older weight versions kept for vertical weight stashing
+        self.history = {}        # version -> parameters after that many updates
         self.q = storage_rounding(precision)
 
     # -- forward of one micro-batch -------------------------------------------------------
-    def forward_micro(self, slot, x, labels=None):
-        """Returns the stage output; on the last stage returns (logits, micro-batch mean loss)."""
+    def forward_micro(self, slot, x, labels=None, version=None):
+        """Returns the stage output; on the last stage returns (logits, micro-batch mean loss).
+        version: vertical weight stashing (Methodology, first paragraph; "GPU Memory Overhead"): run the layers on
+        this stage's weights as they were after `version` updates (kept by keep_versions) instead of the live ones."""
         if slot in self.stash:
             raise RuntimeError("stash slot %r is in use" % (slot,))
         caches = []
@@ -51,7 +55,8 @@ class Stage:
             """Result of the layer k positions before layer li; one before the first layer is the stage input."""
             return outs[li - k] if li - k >= 0 else x_in
 
-        for li, (spec, p) in enumerate(zip(self.specs, self.params)):
+        weights = self.params if version is None or version == self.version else self.history[version]
+        for li, (spec, p) in enumerate(zip(self.specs, weights)):
             k = spec["kind"]
             if k == "conv" and spec.get("src", 1) != 1:
                 a = earlier(li, spec["src"])
@@ -173,6 +178,11 @@ class Stage:
 
     # -- in-place update -------------------------------------------------------------------
     def update(self):
+        if self.keep_versions:
+            # the superseded weights stay until no forward pass needs them ("GPU Memory Overhead")
+            self.history[self.version] = [{k: v.copy() for k, v in p.items()} for p in self.params]
+            for old in [v for v in self.history if v < self.version + 1 - self.keep_versions]:
+                del self.history[old]
         for p, buf, g in zip(self.params, self.bufs, self.grads):
             if g is None:
                 continue

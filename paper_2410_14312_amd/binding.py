@@ -44,6 +44,10 @@ EXPORTS = {
     "tmps_stage_output_ptr": (C.c_void_p, [C.c_void_p, C.c_int]),
     "tmps_stage_version": (C.c_long, [C.c_void_p]),
     "tmps_stage_set_version": (C.c_int, [C.c_void_p, C.c_long]),
+    "tmps_stage_set_shadow": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]),
+    "tmps_forward_micro_at": (C.c_int, [C.c_void_p, C.c_long, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]),
+    "tmps_schedule_shadow_versions": (C.c_int, [C.c_int, C.c_int, C.c_int]),
     "tmps_forward_micro": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_backward": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_update": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -53,6 +57,8 @@ EXPORTS = {
     "tmps_version_diff_simulated": (C.c_int, [C.c_int, C.c_int]),
     "tmps_schedule_run": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                     C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_int32)]),
+    "tmps_schedule_run_vsync": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                          C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_int32)]),
     "tmps_streams_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_int]),
     "tmps_streams_destroy": (C.c_int, [C.POINTER(C.c_void_p), C.c_int]),
     "tmps_profile_enable": (C.c_int, [C.c_int]),
@@ -97,6 +103,10 @@ def schedule_plan(W, N, n_minibatches):
 
 def schedule_stash_groups(W, N, stage):
     return _check(lib().tmps_schedule_stash_groups(W, N, stage))
+
+
+def schedule_shadow_versions(W, N, stage):
+    return _check(lib().tmps_schedule_shadow_versions(W, N, stage))
 
 
 def version_diff_formula(W, N):
@@ -297,6 +307,20 @@ class Stage:
     def version(self):
         return lib().tmps_stage_version(self.handle)
 
+    def set_shadow(self, n_versions):
+        """Vertical weight stashing: keep the parameters of the last n_versions updates (a device region of its own)."""
+        torch = self.torch
+        one = self.regions[0].numel()
+        self.shadow = torch.zeros(max(one * n_versions, 256), dtype=torch.uint8, device=self.device) if n_versions else None
+        _check(lib().tmps_stage_set_shadow(self.handle, C.c_void_p(self.shadow.data_ptr()) if n_versions else None,
+                                           one * n_versions, n_versions))
+
+    def forward_micro_at(self, version, slot, x, y=None, labels=None, loss_out=None, stream=None):
+        _check(lib().tmps_forward_micro_at(
+            self.handle, version, slot, C.c_void_p(x.data_ptr()), C.c_void_p(y.data_ptr()) if y is not None else None,
+            C.c_void_p(labels.data_ptr()) if labels is not None else None,
+            C.c_void_p(loss_out.data_ptr()) if loss_out is not None else None, C.c_void_p(self._stream(stream))))
+
     # ---- stage-wise checkpoints (section "Checkpointing") ----
     def save_checkpoint(self, directory, stage_index, epoch):
         """Write this stage's master parameters, momentum and version to its own file (no other stage is involved)."""
@@ -342,10 +366,13 @@ class Stage:
 class Pipeline:
     """K stages of a workloads.Config on K streams of one GPU, run in nF1B order by tmps_schedule_run."""
 
-    def __init__(self, cfg, params, device="cuda:0", extra_groups=0, one_stream=False):
+    def __init__(self, cfg, params, device="cuda:0", extra_groups=0, one_stream=False, vertical_sync=False):
+        """vertical_sync: forward passes read the weight version they are tagged with (the paper's vertical weight
+        stashing; every stage keeps the older versions the schedule needs) instead of the live weights."""
         import torch
         self.torch = torch
         self.cfg = cfg
+        self.vertical_sync = bool(vertical_sync)
         self.device = torch.device(device)
         K, N = cfg.K, cfg.N
         self.stages = []
@@ -354,6 +381,8 @@ class Pipeline:
             st = Stage(cfg.stages[s], cfg.dtype, cfg.micro, N, groups * N, cfg.lr, cfg.momentum,
                        borrow_input=True, device=device)
             st.set_params(params[s])
+            if self.vertical_sync:
+                st.set_shadow(schedule_shadow_versions(K, N, s))
             self.stages.append(st)
         # K streams created back to back by the library, so that they land on distinct hardware queues (streams from
         # torch's pool may share one, and then two workers run one after the other); wrapped for torch.
@@ -395,9 +424,9 @@ class Pipeline:
             n_tasks = _check(lib().tmps_schedule_plan(K, N, n_minibatches, None, 0))
             log = (C.c_int32 * (7 * n_tasks))()
             logp = log
-        _check(lib().tmps_schedule_run(handles, K, N, n_minibatches, C.c_void_p(x_dev.data_ptr()),
-                                       C.c_void_p(y_dev.data_ptr()), streams,
-                                       C.c_void_p(losses_dev.data_ptr()), logp))
+        run = lib().tmps_schedule_run_vsync if self.vertical_sync else lib().tmps_schedule_run
+        _check(run(handles, K, N, n_minibatches, C.c_void_p(x_dev.data_ptr()), C.c_void_p(y_dev.data_ptr()), streams,
+                   C.c_void_p(losses_dev.data_ptr()), logp))
         if log is None:
             return None
         return np.frombuffer(log, dtype=np.int32).reshape(-1, 7).copy()

@@ -37,6 +37,8 @@ struct EventPool {
 };
 
 struct RunCtx {
+    bool vsync = false;              // forward passes read the weight version they are tagged with
+    std::vector<long> base_version;  // every stage's version when the run started
     tmps_stage** stages;
     int K, N, M, mb, n_minibatches;
     const void* inputs;
@@ -103,7 +105,11 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
             if ((rc = c.wait_for(c.fwd_ev(k.stage - 1, q), s)) != TMPS_OK) return rc;
         }
         const int32_t* lab = st->cfg.is_last ? c.labels + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->label_rps : nullptr;
-        if ((rc = tmps_forward_micro(st, slot, x, nullptr, lab, nullptr, s)) != TMPS_OK) return rc;
+        if (c.vsync)
+            rc = tmps_forward_micro_at(st, c.base_version[k.stage] + k.net_version, slot, x, nullptr, lab, nullptr, s);
+        else
+            rc = tmps_forward_micro(st, slot, x, nullptr, lab, nullptr, s);
+        if (rc != TMPS_OK) return rc;
         if (k.stage < K - 1 && (rc = c.record(c.fwd_ev(k.stage, q), s)) != TMPS_OK) return rc;
         if (st->cfg.is_last && k.j == N - 1 && c.losses_out) {
             ProfileScope scope(kcReduce, s);
@@ -133,9 +139,8 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
 
 }  // namespace
 
-extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
-                                 const int32_t* labels, void** hip_streams, float* losses_out,
-                                 int32_t* version_log_out) {
+static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs, const int32_t* labels,
+                        void** hip_streams, float* losses_out, int32_t* version_log_out, bool vsync) {
     if (!stages || !hip_streams || !inputs || !labels) return fail(TMPS_EINVAL, "null argument");
     if (K < 1 || N < 1 || n_minibatches < 1) return fail(TMPS_EINVAL, "K, N and n_minibatches must be positive");
     const int mb = stages[0] ? stages[0]->cfg.micro_batch : 0;
@@ -155,6 +160,9 @@ extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_miniba
             return fail(TMPS_ESTASH, "stage %d can stash %d mini-batches, the schedule needs %d", s, st->cfg.max_stash / N, need);
         for (char u : st->slot_used)
             if (u) return fail(TMPS_ESLOT, "stage %d has a stash slot in use", s);
+        if (vsync && st->shadow_n < shadow_versions(K, N, s))
+            return fail(TMPS_ESTASH, "stage %d keeps %d older weight versions, vertical weight stashing needs %d", s,
+                        st->shadow_n, shadow_versions(K, N, s));
     }
     const std::vector<Task> tasks = plan_nf1b(K, N, n_minibatches);
 
@@ -162,6 +170,8 @@ extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_miniba
     c.stages = stages; c.K = K; c.N = N; c.mb = mb; c.M = mb * N; c.n_minibatches = n_minibatches;
     c.inputs = inputs; c.labels = labels; c.streams = hip_streams; c.losses_out = losses_out;
     c.log = version_log_out;
+    c.vsync = vsync;
+    for (int s = 0; s < K; ++s) c.base_version.push_back(stages[s]->version);
     c.asz = stages[0]->asz;
     c.total_micro = (size_t)n_minibatches * N;
     c.n_fwd_ev = (size_t)(K - 1) * c.total_micro;
@@ -221,6 +231,18 @@ extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_miniba
                 std::chrono::duration<double, std::milli>(t2 - t0).count());
     }
     return TMPS_OK;
+}
+
+extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
+                                 const int32_t* labels, void** hip_streams, float* losses_out,
+                                 int32_t* version_log_out) {
+    return schedule_run(stages, K, N, n_minibatches, inputs, labels, hip_streams, losses_out, version_log_out, false);
+}
+
+extern "C" int tmps_schedule_run_vsync(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
+                                       const int32_t* labels, void** hip_streams, float* losses_out,
+                                       int32_t* version_log_out) {
+    return schedule_run(stages, K, N, n_minibatches, inputs, labels, hip_streams, losses_out, version_log_out, true);
 }
 
 extern "C" int tmps_streams_create(void** out, int n) {

@@ -77,6 +77,14 @@ int stash_groups(int W, int N, int stage) {
     return need;
 }
 
+int shadow_versions(int W, int N, int stage) {
+    const int n = 4 * W + 4 * N + 8;
+    int need = 0;
+    for (const Task& k : plan_nf1b(W, N, n))
+        if (k.kind == kFwd && k.stage == stage) need = std::max(need, (int)(k.stage_version - k.net_version));
+    return need;
+}
+
 int version_diff_simulated(int W, int N) {
     const int n = 4 * W + 4 * N + 8;
     std::vector<Task> tasks = plan_nf1b(W, N, n);
@@ -103,6 +111,11 @@ extern "C" int tmps_schedule_plan(int W, int N, int n_minibatches, int32_t* ops_
         }
     }
     return (int)tasks.size();
+}
+
+extern "C" int tmps_schedule_shadow_versions(int W, int N, int stage) {
+    if (W < 1 || N < 1 || stage < 0 || stage >= W) return fail(TMPS_EINVAL, "W, N must be positive and 0 <= stage < W");
+    return shadow_versions(W, N, stage);
 }
 
 extern "C" int tmps_schedule_stash_groups(int W, int N, int stage) {

@@ -16,5 +16,7 @@ std::vector<Task> plan_nf1b(int W, int N, int n_minibatches);
 // Largest number of mini-batches simultaneously between first forward and backward on `stage`.
 int stash_groups(int W, int N, int stage);
 int version_diff_simulated(int W, int N);
+// Older weight versions `stage` must keep so that every forward pass finds the version it is tagged with.
+int shadow_versions(int W, int N, int stage);
 
 }  // namespace tmps

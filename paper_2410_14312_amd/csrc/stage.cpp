@@ -350,12 +350,33 @@ extern "C" int64_t tmps_stage_input_elems(const tmps_stage* stage) { return stag
 extern "C" int64_t tmps_stage_output_elems(const tmps_stage* stage) { return stage ? stage->out_elems : 0; }
 extern "C" long tmps_stage_version(const tmps_stage* stage) { return stage ? stage->version : -1; }
 
+static size_t params_region_bytes(const tmps_stage& st) {
+    return align_up((size_t)st.P * (st.cfg.dtype == TMPS_BF16_F32MASTER ? 6 : 4), 256);
+}
+
+extern "C" int tmps_stage_set_shadow(tmps_stage* stage, void* shadow, size_t bytes, int n_versions) {
+    if (!stage) return fail(TMPS_EINVAL, "stage is null");
+    if (n_versions < 0 || (n_versions > 0 && !shadow)) return fail(TMPS_EINVAL, "shadow region is null or n_versions negative");
+    if (reinterpret_cast<uintptr_t>(shadow) & 255) return fail(TMPS_EINVAL, "the shadow region must be 256-byte aligned");
+    const size_t one = params_region_bytes(*stage);
+    if (bytes < one * (size_t)n_versions)
+        return fail(TMPS_EINVAL, "%d versions of %zu bytes need %zu bytes, got %zu", n_versions, one, one * (size_t)n_versions, bytes);
+    for (char u : stage->slot_used)
+        if (u) return fail(TMPS_ESLOT, "a stash slot is in use");
+    stage->shadow = n_versions ? (char*)shadow : nullptr;
+    stage->shadow_n = n_versions;
+    stage->param_bytes = one;
+    stage->shadow_ver.assign((size_t)n_versions, -1L);
+    return TMPS_OK;
+}
+
 extern "C" int tmps_stage_set_version(tmps_stage* stage, long version) {
     if (!stage) return fail(TMPS_EINVAL, "stage is null");
     if (version < 0) return fail(TMPS_EINVAL, "version %ld is negative", version);
     for (char u : stage->slot_used)
         if (u) return fail(TMPS_ESLOT, "a stash slot is in use: the version is restored between mini-batches");
     stage->version = version;
+    std::fill(stage->shadow_ver.begin(), stage->shadow_ver.end(), -1L);   // kept copies belong to the old numbering
     return TMPS_OK;
 }
 
@@ -753,7 +774,37 @@ extern "C" int tmps_update(tmps_stage* st, void* hip_stream) {
         // an empty bracket: what a pair of timing events costs by itself on this stream
         ProfileScope empty(kcEventPair, s);
     }
+    if (st->shadow_n > 0) {
+        // vertical weight stashing: the version about to be superseded is kept for the forward passes tagged with it
+        const int slot = (int)(st->version % st->shadow_n);
+        TMPS_RUN(kcCopy, s, hipMemcpyAsync(st->shadow + (size_t)slot * st->param_bytes, st->params, st->param_bytes,
+                                           hipMemcpyDeviceToDevice, s));
+        st->shadow_ver[slot] = st->version;
+    }
     TMPS_RUN(kcUpdate, s, sgd_momentum(st->master, st->mom, st->grad, st->wcopy, st->P, st->cfg.lr, st->cfg.momentum, s));
     ++st->version;
     return TMPS_OK;
+}
+
+extern "C" int tmps_forward_micro_at(tmps_stage* st, long version, int slot, const void* x, void* y, const int32_t* labels,
+                                     float* loss_out, void* hip_stream) {
+    if (!st) return fail(TMPS_EINVAL, "stage is null");
+    if (version == st->version) return tmps_forward_micro(st, slot, x, y, labels, loss_out, hip_stream);
+    int found = -1;
+    for (int k = 0; k < st->shadow_n; ++k)
+        if (st->shadow_ver[k] == version) found = k;
+    if (found < 0)
+        return fail(TMPS_EINVAL, "weights after %ld updates are not kept (the stage is at %ld and keeps %d older versions)",
+                    version, st->version, st->shadow_n);
+    // The kernels take their weight pointers when they are launched: point the stage at the kept copy for the
+    // duration of this call.  (Calls on one stage come from one host thread at a time.)
+    float* const live_master = st->master;
+    void* const live_wcopy = st->wcopy;
+    char* base = st->shadow + (size_t)found * st->param_bytes;
+    st->master = reinterpret_cast<float*>(base);
+    if (live_wcopy) st->wcopy = base + (size_t)st->P * 4;
+    const int rc = tmps_forward_micro(st, slot, x, y, labels, loss_out, hip_stream);
+    st->master = live_master;
+    st->wcopy = live_wcopy;
+    return rc;
 }

@@ -49,6 +49,11 @@ struct tmps_stage {
     std::vector<char> slot_used;
     std::vector<const void*> slot_x;
     long version = 0;
+    // vertical weight stashing: copies of the `params` region as it was after earlier updates
+    char* shadow = nullptr;
+    int shadow_n = 0;                 // copies the caller's region holds
+    size_t param_bytes = 0;           // size of `params` (one copy)
+    std::vector<long> shadow_ver;     // version each copy holds (-1: none)
 
     int M() const { return cfg.micro_batch * cfg.n_micro; }
     // weights the contractions read

@@ -22,14 +22,14 @@ from workloads.configs import conv, linear, maxpool, softmax_ce
 pytestmark = pytest.mark.gpu
 
 
-def _compare(cfg, n_steps, loss_tol=None, bias_std=0.0):
+def _compare(cfg, n_steps, loss_tol=None, bias_std=0.0, vertical_sync=False):
     import torch
     from paper_2410_14312_amd import Pipeline
     tol = TOL[cfg.dtype]
     params = init_params(cfg, bias_std=bias_std)
     batches = [make_batch(cfg, i) for i in range(n_steps)]
-    ref = pipeline.run(cfg, params, batches)
-    pipe = Pipeline(cfg, params)
+    ref = pipeline.run(cfg, params, batches, vertical_sync=vertical_sync)
+    pipe = Pipeline(cfg, params, vertical_sync=vertical_sync)
     losses, log = pipe.run(batches)
     # integer bookkeeping: bit-exact
     assert np.array_equal(log, np.array(ref["ops"], dtype=np.int32))
@@ -174,3 +174,39 @@ def test_resume_from_stage_checkpoints(name, tmp_path):
     assert losses_c == losses_a
     # nothing to resume from
     assert Pipeline(cfg, params).resume(str(tmp_path / "empty")) is None
+
+
+def test_vertical_weight_stashing_on_the_tiny_mlp():
+    """The paper's own weight policy for forward passes (vertical weight stashing): parity with the oracle in that
+    mode, and a different trajectory from the in-place mode once a later worker runs ahead of worker 1."""
+    cfg = get_config("tiny_mlp_f32")
+    vs = _compare(cfg, 12, vertical_sync=True)
+    ip = _compare(cfg, 12)
+    assert vs[0] == ip[0] and vs != ip
+
+
+@pytest.mark.parametrize("name", ["tiny_transformer_f32", "tiny_transformer_bf16", "tiny_resnet_bf16"])
+def test_vertical_weight_stashing_small_networks(name):
+    _compare(get_config(name), 5, bias_std=0.05, vertical_sync=True)
+
+
+def test_vertical_weight_stashing_deep_pipeline_and_errors():
+    # W=4, N=2: the last worker runs up to 3 versions ahead of the tag
+    from paper_2410_14312_amd import Pipeline, TmpsError, schedule_shadow_versions
+    layers = [linear(32, 32, True), linear(32, 32, True), linear(32, 32, True), linear(32, 10, False), softmax_ce(10)]
+    cfg = Config(name="t", dtype="f32", M=8, N=2, stages=[layers[:1], layers[1:2], layers[2:3], layers[3:]],
+                 in_shape=(32,), classes=10, seed=3)
+    assert [schedule_shadow_versions(4, 2, s) for s in range(4)] == [0, 1, 2, 3]
+    assert [schedule_shadow_versions(4, 8, s) for s in range(4)] == [0, 1, 1, 1]
+    _compare(cfg, 10, bias_std=0.05, vertical_sync=True)
+    # a stage that keeps too few versions is refused before anything runs
+    pipe = Pipeline(cfg, init_params(cfg, bias_std=0.05), vertical_sync=True)
+    pipe.stages[3].set_shadow(1)
+    with pytest.raises(TmpsError):
+        pipe.run([make_batch(cfg, i) for i in range(3)])
+    # a version that is not kept is an error of the versioned forward call
+    import torch
+    st = pipe.stages[0]
+    x = st.prepare_input(make_batch(cfg, 0)[0][:cfg.micro])
+    with pytest.raises(TmpsError):
+        st.forward_micro_at(5, 0, x)
