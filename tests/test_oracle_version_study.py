@@ -34,11 +34,11 @@ def cut(W):
     return stages
 
 
-def train(W, steps=80, N=2):
+def train(W, steps=80, N=2, vertical_sync=False):
     cfg = Config(name="study", dtype="f32", M=8, N=N, stages=cut(W), in_shape=(32,), classes=10, seed=11, lr=0.005)
     params = init_params(cfg, bias_std=0.05)
     batches = [make_batch(cfg, i % 8) for i in range(steps)]   # 8 distinct mini-batches, revisited
-    return cfg, pipeline.run(cfg, params, batches)
+    return cfg, pipeline.run(cfg, params, batches, vertical_sync=vertical_sync)
 
 
 RUNS = {}
@@ -94,3 +94,15 @@ def test_training_converges_for_every_v_and_drifts_with_depth():
     d = {W: float(np.abs(losses[W] - losses[1]).mean()) for W in (3, 4, 7)}
     assert d[3] < d[7] and d[4] < d[7]
     assert all(losses[1][-8:].mean() < losses[W][-8:].mean() for W in (3, 4, 7))
+
+
+def test_in_place_weights_stay_closer_to_sequential_sgd_than_vertical_weight_stashing():
+    # The same cuts under the paper's vertical weight stashing (forward passes of later workers on the tagged, older
+    # version; backward passes on the live weights): every cut still converges at this learning rate, and drifts
+    # further from sequential SGD than under the in-place policy, the more so the deeper the pipeline.
+    seq = np.array(run_of(1)[1]["losses"])
+    for W in (3, 4, 7):
+        in_place = np.array(run_of(W)[1]["losses"])
+        stashed = np.array(train(W, vertical_sync=True)[1]["losses"])
+        assert stashed[-8:].mean() < 0.7 * stashed[:8].mean()
+        assert np.abs(stashed - seq).mean() > np.abs(in_place - seq).mean()
