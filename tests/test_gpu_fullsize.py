@@ -39,3 +39,38 @@ def test_resnet50_stage_in_fp32(stage):
     from workloads import get_config
     cfg = get_config("resnet50_bf16")
     run_stage_case(cfg.stages[stage], "f32", cfg.micro, 2, seed=503, borrow=True, deep=True)
+
+
+@pytest.mark.parametrize("name", ["gpt2_small_bf16", "resnet50_bf16"])
+def test_benchmark_launch_configuration_at_full_size(name):
+    """The whole pipeline in the configuration bench.py times (K stages on K streams, host threads issuing), at full
+    size, held by properties that need no oracle run of that size: overlapping the stages changes no number (every
+    loss, every parameter and the version log equal those of the same run with all workers on ONE stream, bit for
+    bit, and those of a second K-stream run), the version log is the planned one, every loss is finite and the first
+    loss of the language model is that of an untrained one.  Each stage's step is held to the oracle element by
+    element by the tests above."""
+    import numpy as np
+    from paper_2410_14312_amd import Pipeline, schedule_plan
+    from workloads import get_config, init_params, make_batch
+    cfg = get_config(name)
+    params = init_params(cfg)
+    batches = [make_batch(cfg, i % 2) for i in range(6)]
+    runs = []
+    for one_stream in (False, True, False):
+        pipe = Pipeline(cfg, params, one_stream=one_stream)
+        losses, log = pipe.run(batches)
+        runs.append((losses, log, [pipe.get_params(s) for s in range(cfg.K)]))
+        del pipe
+    plan = np.array(schedule_plan(cfg.K, cfg.N, len(batches)), dtype=np.int32).reshape(-1, 7)
+    for losses, log, weights in runs:
+        assert np.array_equal(log, plan)
+        assert all(np.isfinite(losses))
+    for other in runs[1:]:
+        assert other[0] == runs[0][0]
+        for sa, sb in zip(runs[0][2], other[2]):
+            for pa, pb in zip(sa, sb):
+                for k in pa:
+                    assert np.array_equal(pa[k], pb[k])
+    if name.startswith("gpt2"):
+        # an untrained language model with small initial logits: the loss of the first mini-batch is ln(vocabulary)
+        assert abs(runs[0][0][0] - np.log(cfg.classes)) < 0.1 * np.log(cfg.classes)
