@@ -239,6 +239,33 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
+// 8 consecutive elements fetched now and converted later: the 8-wide epilogues request what they read from memory
+// (a residual source, a mask, the gradient already collected) for several rows at once, BEFORE the results of those
+// rows are ready, so that the memory latency is paid once per group of rows and not once per row.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 u;
+    __device__ __forceinline__ void load(const bf16_t* p) { u = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void get(float (&v)[8]) const {
+        Pack8 pk;
+        pk.u = u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (float)pk.h[e];
+    }
+};
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p) {
+        a = *reinterpret_cast<const float4*>(p);
+        b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void get(float (&v)[8]) const {
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+};
+struct NoCol8 {};
+struct NoRow8 {};
+
 // Host-side test for the 8-wide (16-byte) form of an epilogue: every tensor it touches is 16-byte aligned and a row
 // start keeps that alignment.
 static inline bool epi_al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -292,6 +319,41 @@ template <typename TOut> struct EpiBiasAct {
         if (res) {
             float r[8];
             load8(res + idx, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += r[e];
+        }
+        store8(out + idx, v);
+    }
+    // the same with the column data (bias) and the row data (residual source) requested ahead of time
+    struct Col8 { float b[8]; };
+    struct Row8 { Raw8<TOut> r; };
+    __device__ __forceinline__ Col8 col8(int n) const {
+        Col8 c;
+        if (bias) load8(bias + n, c.b);
+        return c;
+    }
+    __device__ __forceinline__ Row8 row8(int64_t idx, bool ok) const {
+        Row8 p;
+        if (res && ok) p.r.load(res + idx);
+        return p;
+    }
+    __device__ __forceinline__ void at8(const Col8& c, const Row8& p, int64_t idx, float (&v)[8], int) const {
+        if (bias) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += c.b[e];
+        }
+        if (relu == kActRelu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+        } else if (relu == kActGelu) {
+            float d[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) gelu_both(v[e], v[e], d[e]);
+            if (zout) store8(zout + idx, d);
+        }
+        if (res) {
+            float r[8];
+            p.r.get(r);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += r[e];
         }
@@ -364,6 +426,43 @@ template <typename TOut> struct EpiConvAffine {
         }
         store8(yout + idx, v);
     }
+    struct Col8 { float b[8], g[8], s[8]; };
+    struct Row8 { Raw8<TOut> r; };
+    __device__ __forceinline__ Col8 col8(int n) const {
+        Col8 c;
+        load8(gain + n, c.g);
+        load8(shift + n, c.s);
+        if (bias) load8(bias + n, c.b);
+        return c;
+    }
+    __device__ __forceinline__ Row8 row8(int64_t idx, bool ok) const {
+        Row8 p;
+        if (res && ok) p.r.load(res + idx);
+        return p;
+    }
+    __device__ __forceinline__ void at8(const Col8& c, const Row8& p, int64_t idx, float (&v)[8], int) const {
+        if (bias) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += c.b[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = to_f32(from_f32<TOut>(v[e]));
+        store8(out + idx, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = to_f32(from_f32<TOut>(c.g[e] * v[e] + c.s[e]));   // rounded as the stored tensor would be
+        if (aout) store8(aout + idx, v);
+        if (res) {
+            float r[8];
+            p.r.get(r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += r[e];
+        }
+        if (relu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+        }
+        store8(yout + idx, v);
+    }
     __device__ __forceinline__ void operator()(int m, int n, float v, int z) const { at(column(n), (int64_t)m * ld + n, v, z); }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
@@ -409,6 +508,33 @@ template <typename TOut, typename TMask> struct EpiMask {
         }
         store8(out + i, v);
     }
+    typedef NoCol8 Col8;
+    struct Row8 { Raw8<TOut> a; Raw8<TMask> t; };
+    __device__ __forceinline__ Col8 col8(int) const { return Col8{}; }
+    __device__ __forceinline__ Row8 row8(int64_t i, bool ok) const {
+        Row8 p;
+        if (add && ok) p.a.load(add + i);
+        if (mask && ok) p.t.load(mask + i);
+        return p;
+    }
+    __device__ __forceinline__ void at8(const Col8&, const Row8& p, int64_t i, float (&v)[8], int) const {
+        if (add) {
+            float a[8];
+            p.a.get(a);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += a[e];
+        }
+        if (mask) {
+            float t[8];
+            p.t.get(t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (mode == kActGelu) v[e] *= t[e];
+                else if (!(t[e] > 0.0f)) v[e] = 0.0f;
+            }
+        }
+        store8(out + i, v);
+    }
     __device__ __forceinline__ void rowsum(int, float, int) const {}
 };
 
@@ -428,6 +554,13 @@ struct EpiWgrad {
         out[z * slice_stride + idx] = v;
     }
     __device__ __forceinline__ void at8(int, int64_t idx, float (&v)[8], int z) const {
+        store8(out + z * slice_stride + idx, v);
+    }
+    typedef NoCol8 Col8;
+    typedef NoRow8 Row8;
+    __device__ __forceinline__ Col8 col8(int) const { return Col8{}; }
+    __device__ __forceinline__ Row8 row8(int64_t, bool) const { return Row8{}; }
+    __device__ __forceinline__ void at8(const Col8&, const Row8&, int64_t idx, float (&v)[8], int z) const {
         store8(out + z * slice_stride + idx, v);
     }
     __device__ __forceinline__ void rowsum(int m, float v, int z) const {

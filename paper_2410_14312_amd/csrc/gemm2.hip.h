@@ -512,6 +512,16 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
+                // what the epilogue reads from memory for this block's two groups of rows is requested before the
+                // block is transposed, so that the loads fly meanwhile
+                typename Epi::Row8 prow[2];
+                const int pn = n0 + wn * (BN / 2) + j * 32 + (lane & 3) * 8;
+                const typename Epi::Col8 pcol = epi.col8(pn < N ? pn : 0);
+#pragma unroll
+                for (int ps = 0; ps < 2; ++ps) {
+                    const int pm = m0 + wm * (BM / 2) + i * 32 + ps * 16 + (lane >> 2);
+                    prow[ps] = epi.row8((int64_t)pm * ld + pn, pm < M && pn < N);
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + row_in + (r & 3)) * SP + col_in] = acc[0][i][j][r];
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -523,7 +533,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M
                     const float4 hi = *reinterpret_cast<const float4*>(stage + row * SP + (lane & 3) * 8 + 4);
                     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                     const int m = m0 + wm * (BM / 2) + i * 32 + row;
-                    if (m < M && n < N) epi.at8(n, (int64_t)m * ld + n, v, z);
+                    if (m < M && n < N) epi.at8(pcol, prow[ps], (int64_t)m * ld + n, v, z);
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten
             }
@@ -572,6 +582,13 @@ struct EpiPartial {
         part[z * slice_stride + idx] = v;
     }
     __device__ __forceinline__ void at8(int, int64_t idx, float (&v)[8], int z) const {
+        store8(part + z * slice_stride + idx, v);
+    }
+    typedef NoCol8 Col8;
+    typedef NoRow8 Row8;
+    __device__ __forceinline__ Col8 col8(int) const { return Col8{}; }
+    __device__ __forceinline__ Row8 row8(int64_t, bool) const { return Row8{}; }
+    __device__ __forceinline__ void at8(const Col8&, const Row8&, int64_t idx, float (&v)[8], int z) const {
         store8(part + z * slice_stride + idx, v);
     }
     __device__ __forceinline__ void rowsum(int, float, int) const {}

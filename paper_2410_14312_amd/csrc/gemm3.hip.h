@@ -321,6 +321,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int jp = 0; jp < TN / 2; ++jp) {
+                    // what the epilogue reads from memory for the four groups of 8 rows of this block is requested before
+                    // the block is transposed: one memory latency per block, not one per group of rows
+                    const int n = n0 + wn * (BN / WN) + jp * 64 + (lane & 7) * 8;
+                    const typename Epi::Col8 pcol = epi.col8(n < N ? n : 0);
+                    typename Epi::Row8 prow[4];
+#pragma unroll
+                    for (int sp = 0; sp < 4; ++sp) {
+                        const int pm = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
+                        prow[sp] = epi.row8((int64_t)pm * ld + n, pm < M && n < N);
+                    }
                     // accumulator register r of a lane: row 8 (r / 4) + 4 half + r % 4, column lane % 32
 #pragma unroll
                     for (int jj = 0; jj < 2; ++jj)
@@ -330,7 +340,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                             *reinterpret_cast<float*>(stg + base + (r & 3) * 256 + (jj * 32 + col_in) * 4) = acc[i][2 * jp + jj][r];
                         }
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    const int n = n0 + wn * (BN / WN) + jp * 64 + (lane & 7) * 8;
 #pragma unroll
                     for (int sp = 0; sp < 4; ++sp) {
                         // staged row 8 sp + lane / 8 lies in piece 2 sp + half, at row (lane / 8) % 4 of the piece
@@ -339,7 +348,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                         const float4 lo = *reinterpret_cast<const float4*>(src), hi = *reinterpret_cast<const float4*>(src + 16);
                         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                         const int m = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
-                        if (m < M && n < N) epi.at8(n, (int64_t)m * ld + n, v, z);   // N is a multiple of 8
+                        if (m < M && n < N) epi.at8(pcol, prow[sp], (int64_t)m * ld + n, v, z);   // N is a multiple of 8
                     }
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten
                 }
