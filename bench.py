@@ -7,8 +7,9 @@ in nF1B order on K HIP streams by tmps_schedule_run.  Inputs are synthetic (seed
 uniform labels, He-normal weights) and resident in HBM before the timed region.
 
 Prints ONE JSON line: whole-job samples/s, the roofline of the dominant kernel class (measured
-with HIP events on the kernels' own streams in a second pass of the same workload), and the CPU
-oracle timed on a bounded sample of the same workload as a baseline.
+with HIP events on the kernels' own streams in a second pass of the same workload), samples/s of
+every stage's own step with the device to itself (stage_steps), and the CPU oracle timed on a
+bounded sample of the same workload as a baseline.
 """
 import argparse
 import json
@@ -23,8 +24,9 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 
-def algorithmic_work(cfg):
-    """Per kernel class and per mini-batch: (launches, FLOPs, algorithmic bytes) from the shapes alone.
+def algorithmic_work(cfg, only_stage=None):
+    """Per kernel class and per mini-batch: (launches, FLOPs, algorithmic bytes) from the shapes alone
+    (of every stage, or of stage `only_stage` alone).
 
     Dense GEMMs count 2*rows*Din*Dout FLOPs and their operand/result bytes once; the update counts
     22 bytes per parameter in bf16 stages (read w, buf, g fp32; write w, buf fp32 and the bf16 copy)
@@ -40,6 +42,8 @@ def algorithmic_work(cfg):
         a[2] += nbytes
 
     for si, st in enumerate(cfg.stages):
+        if only_stage is not None and si != only_stage:
+            continue
         P = 0
         for li, sp in enumerate(st):
             if sp["kind"] == "linear":
@@ -124,6 +128,60 @@ def measured_traffic(workload, kernel_class):
     return None
 
 
+def stage_step_rates(T, cfg, params, steps, warmup=3):
+    """Each stage of `cfg` ALONE on the device: its training step (N micro-batch forward passes, the backward pass over
+    the mini-batch, the update) repeated on one stream, stash warm, fed resident synthetic boundary tensors of the
+    stage's own shapes (the workload's inputs and labels on the first and last stage, Gaussian activations and
+    gradients of magnitude 1/M elsewhere).  samples/s = M / time per step."""
+    import numpy as np
+    import torch
+    from workloads import make_batch
+    from workloads.configs import stage_shapes
+    dev = torch.device("cuda:0")
+    M, N, mb = cfg.M, cfg.N, cfg.micro
+    x0, labels0 = make_batch(cfg, 0)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(cfg.seed)
+    out = []
+    for si in range(cfg.K):
+        st = T.Stage(cfg.stages[si], cfg.dtype, mb, N, N, cfg.lr, cfg.momentum, borrow_input=True, device=dev)
+        st.set_params(params[si])
+        adt = st.act_dtype
+        if si == 0:
+            xd = st.prepare_input(x0)
+        else:
+            xd = torch.randn(M, st.in_elems, generator=gen).to(adt).to(dev)
+        xd = xd.reshape(M, -1).contiguous()
+        ld = torch.from_numpy(np.ascontiguousarray(labels0.astype(np.int32))).to(dev) if st.is_last else None
+        dy = None if st.is_last else (torch.randn(M, st.out_elems, generator=gen) / M).to(adt).to(dev)
+        y = None if st.is_last else torch.empty(mb * st.out_elems, dtype=adt, device=dev)
+        loss = torch.zeros(1, dtype=torch.float32, device=dev) if st.is_last else None
+        dx = None if si == 0 else torch.empty(M * st.in_elems, dtype=adt, device=dev)
+        slots = list(range(N))
+
+        def step():
+            for j in range(N):
+                st.forward_micro(j, xd[j * mb:(j + 1) * mb], y=y, labels=ld[j * mb:(j + 1) * mb] if st.is_last else None,
+                                 loss_out=loss)
+            st.backward(slots, dy=dy, dx=dx)
+            st.update()
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        assert loss is None or bool(torch.isfinite(loss).all()), "non-finite loss on stage %d" % si
+        flops = sum(v[1] for v in algorithmic_work(cfg, only_stage=si).values())
+        out.append({"stage": si, "samples_per_s": M / dt, "ms_per_step": 1e3 * dt, "gflop_per_step": flops / 1e9,
+                    "mfma_frac_of_bf16_peak": flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else None})
+        del st, xd, dy, y, dx
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,7 +228,7 @@ def main():
     cfg = get_config(args.workload)
     params = init_params(cfg)
     pipe = T.Pipeline(cfg, params, one_stream=args.one_stream, vertical_sync=args.vertical_sync)
-    pipe_stages = list(pipe.stages)
+    shadow_bytes = sum(int(st.shadow.numel()) for st in pipe.stages if getattr(st, "shadow", None) is not None)
     n_distinct = min(32, max(args.steps, args.warmup, 1))
     distinct = [make_batch(cfg, i) for i in range(n_distinct)]
 
@@ -293,17 +351,22 @@ def main():
             cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
                    "sample": "%d mini-batches of the same workload through the numpy fp64 oracle pipeline (%.1f s)" % (n_cpu, dc)}
 
+    # Every stage's own training step with the device to itself (one stream, no other stage's kernels).
+    del pipe, xw, yw, lw, xs, ys, ls
+    torch.cuda.empty_cache()
+    stage_steps = None
+    if not args.one_stream and not args.calibrate_copy and not args.vertical_sync:
+        stage_steps = stage_step_rates(T, cfg, params, max(5, min(args.steps, 20)))
     # The other benchmark configurations, for context: the same measurement (resident inputs, K streams, wall time
-    # between device synchronisations) on a short run each, without per-kernel timing.
+    # between device synchronisations) on a short run each, without per-kernel timing, and their stages' own steps.
     others = []
     if not args.no_other_workloads and not args.one_stream and not args.calibrate_copy and not args.vertical_sync:
-        del pipe, xw, yw, lw, xs, ys, ls
-        torch.cuda.empty_cache()
         for name in ("tiny_mlp_f32", "mlp4x1024_bf16", "vgg16_bf16", "resnet50_bf16", "gpt2_small_bf16"):
             if name == cfg.name:
                 continue
             ocfg = get_config(name)
-            opipe_ = T.Pipeline(ocfg, init_params(ocfg))
+            oparams = init_params(ocfg)
+            opipe_ = T.Pipeline(ocfg, oparams)
             n = 20 if name in ("resnet50_bf16", "gpt2_small_bf16") else 60
             ob = [make_batch(ocfg, i) for i in range(min(n, 8))]
             ox, oy = opipe_.upload([ob[i % len(ob)] for i in range(n)])
@@ -317,13 +380,14 @@ def main():
             od = time.perf_counter() - t1
             assert np.all(np.isfinite(ol.cpu().numpy())), "non-finite loss in %s" % name
             ow = algorithmic_work(ocfg)
+            del opipe_, ox, oy, ol
+            torch.cuda.empty_cache()
             others.append({"workload": name, "value": ocfg.M * n / od, "unit": "samples/s", "ms_per_step": 1e3 * od / n,
                            "steps": n, "mini_batch": ocfg.M, "micro_batches": ocfg.N, "stages": ocfg.K,
                            "dtype": "bf16" if ocfg.dtype == "bf16" else "f32",
                            "mfma_frac_of_bf16_peak_end_to_end": (sum(v[1] for v in ow.values()) / (od / n) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
-                           if ocfg.dtype == "bf16" else None})
-            del opipe_, ox, oy, ol
-            torch.cuda.empty_cache()
+                           if ocfg.dtype == "bf16" else None,
+                           "stage_steps": stage_step_rates(T, ocfg, oparams, 20)})
 
     out = {
         "metric": "training samples/sec (all K stages, nF1B) on 1 MI355X",
@@ -333,10 +397,10 @@ def main():
         "config": {"workload": cfg.name, "mini_batch": cfg.M, "micro_batches": cfg.N, "stages": cfg.K,
                    "version_difference": T.version_diff_simulated(cfg.K, cfg.N),
                    "weight_policy": "vertical weight stashing" if args.vertical_sync else "in place",
-                   "shadow_weight_bytes": sum(int(st.shadow.numel()) for st in pipe_stages if getattr(st, "shadow", None) is not None),
+                   "shadow_weight_bytes": shadow_bytes,
                    "streams": 1 if args.one_stream else cfg.K, "hw_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
         "mfma_frac_of_bf16_peak_end_to_end": flops_step / (dt / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "kernels_one_stream": kernels_alone,
+        "stage_steps": stage_steps, "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "kernels_one_stream": kernels_alone,
         "final_loss": float(losses[-1]) if np.isfinite(losses[-1]) else None, "diverged": diverged, "other_workloads": others,
     }
     print(json.dumps(out))
