@@ -330,8 +330,11 @@ template <int BM, int BN, class AOp, class BOp> constexpr int gemm2_lds_bytes() 
 }
 
 // D = number of k-tiles whose global loads are in flight per thread (register ring).
+// The 64 x 64 tiles are compiled for three waves per SIMD (168 registers, nothing spilled): launches of 500 to 800
+// tiles, as the 1024-row transformer GEMMs are, then have all their workgroups resident at once instead of running
+// a second, nearly empty round.
 template <int BM, int BN, int D, bool ROWSUM, class AOp, class BOp, class Epi>
-__global__ __launch_bounds__(256) void gemm2_kernel(AOp A, BOp B, Epi epi, int M, int N, int K, int k_per_slice,
+__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_kernel(AOp A, BOp B, Epi epi, int M, int N, int K, int k_per_slice,
                                                     int col_major, int wide) {
     constexpr bool AKC = AOp::kContig, BKC = BOp::kContig;
     constexpr int TM = BM / 64, TN = BN / 64;
