@@ -346,18 +346,23 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin in launch order.  Renumber the tiles
-    // of a k-slice so that the workgroups of one XCD own a contiguous run of tiles: in row-major order the tiles of
-    // a row share their A panel and find it in their own L2, but every XCD fetches all of B; in column-major order
-    // (col_major, chosen by the host when B is the larger operand) it is the other way round.
-    int tile_x = blockIdx.x, tile_y = blockIdx.y;
+    // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin in launch order (x fastest, then y, then
+    // z).  Renumber them so that the workgroups of one XCD own a contiguous run of (k-slice, tile) pairs, the tiles of
+    // a k-slice next to each other: the tiles of one k-slice read the same k-range of both operands (a split
+    // weight gradient: the same positions of dY and of X, nine times over for a 3x3 filter), which then comes in
+    // from memory once instead of once per XCD.  Within a k-slice, in row-major order the tiles of a row share their
+    // A panel and find it in their own L2, but every XCD fetches all of B; in column-major order (col_major, chosen
+    // by the host when B is the larger operand) it is the other way round.
+    int tile_x = blockIdx.x, tile_y = blockIdx.y, z = blockIdx.z;
     {
-        const int gx = gridDim.x, gy = gridDim.y, nb = gx * gy;
-        if (nb >= 16) {
-            const int lin = tile_y * gx + tile_x;
+        const int gx = gridDim.x, gy = gridDim.y, nb = gx * gy, total = nb * gridDim.z;
+        if (total >= 16) {
+            const int lin = (z * gy + tile_y) * gx + tile_x;
             const int xcd = lin & 7, idx = lin >> 3;
-            const int q = nb >> 3, r = nb & 7;
-            const int moved = xcd * q + min(xcd, r) + idx;
+            const int q = total >> 3, r = total & 7;
+            int moved = xcd * q + min(xcd, r) + idx;
+            z = moved / nb;
+            moved -= z * nb;
             if (col_major) {
                 tile_x = moved / gy;
                 tile_y = moved - tile_x * gy;
@@ -367,7 +372,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
             }
         }
     }
-    const int m0 = tile_y * BM, n0 = tile_x * BN, z = blockIdx.z;
+    const int m0 = tile_y * BM, n0 = tile_x * BN;
     const int k_begin = z * k_per_slice;
     const int k_end = min(K, k_begin + k_per_slice);
     const int nk = (k_end - k_begin + kBK2 - 1) / kBK2;
