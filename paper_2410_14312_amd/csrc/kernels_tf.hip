@@ -670,13 +670,31 @@ __device__ __forceinline__ void softmax_block(f32x16_t& st, int kb, int q, int h
 }
 
 // Forward.  Block = NW waves = 32*NW query rows of one (batch, head).
+// Workgroups go to the 8 XCDs (each with its own L2) round-robin in launch order (x fastest, then y, then z).  Hand
+// every XCD a contiguous run of that order instead: the query (or key) blocks of one (batch, head) then sit on one XCD,
+// and the keys and values (queries and output gradients) they all read come in from memory once, not once per XCD.
+__device__ __forceinline__ void xcd_local_block(int& x, int& y, int& z) {
+    const int gx = gridDim.x, gy = gridDim.y, plane = gx * gy, total = plane * gridDim.z;
+    x = blockIdx.x; y = blockIdx.y; z = blockIdx.z;
+    if (total < 16) return;
+    const int lin = (z * gy + y) * gx + x;
+    const int xcd = lin & 7, idx = lin >> 3, q = total >> 3, r = total & 7;
+    int moved = xcd * q + min(xcd, r) + idx;
+    z = moved / plane;
+    moved -= z * plane;
+    y = moved / gx;
+    x = moved - y * gx;
+}
+
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                                 float* __restrict__ lse, int S, int D, int H, float scale) {
     __shared__ __attribute__((aligned(16))) bf16_t sKb[2][64 * kAP];
     __shared__ __attribute__((aligned(16))) bf16_t sVb[2][64 * kAP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int bx, h, b;
+    xcd_local_block(bx, h, b);
+    const int qb = gridDim.x - 1 - bx;
     const int64_t ld = 3 * (int64_t)D;
     const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
     const int q0 = (qb * NW + wave) * 32;
@@ -759,7 +777,9 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_split_kernel(const bf16_t* _
     __shared__ float sOw[NW - 1][32][64];
     __shared__ float sMw[NW - 1][32], sLw[NW - 1][32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int bx, h, b;
+    xcd_local_block(bx, h, b);
+    const int qb = gridDim.x - 1 - bx;
     const int64_t ld = 3 * (int64_t)D;
     const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
     const int q0 = qb * 32;
@@ -876,7 +896,9 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_q_mfma_kernel(const bf16_t* 
     __shared__ __attribute__((aligned(16))) bf16_t sKb[2][64 * kAP];
     __shared__ __attribute__((aligned(16))) bf16_t sVb[2][64 * kAP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int bx, h, b;
+    xcd_local_block(bx, h, b);
+    const int qb = gridDim.x - 1 - bx;
     const int64_t ld = 3 * (int64_t)D;
     const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
     const bf16_t* dob = dout + (int64_t)b * S * D + h * 64;
@@ -970,7 +992,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_kv_mfma_kernel(const bf16_t*
     __shared__ __attribute__((aligned(16))) bf16_t sOb[2][64 * kAP];
     __shared__ __attribute__((aligned(16))) float sLb[2][64], sDlb[2][64];   // log-sum-exp (in units of log 2) and delta
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int kblk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int kblk, h, b;
+    xcd_local_block(kblk, h, b);
     const int64_t ld = 3 * (int64_t)D;
     const bf16_t* base = qkv + (int64_t)b * S * ld + h * 64;
     const bf16_t* dob = dout + (int64_t)b * S * D + h * 64;
