@@ -610,6 +610,13 @@ __global__ void splitk_finish_kernel(const float* __restrict__ part, Epi epi, in
     if (i >= total) return;
     float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
     int z = 0;
+    for (; z + 8 <= slices; z += 8) {   // eight loads in flight; the sums are those of two rounds of the loop below
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[(z + u) * total + i];
+        a0 += v[0]; a1 += v[1]; a2 += v[2]; a3 += v[3];
+        a0 += v[4]; a1 += v[5]; a2 += v[6]; a3 += v[7];
+    }
     for (; z + 4 <= slices; z += 4) {
         a0 += part[(z + 0) * total + i];
         a1 += part[(z + 1) * total + i];
@@ -619,6 +626,51 @@ __global__ void splitk_finish_kernel(const float* __restrict__ part, Epi epi, in
     for (; z < slices; ++z) a0 += part[z * total + i];
     int m = (int)(i / N), n = (int)(i - (int64_t)m * N);
     epi.at(epi.column(n), (int64_t)m * epi.ld + n, (a0 + a1) + (a2 + a3), 0);
+}
+
+// The same for 8 consecutive columns per thread (N a multiple of 8, every tensor of the epilogue 16-byte aligned):
+// 16-byte loads of the partial sums and of what the epilogue reads, 16-byte stores; sums in the order of the kernel
+// above (slice z goes to accumulator z % 4).
+template <class Epi>
+__global__ __launch_bounds__(256) void splitk_finish8_kernel(const float* __restrict__ part, Epi epi, int M, int N, int slices) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int n8 = N >> 3;
+    if (c >= (int64_t)M * n8) return;
+    const int m = (int)(c / n8), n = (int)(c - (int64_t)m * n8) * 8;
+    const int64_t total = (int64_t)M * N, idx = (int64_t)m * epi.ld + n;
+    const typename Epi::Col8 pcol = epi.col8(n);
+    const typename Epi::Row8 prow = epi.row8(idx, true);
+    const float* p = part + (int64_t)m * N + n;
+    float a[4][8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[k][e] = 0.0f;
+    int z = 0;
+    for (; z + 4 <= slices; z += 4) {
+        float4 lo[4], hi[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            lo[k] = *reinterpret_cast<const float4*>(p + k * total);
+            hi[k] = *reinterpret_cast<const float4*>(p + k * total + 4);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            a[k][0] += lo[k].x; a[k][1] += lo[k].y; a[k][2] += lo[k].z; a[k][3] += lo[k].w;
+            a[k][4] += hi[k].x; a[k][5] += hi[k].y; a[k][6] += hi[k].z; a[k][7] += hi[k].w;
+        }
+        p += 4 * total;
+    }
+    for (; z < slices; ++z) {
+        const float4 lo = *reinterpret_cast<const float4*>(p), hi = *reinterpret_cast<const float4*>(p + 4);
+        a[0][0] += lo.x; a[0][1] += lo.y; a[0][2] += lo.z; a[0][3] += lo.w;
+        a[0][4] += hi.x; a[0][5] += hi.y; a[0][6] += hi.z; a[0][7] += hi.w;
+        p += total;
+    }
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (a[0][e] + a[1][e]) + (a[2][e] + a[3][e]);
+    epi.at8(pcol, prow, idx, v, 0);
 }
 
 }  // namespace tmps

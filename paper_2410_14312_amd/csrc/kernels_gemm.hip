@@ -65,9 +65,55 @@ __global__ void slice_sum_kernel(const float* __restrict__ part, float* __restri
                                  int slices) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
+    // eight loads in flight per thread, added in slice order
+    const float* p = part + i;
     float a = 0.0f;
-    for (int z = 0; z < slices; ++z) a += part[(int64_t)z * count + i];
+    int z = 0;
+    for (; z + 8 <= slices; z += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[u * count];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+        p += 8 * count;
+    }
+    for (; z < slices; ++z) {
+        a += *p;
+        p += count;
+    }
     out[i] = a;
+}
+
+// The same for 4 consecutive elements per thread (count a multiple of 4, both arrays 16-byte aligned).
+__global__ __launch_bounds__(256) void slice_sum4_kernel(const float* __restrict__ part, float* __restrict__ out, int64_t count,
+                                                         int slices) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= count) return;
+    const float* p = part + i;
+    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    int z = 0;
+    for (; z + 8 <= slices; z += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(p + u * count);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            a.x += v[u].x; a.y += v[u].y; a.z += v[u].z; a.w += v[u].w;
+        }
+        p += 8 * count;
+    }
+    for (; z < slices; ++z) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        p += count;
+    }
+    *reinterpret_cast<float4*>(out + i) = a;
+}
+
+static hipError_t slice_sum(const float* part, float* out, int64_t count, int slices, hipStream_t s) {
+    if (count % 4 == 0 && aligned16(part) && aligned16(out))
+        return launch_timed(kcSliceSum, slice_sum4_kernel, dim3(cdiv(count / 4, 256)), dim3(256), 0, s, part, out, count, slices);
+    return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, part, out, count, slices);
 }
 
 // slice length (whole k-tiles) and the number of slices really launched
@@ -116,6 +162,9 @@ static hipError_t run2(int kc, const AOp& A, const BOp& B, const Epi& epi, int M
     hipError_t e = launch2_tile<false>(kc, p.tile, A, B, part, M, N, K, per, nz, s);
     if (e != hipSuccess) return e;
     int64_t total = (int64_t)M * N;
+    if (N % 8 == 0 && epi.wide_ok() && aligned16(ws))
+        return launch_timed(kcSplitFinish, splitk_finish8_kernel<Epi>, dim3(cdiv(total / 8, 256)), dim3(256), 0, s,
+                            (const float*)ws, epi, M, N, nz);
     return launch_timed(kcSplitFinish, splitk_finish_kernel<Epi>, dim3(cdiv(total, 256)), dim3(256), 0, s,
                         (const float*)ws, epi, M, N, nz);
 }
@@ -131,8 +180,7 @@ static hipError_t run2_wgrad(int kc, const AOp& A, const BOp& B, float* gw, int 
     EpiWgrad epi{nz > 1 ? ws : gw, cols, (int64_t)rows * cols, count};
     hipError_t e = launch2_tile<true>(kc, p.tile, A, B, epi, rows, cols, (int)K, per, nz, s);
     if (e != hipSuccess || nz <= 1) return e;
-    return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw,
-                        count, nz);
+    return slice_sum((const float*)ws, gw, count, nz, s);
 }
 
 static int one_slice(int64_t K, int ktile) {
@@ -229,8 +277,7 @@ static hipError_t wgrad_fallback(int kc, const AOp& A, const BOp& B, float* gw, 
     else
         e = launch_f32<true>(kc, A, B, epi, rows, cols, (int)K, per, nz, s);
     if (e != hipSuccess || nz <= 1) return e;
-    return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw,
-                        count, nz);
+    return slice_sum((const float*)ws, gw, count, nz, s);
 }
 
 // ---------------------------------------------------------------------------------------- dense
@@ -312,8 +359,7 @@ static hipError_t dense_wgrad_as(int kc, int dtype, const void* dy, const void* 
             EpiWgrad epi{plan.slices > 1 ? ws : gw, Din, (int64_t)Dout * Din, count};
             hipError_t e = launch3<false, false, true>(kc, A, Bv, epi, Dout, Din, B, plan, s);
             if (e != hipSuccess || plan.slices <= 1) return e;
-            return launch_timed(kcSliceSum, slice_sum_kernel, dim3(cdiv(count, 256)), dim3(256), 0, s, (const float*)ws, gw, count,
-                                plan.slices);
+            return slice_sum((const float*)ws, gw, count, plan.slices, s);
         }
         if (fast) {
             DenseRC A{(const bf16_t*)dy, Dout, B, Dout};

@@ -131,8 +131,24 @@ __global__ __launch_bounds__(1024) void affine_slab_sum_kernel(const float* __re
     const int cl = threadIdx.x & 63, sl = threadIdx.x >> 6;
     const int i = blockIdx.x * 64 + cl;
     float a = 0.0f;
-    if (i < count)
-        for (int z = sl; z < slabs; z += 16) a += part[(int64_t)z * count + i];
+    if (i < count) {
+        // eight loads in flight per lane, added in slab order
+        const float* p = part + (int64_t)sl * count + i;
+        const int64_t step = (int64_t)16 * count;
+        int z = sl;
+        for (; z + 7 * 16 < slabs; z += 8 * 16) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[u * step];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += v[u];
+            p += 8 * step;
+        }
+        for (; z < slabs; z += 16) {
+            a += *p;
+            p += step;
+        }
+    }
     sp[sl][cl] = a;
     __syncthreads();
     if (sl == 0 && i < count) {
