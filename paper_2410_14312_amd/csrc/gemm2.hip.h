@@ -423,7 +423,12 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[a][i][j][r] = 0.0f;
-    float rsum = 0.0f;
+    // Row sums of A (ROWSUM): the waves of the first tile column's first wave column add up the A fragments they
+    // hold anyway: a lane has 8 consecutive k of its row per fragment, the two half-waves the two halves of 16 k.
+    float rsum[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) rsum[i] = 0.0f;
+    const bool sums_rows = ROWSUM && tile_x == 0 && wn == 0;
 
     // Register ring: tile t is fetched into slot t % D.
     uint4 ra[D][A_CH], rb[D][B_CH];
@@ -472,15 +477,13 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[kk % NACC][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[kk % NACC][i][j], 0, 0, 0);
-        if (ROWSUM && tile_x == 0 && tid < BM) {
-            if constexpr (AKC) {
-                const bf16_t* rowp = tA + tid * TileShape<BM, true>::pitch;
-#pragma unroll 8
-                for (int e = 0; e < kBK2; ++e) rsum += (float)rowp[e];
-            } else {
-#pragma unroll 8
-                for (int e = 0; e < kBK2; ++e) rsum += (float)tA[e * TileShape<BM, false>::pitch + tid];
-            }
+        if (sums_rows) {
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) rsum[i] += (float)af[kk][i][e];
         }
     };
 
@@ -577,7 +580,14 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
                 }
             }
     }
-    if (ROWSUM && tile_x == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
+    if (sums_rows) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const float total = rsum[i] + __shfl_xor(rsum[i], 32);
+            const int m = m0 + wm * (BM / 2) + i * 32 + (lane & 31);
+            if (lane < 32 && m < M) epi.rowsum(m, total, z);
+        }
+    }
 }
 
 // Split-k partial sums: slice z stores fp32 at part[z][m][n].
