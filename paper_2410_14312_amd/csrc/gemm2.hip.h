@@ -292,6 +292,135 @@ struct ConvWgradB2 {
     __device__ __forceinline__ void next(KS& ks) const { ks.kb += kBK2; }
 };
 
+// Input gradient of a convolution with stride 2, rows ordered by the PARITY of their position: row
+// m = ((a, b), n, h2, w2) stands for position (h, w) = (2 h2 + a, 2 w2 + b) of image n (H and W even, every class
+// a whole number of tiles).  Position (h, w) receives gradient only through the filter taps r = h + pad (mod 2),
+// s = w + pad (mod 2), so the tiles of one class walk just those taps, k = (r, s, co) over r = r0, r0 + 2, ...,
+// s = s0, s0 + 2, ...: a quarter of the products of the natural order, where the other three quarters multiply
+// zeros.  The kernel asks the loaders for the k extent of a tile (k_total) and for the memory row of a row (out_row).
+struct ParityGeom {
+    int Mc, W2;                      // rows per class, half width
+    FastDiv d_mc, d_h2w2, d_w2;
+};
+
+struct ParityTaps {
+    int r0, s0, ns, keff;            // first tap of the class along r and s, taps along s, k extent
+    __device__ __forceinline__ void set(int pc, const ConvGeom2& g) {
+        r0 = ((pc >> 1) + g.pad) & 1;
+        s0 = ((pc & 1) + g.pad) & 1;
+        const int nr = r0 < g.R ? (g.R - r0 + 1) >> 1 : 0;
+        ns = s0 < g.S ? (g.S - s0 + 1) >> 1 : 0;
+        keff = nr * ns * g.Cout;
+    }
+    // tap and channel of k = (r, s, co) in the class's own order
+    __device__ __forceinline__ void locate(int k, const ConvGeom2& g, int& r, int& s, int& co) const {
+        const int t = (int)g.d_cout.div((uint32_t)k);
+        co = k - t * g.Cout;
+        const int ri = ns > 0 ? t / ns : 0;
+        r = r0 + 2 * ri;
+        s = s0 + 2 * (t - ri * ns);
+    }
+    __device__ __forceinline__ void carry(int& r, int& s, int& co, const ConvGeom2& g) const {
+        while (co >= g.Cout) {
+            co -= g.Cout;
+            s += 2;
+            if (s >= g.S) { s = s0; r += 2; }
+        }
+    }
+};
+
+struct ConvDgradA2P {
+    static constexpr bool kContig = true;
+    const bf16_t* dy;
+    ConvGeom2 g;
+    int rows, K;
+    ParityGeom p;
+    ParityTaps taps;
+    struct KS { int k, r, s, co; };
+    struct Ctx { int hp, wp, nbase; bool ok; };
+    __device__ __forceinline__ void position(int m, int& n, int& h, int& w) const {
+        const int pc = (int)p.d_mc.div((uint32_t)m);
+        uint32_t n_, rem, h2, w2;
+        p.d_h2w2.divmod((uint32_t)(m - pc * p.Mc), n_, rem);
+        p.d_w2.divmod(rem, h2, w2);
+        n = (int)n_;
+        h = 2 * (int)h2 + (pc >> 1);
+        w = 2 * (int)w2 + (pc & 1);
+    }
+    __device__ __forceinline__ void begin_tile(int m0) { taps.set((int)p.d_mc.div((uint32_t)m0), g); }
+    __device__ __forceinline__ int k_total(int) const { return taps.keff; }
+    __device__ __forceinline__ int out_row(int m) const {
+        int n, h, w;
+        position(m, n, h, w);
+        return (n * g.H + h) * g.W + w;
+    }
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int col) const {
+        ks.k = k_begin + col * 8;
+        taps.locate(ks.k, g, ks.r, ks.s, ks.co);
+    }
+    __device__ __forceinline__ void init(Ctx& c, int m, int, int) const {
+        c.ok = m < rows;
+        int n, h, w;
+        position(c.ok ? m : 0, n, h, w);
+        c.hp = h + g.pad;
+        c.wp = w + g.pad;
+        c.nbase = n * g.Ho * g.Wo * g.Cout;
+    }
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        const int hy = c.hp - ks.r, wy = c.wp - ks.s;   // even for the taps of this class
+        const int ho = hy >> 1, wo = wy >> 1;
+        const bool ok = c.ok && ks.k + 8 <= k_end && hy >= 0 && wy >= 0 && ho < g.Ho && wo < g.Wo;
+        return ld16_if(dy, c.nbase + (ho * g.Wo + wo) * g.Cout + ks.co, ok);
+    }
+    __device__ __forceinline__ void next(KS& ks) const {
+        ks.k += kBK2;
+        ks.co += kBK2;
+        taps.carry(ks.r, ks.s, ks.co, g);
+    }
+};
+
+// The filter taps in the same order: row n = ci (8 consecutive), k = (r, s, co) of the tile's class -> w[co, r, s, ci].
+struct ConvDgradB2P {
+    static constexpr bool kContig = false;
+    const bf16_t* w;
+    ConvGeom2 g;
+    int rows, K;
+    ParityGeom p;
+    ParityTaps taps;
+    struct KS { int kb, r, s, co; };
+    struct Ctx { int ci0, kl; bool ok; };
+    __device__ __forceinline__ void begin_tile(int m0) { taps.set((int)p.d_mc.div((uint32_t)m0), g); }
+    __device__ __forceinline__ void init_thread(KS& ks, int k_begin, int) const {
+        ks.kb = k_begin;
+        taps.locate(k_begin, g, ks.r, ks.s, ks.co);
+    }
+    __device__ __forceinline__ void init(Ctx& c, int row0, int kl, int) const {
+        c.ok = row0 + 8 <= rows;
+        c.ci0 = row0;
+        c.kl = kl;
+    }
+    __device__ __forceinline__ uint4 load(Ctx& c, const KS& ks, int k_end) const {
+        const bool ok = c.ok && ks.kb + c.kl < k_end;
+        int co = ks.co + c.kl, s = ks.s, r = ks.r;
+        taps.carry(r, s, co, g);
+        const int off = mul24(mul24(mul24(co, g.R) + r, g.S) + s, g.Cin) + c.ci0;
+        return ld16_if(w, off, ok);
+    }
+    __device__ __forceinline__ void next(KS& ks) const {
+        ks.kb += kBK2;
+        ks.co += kBK2;
+        taps.carry(ks.r, ks.s, ks.co, g);
+    }
+};
+
+// What gemm2_kernel asks of a loader beyond its chunks; loaders without these members get the defaults.
+template <class Op> __device__ __forceinline__ auto op_begin_tile(Op& op, int m0, int) -> decltype(op.begin_tile(m0), void()) { op.begin_tile(m0); }
+template <class Op> __device__ __forceinline__ void op_begin_tile(Op&, int, long) {}
+template <class Op> __device__ __forceinline__ auto op_k_total(const Op& op, int K, int) -> decltype(op.k_total(K)) { return op.k_total(K); }
+template <class Op> __device__ __forceinline__ int op_k_total(const Op&, int K, long) { return K; }
+template <class Op> __device__ __forceinline__ auto op_out_row(const Op& op, int m, int) -> decltype(op.out_row(m)) { return op.out_row(m); }
+template <class Op> __device__ __forceinline__ int op_out_row(const Op&, int m, long) { return m; }
+
 // ------------------------------------------------------------------------------------------
 // LDS tile shapes.  k-contiguous: [rows][64 + 8] (144-byte rows: 16-byte reads of 8 consecutive rows
 // hit disjoint banks).  row-contiguous: [64][rows + 16] (row pitch = 32 bytes mod 128, so the 4 k-rows
@@ -373,9 +502,13 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
         }
     }
     const int m0 = tile_y * BM, n0 = tile_x * BN;
+    // (a loader may walk a k range of its own for this tile, and may keep its rows in another order than memory does:
+    // the wide epilogue below asks it for the memory row; the host sends such a loader only there)
+    op_begin_tile(A, m0, 0);
+    op_begin_tile(B, m0, 0);
     const int k_begin = z * k_per_slice;
-    const int k_end = min(K, k_begin + k_per_slice);
-    const int nk = (k_end - k_begin + kBK2 - 1) / kBK2;
+    const int k_end = min(op_k_total(A, K, 0), k_begin + k_per_slice);
+    const int nk = max(0, (k_end - k_begin + kBK2 - 1) / kBK2);
 
     typename AOp::KS ksa;
     typename BOp::KS ksb;
@@ -531,7 +664,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
 #pragma unroll
                 for (int ps = 0; ps < 2; ++ps) {
                     const int pm = m0 + wm * (BM / 2) + i * 32 + ps * 16 + (lane >> 2);
-                    prow[ps] = epi.row8((int64_t)pm * ld + pn, pm < M && pn < N);
+                    prow[ps] = epi.row8((int64_t)op_out_row(A, pm < M ? pm : 0, 0) * ld + pn, pm < M && pn < N);
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + row_in + (r & 3)) * SP + col_in] = acc[0][i][j][r];
@@ -544,7 +677,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
                     const float4 hi = *reinterpret_cast<const float4*>(stage + row * SP + (lane & 3) * 8 + 4);
                     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                     const int m = m0 + wm * (BM / 2) + i * 32 + row;
-                    if (m < M && n < N) epi.at8(pcol, prow[ps], (int64_t)m * ld + n, v, z);
+                    if (m < M && n < N) epi.at8(pcol, prow[ps], (int64_t)op_out_row(A, m, 0) * ld + n, v, z);
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten
             }

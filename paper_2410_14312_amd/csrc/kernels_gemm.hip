@@ -150,11 +150,13 @@ static hipError_t launch2_tile(int kc, int tile, const AOp& A, const BOp& B, con
 }
 
 // Forward / input-gradient style GEMM: epilogue `epi` applied once per output element.
+// tile: 0 = the plan's choice, else the tile edge to use (the slices stay the plan's)
 template <class AOp, class BOp, class Epi>
 static hipError_t run2(int kc, const AOp& A, const BOp& B, const Epi& epi, int M, int N, int K, float* ws,
-                       hipStream_t s) {
+                       hipStream_t s, int tile = 0) {
     if (M <= 0 || N <= 0) return hipSuccess;
     GemmPlan p = plan_gemm(M, N, K);
+    if (tile) p.tile = tile;
     int per, nz;
     slice_geometry(K, ws ? p.slices : 1, kBK2, per, nz);
     if (nz <= 1) return launch2_tile<false>(kc, p.tile, A, B, epi, M, N, K, per, nz, s);
@@ -473,6 +475,31 @@ hipError_t conv_dgrad(int dtype, const void* dy, const void* w, void* dx, const 
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, c.Cin, kActRelu, (const bf16_t*)add};
         if (c.Cin % 8 == 0 && c.Cout % 8 == 0 && aligned16(dy) && aligned16(w) && small_enough(c)) {
+            if (c.stride == 2 && c.H % 2 == 0 && c.W % 2 == 0) {
+                // Rows ordered by the parity of their position, each class walking only the filter taps that reach it:
+                // k extent of the largest class; every class a whole number of tiles; the 16-byte epilogue (the one
+                // that asks the loader where a row lies in memory), also for the partial sums of a split.
+                const int Kp = ((c.R + 1) / 2) * ((c.S + 1) / 2) * c.Cout;
+                const GemmPlan plan = plan_gemm(M, c.Cin, Kp);
+                const int Mc = M / 4;
+                int per, nz;
+                slice_geometry(Kp, ws ? plan.slices : 1, kBK2, per, nz);
+                const bool split_ok = nz <= 1 || (aligned16(ws) && ((int64_t)M * c.Cin) % 4 == 0);
+                // (where a class is no whole number of the plan's tiles, smaller tiles still pay for a filter with
+                // several taps; a 1x1 filter's launch is mostly epilogue either way and keeps the plain order then)
+                const int tile = (Mc % plan.tile == 0 || c.R * c.S == 1) ? plan.tile : 64;
+                if (Mc % tile == 0 && epi.wide_ok() && split_ok) {
+                    ParityGeom pg;
+                    pg.Mc = Mc;
+                    pg.W2 = c.W / 2;
+                    pg.d_mc = FastDiv(Mc);
+                    pg.d_h2w2 = FastDiv((c.H / 2) * (c.W / 2));
+                    pg.d_w2 = FastDiv(c.W / 2);
+                    ConvDgradA2P A{(const bf16_t*)dy, geom2(c), M, Kp, pg, {}};
+                    ConvDgradB2P Bv{(const bf16_t*)w, geom2(c), c.Cin, Kp, pg, {}};
+                    return run2(kcConvDgrad, A, Bv, epi, M, c.Cin, Kp, ws, s, tile);
+                }
+            }
             ConvDgradA2 A{(const bf16_t*)dy, geom2(c), M, K};
             ConvDgradB2 Bv{(const bf16_t*)w, geom2(c), c.Cin, K};
             return run2(kcConvDgrad, A, Bv, epi, M, c.Cin, K, ws, s);

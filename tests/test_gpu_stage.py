@@ -244,6 +244,11 @@ CONV_CASES = [
     (8, 8, 16, 32, 1, 2, 0, False, 4, 2),    # strided 1x1 (projection shortcut shape)
     (20, 20, 3, 16, 7, 2, 3, True, 2, 2),    # 7x7 stride 2 stem
     (4, 4, 64, 128, 3, 1, 1, True, 32, 4),   # deep-layer shape: small image, many channels, M=128
+    # stride 2 on even maps with channel counts of 8: the input gradient orders its rows by position parity
+    (8, 8, 16, 32, 3, 2, 1, True, 4, 2),     # 3x3: 4, 2, 2 and 1 taps per class
+    (16, 16, 8, 16, 7, 2, 3, True, 2, 2),    # 7x7: 3 or 4 taps along each axis
+    (32, 32, 128, 16, 3, 2, 1, True, 8, 2),  # 128-wide tiles
+    (12, 8, 24, 16, 3, 2, 0, False, 4, 2),   # no padding, non-square, ragged channels
 ]
 
 
