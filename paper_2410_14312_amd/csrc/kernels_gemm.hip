@@ -142,16 +142,18 @@ static hipError_t launch2_inst(int kc, const AOp& A, const BOp& B, const Epi& ep
                         (N % 8 == 0 && epi.wide_ok()) ? 1 : 0);
 }
 
-// tile: the plan's tile edge.  Where it is 64 and the output has 512 rows or more, the tiles are 128 rows tall unless
-// the caller needs them square (`square`): a 128 x 64 tile reads a quarter less LDS per MFMA than a 64 x 64 one, and
-// with the stages' kernels sharing the device that outweighs having half as many workgroups (measured: GPT-2 and
-// ResNet-50 steps 1 % shorter, VGG-16 2 %; 128 x 128 and 64 x 128 for the same launches did worse).
+// tile: the plan's tile edge.  Where it is 64, the output has 512 rows or more and 128 x 64 tiles still make 192
+// workgroups, the tiles are 128 rows tall unless the caller needs them square (`square`): a 128 x 64 tile reads a
+// quarter less LDS per MFMA than a 64 x 64 one, and with the stages' kernels sharing the device that outweighs
+// having half as many workgroups (measured: GPT-2 and ResNet-50 steps 1 % shorter, VGG-16 1-2 %; 128 x 128 and
+// 64 x 128 for the same launches did worse; below 192 workgroups the launch itself gets slower and the step no faster).
 template <bool ROWSUM, class AOp, class BOp, class Epi>
 static hipError_t launch2_tile(int kc, int tile, bool square, const AOp& A, const BOp& B, const Epi& epi, int M, int N,
                                int K, int per, int nz, hipStream_t s) {
     if (tile == 128) return launch2_inst<128, 128, 2, ROWSUM>(kc, A, B, epi, M, N, K, per, nz, s);
     if constexpr (!ROWSUM) {
-        if (!square && M >= 512) return launch2_inst<128, 64, 2, false>(kc, A, B, epi, M, N, K, per, nz, s);
+        if (!square && M >= 512 && (int64_t)cdiv(M, 128) * cdiv(N, 64) * nz >= 192)
+            return launch2_inst<128, 64, 2, false>(kc, A, B, epi, M, N, K, per, nz, s);
     }
     return launch2_inst<64, 64, 4, ROWSUM>(kc, A, B, epi, M, N, K, per, nz, s);
 }
