@@ -288,7 +288,19 @@ def main():
     kernels, pair_us = timed_pass(args.one_stream)
     # Pass 3: every worker on one stream, so each kernel has the device to itself: the per-kernel rates that the
     # roofline is about.
-    kernels_alone, pair_us_alone = (kernels, pair_us) if args.one_stream else timed_pass(True)
+    # (three such passes, per class the one with the lowest average: a pass during which the host stalls or the clocks
+    # still ramp reads several microseconds high on every launch)
+    if args.one_stream:
+        kernels_alone, pair_us_alone = kernels, pair_us
+    else:
+        passes = [timed_pass(True) for _ in range(3)]
+        pair_us_alone = min(p[1] for p in passes)
+        best = {}
+        for plist, _ in passes:
+            for e in plist:
+                if e["class"] not in best or e["avg_us"] < best[e["class"]]["avg_us"]:
+                    best[e["class"]] = e
+        kernels_alone = sorted(best.values(), key=lambda e: -e["ms_per_step"])
     dom = kernels_alone[0]
     hbm_bound = dom["class"] in ("update", "softmax_ce", "pool_fwd", "pool_bwd", "relu_mask", "copy", "reduce", "layernorm",
                                  "embedding", "affine", "resadd")
@@ -299,7 +311,8 @@ def main():
             "traffic": measured_traffic(cfg.name, dom["class"]), "avg_launch_us": dom["avg_us"],
             "launches_per_step": dom["launches_per_step"],
             "timing": "per-launch durations of a pass of the same mini-batches with all workers on one stream (no other "
-                      "kernel on the device); rocprofv3 summary of that command: profiles/%s_one_stream_kernel_trace.txt" % cfg.name,
+                      "kernel on the device; per class the lowest average of three such passes); rocprofv3 summary of "
+                      "that command: profiles/%s_one_stream_kernel_trace.txt" % cfg.name,
             "event_pair_us_subtracted": pair_us_alone}
     shared = next((e for e in kernels if e["class"] == dom["class"]), None)
     if shared is not None and not args.one_stream:
