@@ -29,7 +29,11 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     // workgroups finish sooner (measured on 1024-row transformer GEMMs: 13 us against 16 us).
     const bool short_rows = M <= 2048 && t128 < 256 && K <= 4096;
     // (a long contraction is cut into slices anyway: then a dozen 128-tiles suffice to fill the device)
-    p.tile = (wide && !short_rows && (t128 >= 64 || (K > 4096 && t128 >= 8))) ? 128 : 64;
+    // 128 x 128 tiles for outputs of 512 such tiles or more, for 64 or more with a contraction of 2048 or longer, and
+    // for a dozen with a very long one; in between, the smaller tiles (128 x 64 for tall outputs) do better with
+    // the stages' kernels sharing the device (swept on the ResNet-50, VGG-16 and GPT-2 workloads: a short contraction
+    // is mostly epilogue, which the smaller tiles spread over more workgroups)
+    p.tile = (wide && !short_rows && (t128 >= 512 || (t128 >= 64 && K >= 2048) || (K > 4096 && t128 >= 8))) ? 128 : 64;
     const int64_t tiles = p.tile == 128 ? t128 : t64;
     const int64_t target = 384;  // swept 32..2048 on the VGG workload: flat optimum around 384-512
     int64_t s = 1;
