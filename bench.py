@@ -200,6 +200,9 @@ def main():
                          "in-place policy of the default run saves")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short throughput runs of the other benchmark configurations (reported under other_workloads)")
+    ap.add_argument("--one-stream-passes", type=int, default=3,
+                    help="per-kernel timing passes with all workers on one stream (the roofline figures take the lowest class "
+                         "averages among them); 0: none, the roofline then shows the K-stream durations")
     ap.add_argument("--hw-queues", type=int, default=8,
                     help="hardware queues HIP may use (GPU_MAX_HW_QUEUES, read when HIP starts): the K stage streams and "
                          "the default stream share the runtime's default of 4, so two stages would take turns on one queue")
@@ -290,10 +293,10 @@ def main():
     # roofline is about.
     # (three such passes, per class the one with the lowest average: a pass during which the host stalls or the clocks
     # still ramp reads several microseconds high on every launch)
-    if args.one_stream:
+    if args.one_stream or args.one_stream_passes <= 0:
         kernels_alone, pair_us_alone = kernels, pair_us
     else:
-        passes = [timed_pass(True) for _ in range(3)]
+        passes = [timed_pass(True) for _ in range(args.one_stream_passes)]
         pair_us_alone = min(p[1] for p in passes)
         best = {}
         for plist, _ in passes:
@@ -311,7 +314,7 @@ def main():
             "traffic": measured_traffic(cfg.name, dom["class"]), "avg_launch_us": dom["avg_us"],
             "launches_per_step": dom["launches_per_step"],
             "timing": "per-launch durations of a pass of the same mini-batches with all workers on one stream (no other "
-                      "kernel on the device; per class the lowest average of three such passes); rocprofv3 summary of "
+                      "kernel on the device; per class the lowest average of such passes); rocprofv3 summary of "
                       "that command: profiles/%s_one_stream_kernel_trace.txt" % cfg.name,
             "event_pair_us_subtracted": pair_us_alone}
     shared = next((e for e in kernels if e["class"] == dom["class"]), None)
