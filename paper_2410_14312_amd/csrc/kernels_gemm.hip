@@ -37,9 +37,9 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const int64_t tiles = p.tile == 128 ? t128 : t64;
     const int64_t target = 384;  // swept 32..2048 on the VGG workload: flat optimum around 384-512
     int64_t s = 1;
-    // (short outputs with a hundred tiles or more and a short contraction are not split: the finishing kernel costs
-    // more than the split saves)
-    if (tiles < target && !(short_rows && tiles >= 128)) {
+    // (short outputs with 64 tiles or more and a short contraction are not split: the finishing kernel costs
+    // more than the split saves; swept 1..256)
+    if (tiles < target && !(short_rows && tiles >= 64)) {
         s = (target + tiles - 1) / tiles;
         const int64_t by_k = K / 128;
         const int64_t by_bytes = ((M + N) * K) / (2 * M * N);
