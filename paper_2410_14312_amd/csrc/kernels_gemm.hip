@@ -25,9 +25,10 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const int64_t t128 = (int64_t)cdiv(M, 128) * cdiv(N, 128);
     const int64_t t64 = (int64_t)cdiv(M, 64) * cdiv(N, 64);
     const bool wide = N > 64 && M > 64;
-    // A short output (a micro-batch's rows) with fewer 128-tiles than compute units is latency-bound: more, smaller
-    // workgroups finish sooner (measured on 1024-row transformer GEMMs: 13 us against 16 us).
-    const bool short_rows = M <= 2048 && t128 < 256 && K <= 4096;
+    // An output with fewer 128-tiles than compute units and a contraction that is not long is latency-bound: more,
+    // smaller workgroups finish sooner (measured on 1024-row transformer GEMMs: 13 us against 16 us; a row limit of
+    // 2048 that used to stand here cost ResNet-50 1.6 % and VGG-16 2.8 % per step).
+    const bool short_rows = t128 < 256 && K <= 4096;
     // (a long contraction is cut into slices anyway: then a dozen 128-tiles suffice to fill the device)
     // 128 x 128 tiles for outputs of 512 such tiles or more, for 64 or more with a contraction of 2048 or longer, and
     // for a dozen with a very long one; in between, the smaller tiles (128 x 64 for tall outputs) do better with
