@@ -59,13 +59,16 @@ def _cos(a, b):
     return float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
 
 
-def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False, deep=False):
+def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False, deep=False, deep_l2=0.2):
     """deep (bf16 only): a stage of tens of ReLU layers.  The two sides store the same bf16 tensors only up to
-    rounding ties (fp32 against fp64 sums); a stored activation that lands on the other side of zero flips its
-    ReLU mask, the flips accumulate along the backward pass, and after a few dozen layers two CORRECT
-    evaluations of the same stage differ by a few percent in the gradients of the earliest layers (the effect
-    tests/test_oracle_precision.py measures between two precisions of the oracle itself).  Such stages are held
-    to relative L2 error < 0.2 and direction cosine > 0.98 in bf16.  In fp32 the same happens to a handful of
+    rounding ties (fp32 against fp64 sums); the differences grow with depth, a stored activation that lands on
+    the other side of zero flips its ReLU mask, and after a few dozen layers two CORRECT evaluations of the same
+    stage differ by percents in the gradients of the earliest layers.  tests/test_oracle_relu_ties.py shows this
+    between two evaluations of the oracle that differ only in the precision of their sums, and that the
+    element-wise bar holds again once both use the same masks; tests/test_gpu_resnet50_blocks.py holds every
+    block of these stages, fed the oracle's tensors, to the element-wise bar at the real shapes.  A whole stage
+    is held to relative L2 error < deep_l2 and direction cosine > 1 - deep_l2^2 / 2 in bf16 (deep_l2 is set per
+    stage to about twice what the stage measures: 0.013, 0.047, 0.16 and 0.05 for the four ResNet-50 stages).  In fp32 the same happens to a handful of
     activations that lie within rounding of zero, and one flipped mask perturbs the whole receptive field below
     it (a whole 14 x 14 image after six blocks): there the element-wise bar must hold on 90 % of the elements
     of the input gradient, and the relative L2 error of every result must stay below 1e-2."""
@@ -148,7 +151,8 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False, d
     elif deep32:
         mostly(got_dx, o_dx, "dx")
     elif deep:
-        assert rel_l2(got_dx, o_dx) < 0.2 and _cos(got_dx, o_dx) > 0.98, "dx: l2 %g cos %g" % (rel_l2(got_dx, o_dx), _cos(got_dx, o_dx))
+        print("deep dx: max-norm %.3g outside %.3g l2 %.3g cos %.5f" % (rel_err(got_dx, o_dx), frac_outside(got_dx, o_dx, tol), rel_l2(got_dx, o_dx), _cos(got_dx, o_dx)), flush=True)
+        assert rel_l2(got_dx, o_dx) < deep_l2 and _cos(got_dx, o_dx) > 1 - deep_l2 ** 2 / 2, "dx: l2 %g cos %g" % (rel_l2(got_dx, o_dx), _cos(got_dx, o_dx))
     elif has_pool and dtype == "bf16":
         # near-ties of a pooling window can be won by a different element in bf16 than in fp64: such
         # isolated reroutings are valid; everything else must agree
@@ -162,7 +166,8 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False, d
         for k in g:
             if deep:
                 a, b = grads[li][k], g[k]
-                assert rel_l2(a, b) < 0.2 and _cos(a, b) > 0.98, "grad layer %d %s: l2 %g cos %g" % (li, k, rel_l2(a, b), _cos(a, b))
+                print("deep grad %d %s: max-norm %.3g l2 %.3g" % (li, k, rel_err(a.reshape(b.shape), b), rel_l2(a, b)), flush=True)
+                assert rel_l2(a, b) < deep_l2 and _cos(a, b) > 1 - deep_l2 ** 2 / 2, "grad layer %d %s: l2 %g cos %g" % (li, k, rel_l2(a, b), _cos(a, b))
                 continue
             if deep32:
                 mostly(grads[li][k], g[k], "grad layer %d %s" % (li, k), per_sample=False)
@@ -184,7 +189,7 @@ def run_stage_case(specs, dtype, micro, N, seed, has_pool=False, borrow=False, d
     assert gst.version() == 1
     w_after = gst.get_params()
     loose = (has_pool and dtype == "bf16") or deep or deep32
-    step_tol = 0.2 if deep else (1e-2 if deep32 else (3 * tol if loose else tol))
+    step_tol = deep_l2 if deep else (1e-2 if deep32 else (3 * tol if loose else tol))
     for li, p in enumerate(ost.params):
         for k in p:
             assert (rel_l2(w_after[li][k], p[k]) if loose else rel_err(w_after[li][k], p[k])) < (step_tol if (deep or deep32) else tol)
