@@ -74,3 +74,16 @@ def test_benchmark_launch_configuration_at_full_size(name):
     if name.startswith("gpt2"):
         # an untrained language model with small initial logits: the loss of the first mini-batch is ln(vocabulary)
         assert abs(runs[0][0][0] - np.log(cfg.classes)) < 0.1 * np.log(cfg.classes)
+
+
+def test_gpt2_small_pipeline_against_the_oracle():
+    """The configuration bench.py times -- GPT-2-small, K = 4 stages on 4 streams, N = 8 micro-batches -- for two
+    mini-batches against the oracle's pipeline at full size: the version log bit for bit, both losses and the final
+    weights within the bf16 bar, the total weight change of every tensor in direction and L2 norm (section "Work
+    Scheduling"; update rule of TiMePReSt).  The second mini-batch's forward passes already run on updated weights
+    of the later stages, and its backward passes on the weights after the first update."""
+    from tests.test_gpu_pipeline import _compare
+    from workloads import get_config
+    cfg = get_config("gpt2_small_bf16")
+    losses = _compare(cfg, 2)
+    assert all(l == l for l in losses)
