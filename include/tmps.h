@@ -163,6 +163,18 @@ int tmps_stage_set_version(tmps_stage* stage, long version);
 int tmps_forward_micro(tmps_stage* stage, int slot, const void* x, void* y, const int32_t* labels,
                        float* loss_out, void* hip_stream);
 
+/* For callers that cannot allocate device memory for a workspace -- code under HIP stream capture, tight serving
+ * loops, harnesses that forbid hipMalloc: tmps_forward_micro with the fp32 workspace of its contractions (the
+ * partial sums of k-split GEMMs, which tmps_forward_micro keeps in the stage's `scratch` region) in a fixed array of
+ * TMPS_STATIC_SCRATCH_BYTES that is part of the library's device code; every GPU the library runs on holds one copy
+ * of it until the process ends.  Same arguments, results (bit for bit) and errors as tmps_forward_micro; in addition
+ * TMPS_ECAP when the stage's forward pass needs a larger workspace (then nothing is launched).  The call allocates
+ * nothing, on the device or through any library.  All calls on one GPU share that GPU's array: two calls whose
+ * kernels can overlap there (different streams, no dependency between them) race; calls on one stream do not. */
+#define TMPS_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int tmps_forward_micro_static(tmps_stage* stage, int slot, const void* x, void* y, const int32_t* labels,
+                              float* loss_out, void* hip_stream);
+
 /* The single backward pass of a mini-batch (section "Challenge 1", Solution): slots must be the
  * n_micro slots g*N .. g*N+N-1 of one group, all filled.  dy (device, M = N*micro_batch rows of
  * the stage output shape, gradient dtype; NULL on the last stage, whose error signal is the

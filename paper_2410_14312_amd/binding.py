@@ -49,6 +49,7 @@ EXPORTS = {
                                         C.c_void_p]),
     "tmps_schedule_shadow_versions": (C.c_int, [C.c_int, C.c_int, C.c_int]),
     "tmps_forward_micro": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tmps_forward_micro_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_backward": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_update": (C.c_int, [C.c_void_p, C.c_void_p]),
     "tmps_schedule_plan": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32), C.c_size_t]),
@@ -348,6 +349,12 @@ class Stage:
 
     def forward_micro(self, slot, x, y=None, labels=None, loss_out=None, stream=None):
         _check(lib().tmps_forward_micro(
+            self.handle, slot, C.c_void_p(x.data_ptr()), C.c_void_p(y.data_ptr()) if y is not None else None,
+            C.c_void_p(labels.data_ptr()) if labels is not None else None,
+            C.c_void_p(loss_out.data_ptr()) if loss_out is not None else None, C.c_void_p(self._stream(stream))))
+
+    def forward_micro_static(self, slot, x, y=None, labels=None, loss_out=None, stream=None):
+        _check(lib().tmps_forward_micro_static(
             self.handle, slot, C.c_void_p(x.data_ptr()), C.c_void_p(y.data_ptr()) if y is not None else None,
             C.c_void_p(labels.data_ptr()) if labels is not None else None,
             C.c_void_p(loss_out.data_ptr()) if loss_out is not None else None, C.c_void_p(self._stream(stream))))

@@ -66,6 +66,7 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
     st.asz = act_bytes(cfg->dtype);
     st.in_esize = st.asz;
     st.layers.clear();
+    st.ws_fwd_bytes = 0;
     const int mb = cfg->micro_batch;
     const int M = mb * cfg->n_micro;
     const int64_t rows_all = (int64_t)cfg->max_stash * mb;
@@ -110,7 +111,8 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                     any_skip = true;
                 }
                 const int64_t rf = (int64_t)mb * L.rps, rb = (int64_t)M * L.rps;
-                L.ws_elems = std::max({gemm_workspace_elems(rf, d[1], d[0], 0), gemm_workspace_elems(rb, d[0], d[1], 0),
+                L.ws_fwd_elems = gemm_workspace_elems(rf, d[1], d[0], 0);
+                L.ws_elems = std::max({L.ws_fwd_elems, gemm_workspace_elems(rb, d[0], d[1], 0),
                                        gemm_workspace_elems(d[1], d[0], rb, 1)});
                 break;
             }
@@ -125,7 +127,8 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
                 L.out_elems = (int64_t)c.Ho * c.Wo * c.Cout;
                 L.w_count = (int64_t)c.Cout * c.R * c.S * c.Cin; L.b_count = c.Cout;
                 const int64_t kf = (int64_t)c.R * c.S * c.Cin, kd = (int64_t)c.R * c.S * c.Cout;
-                L.ws_elems = std::max({gemm_workspace_elems((int64_t)mb * c.Ho * c.Wo, c.Cout, kf, 0),
+                L.ws_fwd_elems = gemm_workspace_elems((int64_t)mb * c.Ho * c.Wo, c.Cout, kf, 0);
+                L.ws_elems = std::max({L.ws_fwd_elems,
                                        gemm_workspace_elems((int64_t)M * c.H * c.W, c.Cin, kd, 0),
                                        gemm_workspace_elems(c.Cout, kf, (int64_t)M * c.Ho * c.Wo, 1)});
                 break;
@@ -223,6 +226,7 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
         // the gradient w.r.t. this layer's input lives in a gradient buffer (the loss layer's is kept in the stash)
         if (i > 0 && L.d.kind != TMPS_SOFTMAX_CE) gmax = std::max(gmax, L.in_elems);
         ws = std::max(ws, L.ws_elems);
+        st.ws_fwd_bytes = std::max(st.ws_fwd_bytes, L.ws_fwd_elems * 4);
         st.layers.push_back(L);
     }
     if (cfg->is_last && st.layers.back().d.kind != TMPS_SOFTMAX_CE)
@@ -399,6 +403,12 @@ static const void* layer_input(const tmps_stage* st, int li, const void* x0, int
 
 extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void* y, const int32_t* labels,
                                   float* loss_out, void* hip_stream) {
+    if (!st) return fail(TMPS_EINVAL, "stage or x is null");
+    return forward_with_workspace(st, slot, x, y, labels, loss_out, hip_stream, reinterpret_cast<float*>(st->scratch + st->ws_off));
+}
+
+int tmps::forward_with_workspace(tmps_stage* st, int slot, const void* x, void* y, const int32_t* labels, float* loss_out,
+                                 void* hip_stream, float* ws) {
     if (!st || !x) return fail(TMPS_EINVAL, "stage or x is null");
     if (slot < 0 || slot >= st->cfg.max_stash) return fail(TMPS_ESLOT, "slot %d outside 0..%d", slot, st->cfg.max_stash - 1);
     if (st->slot_used[slot]) return fail(TMPS_ESLOT, "slot %d is in use", slot);
@@ -408,7 +418,6 @@ extern "C" int tmps_forward_micro(tmps_stage* st, int slot, const void* x, void*
     const int dt = st->cfg.dtype;
     const int64_t row0 = (int64_t)slot * mb;
     const void* x0 = x;
-    float* ws = reinterpret_cast<float*>(st->scratch + st->ws_off);
     if (!st->cfg.borrow_input) {
         char* dst = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->in_esize;
         TMPS_RUN(kcCopy, s, hipMemcpyAsync(dst, x, (size_t)mb * st->in_elems * st->in_esize, hipMemcpyDeviceToDevice, s));

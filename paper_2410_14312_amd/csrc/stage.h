@@ -21,6 +21,7 @@ struct LayerRT {
     int in_b = -1;         // residual join: the second result it reads
     bool out_f32 = false;  // the logits layer (followed by softmax-CE) writes fp32
     size_t ws_elems = 0;   // fp32 workspace elements (split-k partial sums, reductions)
+    size_t ws_fwd_elems = 0;  // the part of it the forward pass needs
 };
 
 struct tmps_stage {
@@ -46,6 +47,7 @@ struct tmps_stage {
     size_t gbuf_off[8] = {0, 0, 0, 0, 0, 0, 0, 0}, gbuf_bytes = 0;  // gradient buffers (M rows each)
     size_t dxout_off[2] = {0, 0}, dxout_bytes = 0;  // boundary gradient buffers used by the scheduler
     size_t ws_off = 0;
+    size_t ws_fwd_bytes = 0;  // fp32 workspace bytes a forward pass needs (the k-split partial sums of its contractions)
     std::vector<char> slot_used;
     std::vector<const void*> slot_x;
     long version = 0;
@@ -79,4 +81,7 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
 void* stage_dxout(tmps_stage* st, int which);
 // Per-row losses of a slot on the last stage.
 float* stage_row_loss(tmps_stage* st, int slot);
+// tmps_forward_micro with the fp32 workspace of its contractions (st->ws_fwd_bytes) given by the caller.
+int forward_with_workspace(tmps_stage* st, int slot, const void* x, void* y, const int32_t* labels, float* loss_out,
+                           void* hip_stream, float* ws);
 }  // namespace tmps
