@@ -349,7 +349,7 @@ def main():
             ost.backward(list(range(cfg.N)), dy)
             ost.update()
             dc = time.perf_counter() - t1
-            cpu = {"value": cfg.M / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            cpu = {"value": cfg.M / dc, "unit": "samples/s", "cores": cores, "kind": "oracle", "stage": si,
                    "sample": "one training step (N forward passes, backward pass, update) of stage %d of %d alone (its "
                              "layers only: samples/s of that stage, not of the whole pipeline) through the numpy fp64 "
                              "oracle (%.1f s)" % (si, cfg.K, dc)}
@@ -364,7 +364,7 @@ def main():
             t1 = time.perf_counter()
             opipe.run(cfg, params, distinct[:n_cpu])
             dc = time.perf_counter() - t1
-            cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            cpu = {"value": cfg.M * n_cpu / dc, "unit": "samples/s", "cores": cores, "kind": "oracle", "stage": None,
                    "sample": "%d mini-batches of the same workload through the numpy fp64 oracle pipeline (%.1f s)" % (n_cpu, dc)}
 
     # Every stage's own training step with the device to itself (one stream, no other stage's kernels).
@@ -405,12 +405,22 @@ def main():
                            if ocfg.dtype == "bf16" else None,
                            "stage_steps": stage_step_rates(T, ocfg, oparams, 20)})
 
+    if cpu is not None:
+        if cpu.get("stage") is not None and stage_steps:
+            # like for like: the same stage's step on the GPU, the device to itself
+            cpu["gpu_same_sample"] = {"value": stage_steps[cpu["stage"]]["samples_per_s"], "unit": "samples/s",
+                                      "what": "training step of stage %d alone on the GPU (stage_steps[%d])" % (cpu["stage"], cpu["stage"])}
+        elif cpu.get("stage") is None:
+            cpu["gpu_same_sample"] = {"value": value, "unit": "samples/s", "what": "the whole pipeline (value)"}
     out = {
-        "metric": "training samples/sec (all K stages, nF1B) on 1 MI355X",
+        # every stage of the pipeline processes every sample, so the pipeline's rate IS each stage's rate in it; the
+        # rate each stage reaches with the device to itself is under stage_steps
+        "metric": "training samples/sec per stage on 1 MI355X; MFMA util % of bf16 peak",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "mini_batch": cfg.M, "micro_batches": cfg.N, "stages": cfg.K,
+                   "measured": "K stages in nF1B order on K streams of one GPU (every stage processes every sample)",
                    "version_difference": T.version_diff_simulated(cfg.K, cfg.N),
                    "weight_policy": "vertical weight stashing" if args.vertical_sync else "in place",
                    "shadow_weight_bytes": shadow_bytes,

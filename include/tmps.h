@@ -181,7 +181,8 @@ int tmps_forward_micro_static(tmps_stage* stage, int slot, const void* x, void* 
  * gradient of the average of the N micro-batch losses) is propagated through the layers in
  * reverse using the stashed activations and the weights AS THEY ARE NOW; weight gradients are
  * summed over the N micro-batches into `state`; dx (device, M rows of the input shape; may be
- * NULL) receives the gradient w.r.t. the stage input.  Frees the slots. */
+ * NULL) receives the gradient w.r.t. the stage input.  Frees the slots, also when the pass fails after its arguments
+ * were accepted (TMPS_EUNSUPPORTED, TMPS_EHIP): the gradients are then incomplete and tmps_update must not follow. */
 int tmps_backward(tmps_stage* stage, const int* slots, int n_slots, const void* dy, void* dx,
                   void* hip_stream);
 
@@ -238,7 +239,10 @@ int tmps_version_diff_simulated(int W, int N);
  * (int32 tokens when it starts with an embedding); labels: device int32, n_minibatches*M times the rows
  * per sample of the loss layer.  losses_out: device float[n_minibatches], the mean
  * of the N micro-batch losses.  version_log_out: host int32[7 * tasks] as tmps_schedule_plan,
- * except that field 5 is read from the stage objects as the tasks are issued; may be NULL.
+ * except that field 5 is read from the stage objects as the tasks are issued (minus the stage's version when the
+ * run started, so that a second run, or a run resumed from a checkpoint, logs the same numbers as the plan); may be NULL.
+ * If a task fails, the call still waits for the streams, frees the stash slots of every stage (the mini-batches in
+ * flight are lost; updates already applied stay) and returns the first error.
  * Cross-stage dependencies are HIP events.  Each stage's tasks are issued by a host thread of its
  * own (one per stage, joined before the call returns; set the environment variable
  * TMPS_ISSUE_THREADS=0 to issue everything from the calling thread).  The call returns after all K

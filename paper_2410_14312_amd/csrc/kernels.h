@@ -101,7 +101,7 @@ hipError_t attention_backward(int dtype, const void* qkv, const void* o, const v
 size_t attention_workspace_elems(int B, int S, int H);
 
 // y[row] = wte[tok[row]] + wpe[row % S] (tables in the contraction dtype), and the table gradients
-// (fp32; dwte by atomic adds after clearing it, dwpe summed over the batch).
+// (fp32; dwte cleared, then every occurring token's rows of dy added in row order, no atomic adds; dwpe summed over the batch).
 hipError_t embedding_forward(int dtype, const int32_t* tok, const void* wte, const void* wpe, void* y,
                              int64_t rows, int S, int D, int vocab, hipStream_t s);
 hipError_t embedding_backward(int dtype, const int32_t* tok, const void* dy, float* dwte, float* dwpe,

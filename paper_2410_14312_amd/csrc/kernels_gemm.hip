@@ -234,10 +234,10 @@ static bool g3_forward_ok(int64_t M, int64_t N, int64_t K) {
     return K % 64 == 0 && K >= 128 && N % 8 == 0 && g3_tiles(M, N) >= 192 && (int64_t)cdiv(N, 256) * 256 * 3 <= N * 4;
 }
 
-static G3Plan g3_plan(int M, int N, int K, int slices) {
+static G3Plan g3_plan(int M, int N, int K, int slices, int bm = kG3Tile, int bn = kG3Tile) {
     G3Plan p;
-    p.tiles_m = cdiv(M, kG3Tile);
-    p.tiles_n = cdiv(N, kG3Tile);
+    p.tiles_m = cdiv(M, bm);
+    p.tiles_n = cdiv(N, bn);
     int per = cdiv(cdiv(K, slices), 64) * 64;
     p.k_per_slice = per;
     p.slices = cdiv(K, per);
@@ -249,15 +249,22 @@ static G3Plan g3_plan(int M, int N, int K, int slices) {
 }
 
 // 256 x 256 x 64 tiles, 8 waves (2 x 4), two LDS stages: the configuration that did best on every large shape tried.
+template <int BM, int BN, int WM, int WN, int NS, int PER_CU, bool AKC, bool BKC, bool ROWSUM, class Epi>
+static hipError_t launch3_inst(int kc, const G3Operand<AKC>& A, const G3Operand<BKC>& B, const Epi& epi, int M, int N, int K,
+                               const G3Plan& plan, hipStream_t s) {
+    constexpr int lds = gemm3_lds_bytes<BM, BN, 64, NS>();
+    auto kern = gemm3_kernel<BM, BN, 64, WM, WN, NS, AKC, BKC, ROWSUM, Epi>;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    const int slots = compute_units() * PER_CU;
+    const int grid = plan.units < slots ? plan.units : slots;
+    return launch_timed(kc, kern, dim3(grid), dim3(64 * WM * WN), lds, s, A, B, epi, M, N, K, plan);
+}
+
 template <bool AKC, bool BKC, bool ROWSUM, class Epi>
 static hipError_t launch3(int kc, const G3Operand<AKC>& A, const G3Operand<BKC>& B, const Epi& epi, int M, int N, int K,
                           const G3Plan& plan, hipStream_t s) {
-    constexpr int lds = gemm3_lds_bytes<256, 256, 64, 2>();
-    auto kern = gemm3_kernel<256, 256, 64, 2, 4, 2, AKC, BKC, ROWSUM, Epi>;
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (attr != hipSuccess) return attr;
-    const int grid = plan.units < compute_units() ? plan.units : compute_units();
-    return launch_timed(kc, kern, dim3(grid), dim3(512), lds, s, A, B, epi, M, N, K, plan);
+    return launch3_inst<256, 256, 2, 4, 2, 1, AKC, BKC, ROWSUM>(kc, A, B, epi, M, N, K, plan, s);
 }
 
 // ---- element-wise fallbacks ------------------------------------------------------------------
@@ -303,6 +310,16 @@ static hipError_t dense_forward_as(int kc, int dtype, const void* x, const void*
                                    int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
     if (dtype == kBF16) {
         const bool fast = (Din % 8 == 0) && aligned16(x) && aligned16(w);
+        static const int x_f128 = getenv("TMPS_X_F128") ? atoi(getenv("TMPS_X_F128")) : 0;
+        if (x_f128 && fast && Din % 64 == 0 && Dout % 8 == 0 && B <= 2048 && aligned16(y) && aligned16(bias) && aligned16(res) && aligned16(zout) && !out_f32) {
+            G3Operand<true> A{(const bf16_t*)x, B, Din};
+            G3Operand<true> Bv{(const bf16_t*)w, Dout, Din};
+            const G3Plan plan = g3_plan(B, Dout, Din, 1, 128, 128);
+            EpiBiasAct<bf16_t> epi{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout};
+            if (x_f128 == 3) return launch3_inst<128, 128, 2, 2, 3, 1, true, true, false>(kc, A, Bv, epi, B, Dout, Din, plan, s);
+            if (x_f128 == 4) return launch3_inst<128, 128, 2, 2, 4, 1, true, true, false>(kc, A, Bv, epi, B, Dout, Din, plan, s);
+            return launch3_inst<128, 128, 2, 2, 2, 2, true, true, false>(kc, A, Bv, epi, B, Dout, Din, plan, s);
+        }
         if (fast && g3_forward_ok(B, Dout, Din) && aligned16(y) && aligned16(bias) && aligned16(res) && aligned16(zout)) {
             G3Operand<true> A{(const bf16_t*)x, B, Din};
             G3Operand<true> Bv{(const bf16_t*)w, Dout, Din};
@@ -337,6 +354,14 @@ static hipError_t dense_dgrad_as(int kc, int dtype, const void* dy, const void* 
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode, (const bf16_t*)add};
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(w);
+        static const int x_d2 = getenv("TMPS_X_D2") ? atoi(getenv("TMPS_X_D2")) : 0;
+        if (x_d2 && fast && Dout % 64 == 0 && B >= 4096 && aligned16(dx) && aligned16(mask) && aligned16(add)) {
+            G3Operand<true> A{(const bf16_t*)dy, B, Dout};
+            G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
+            if (x_d2 == 1) return launch3_inst<256, 128, 2, 2, 2, 1, true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1, 256, 128), s);
+            if (x_d2 == 2) return launch3_inst<256, 128, 2, 2, 3, 1, true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1, 256, 128), s);
+            if (x_d2 == 3) return launch3_inst<128, 256, 1, 4, 3, 1, true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1, 128, 256), s);
+        }
         if (fast && g3_forward_ok(B, Din, Dout) && aligned16(dx) && aligned16(mask) && aligned16(add)) {
             G3Operand<true> A{(const bf16_t*)dy, B, Dout};
             G3Operand<false> Bv{(const bf16_t*)w, Din, Din};

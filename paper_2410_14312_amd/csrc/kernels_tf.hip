@@ -379,17 +379,68 @@ __global__ void embedding_bwd_pos_kernel(const T* __restrict__ dy, float* __rest
     dwpe[i] = a;
 }
 
+// Token-table gradient, deterministic: dwte[t] = sum of the rows of dy whose token is t, added in row order.  One wave
+// per row.  The wave of a token's FIRST row (no earlier row has the token: a scan of the rows before it) collects the
+// later rows with the same token (a scan of the rows after it, 256 tokens per step) and adds them up in increasing row
+// order; every other wave leaves.  No atomic adds, so the sum does not depend on which wave arrives first; rows of
+// tokens that do not occur are zero (the table gradient is cleared before).
 template <typename T>
 __global__ __launch_bounds__(256) void embedding_bwd_tok_kernel(const int32_t* __restrict__ tok, const T* __restrict__ dy,
                                                                 float* __restrict__ dwte, int64_t rows, int D, int vocab) {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    constexpr int CAP = 128;   // later occurrences kept in LDS per wave; a token with more is summed by rescanning
+    __shared__ int later[4][CAP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
     if (row >= rows) return;
     const int t = tok[row];
     if (t < 0 || t >= vocab) return;
+    for (int64_t base = 0; base < row; base += 256) {
+        bool hit = false;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t j = base + u * 64 + lane;
+            hit |= j < row && tok[j] == t;
+        }
+        if (__ballot(hit)) return;   // not the first row of this token (uniform over the wave)
+    }
+    int n = 0;
+    for (int64_t base = row + 1; base < rows; base += 256) {
+        int v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t j = base + u * 64 + lane;
+            v[u] = j < rows ? tok[j] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            unsigned long long m = __ballot(v[u] == t);
+            while (m) {
+                const int b = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                if (n < CAP && lane == 0) later[wave][n] = (int)(base + u * 64 + b);
+                ++n;
+            }
+        }
+    }
+    // lane 0 wrote the list, every lane reads it: LDS operations of one wave complete in order; keep the compiler
+    // from moving the reads up
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
     float* dst = dwte + (int64_t)t * D;
-    const T* g = dy + row * D;
-    for (int i = lane; i < D; i += 64) atomicAdd(dst + i, to_f32(g[i]));
+    if (n <= CAP) {
+        for (int i = lane; i < D; i += 64) {
+            float a = to_f32(dy[row * D + i]);
+            for (int k = 0; k < n; ++k) a += to_f32(dy[(int64_t)later[wave][k] * D + i]);
+            dst[i] = a;
+        }
+    } else {
+        for (int i = lane; i < D; i += 64) {
+            float a = to_f32(dy[row * D + i]);
+            for (int64_t j = row + 1; j < rows; ++j)
+                if (tok[j] == t) a += to_f32(dy[j * D + i]);
+            dst[i] = a;
+        }
+    }
 }
 
 hipError_t embedding_forward(int dtype, const int32_t* tok, const void* wte, const void* wpe, void* y, int64_t rows, int S,

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 #include <thread>
@@ -21,20 +22,16 @@ using namespace tmps;
 
 namespace {
 
-struct EventPool {
-    std::vector<hipEvent_t> ev;
-    ~EventPool() {
-        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+// The events that stand for messages between workers are kept by the stage that records them (tmps_stage::events,
+// destroyed with the stage): a second run on the same stages creates none.
+int grow_events(tmps_stage* st, size_t n) {
+    while (st->events.size() < n) {
+        hipEvent_t e;
+        TMPS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        st->events.push_back(e);
     }
-    int grow(size_t n) {
-        while (ev.size() < n) {
-            hipEvent_t e;
-            TMPS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-            ev.push_back(e);
-        }
-        return TMPS_OK;
-    }
-};
+    return TMPS_OK;
+}
 
 struct RunCtx {
     bool vsync = false;              // forward passes read the weight version they are tagged with
@@ -48,7 +45,6 @@ struct RunCtx {
     int32_t* log;
     size_t asz, total_micro, n_fwd_ev;
     std::vector<int> groups;
-    EventPool pool;
     std::vector<std::atomic<unsigned char>> recorded;
     std::atomic<int> err{TMPS_OK};
     char err_text[512];
@@ -56,6 +52,12 @@ struct RunCtx {
 
     size_t fwd_ev(int s, size_t q) const { return (size_t)s * total_micro + q; }
     size_t bwd_ev(int s, int b0) const { return n_fwd_ev + (size_t)s * n_minibatches + b0; }
+    // the event behind an index: stage s keeps its forward events first, then its backward events
+    hipEvent_t event(size_t e) const {
+        if (e < n_fwd_ev) return stages[e / total_micro]->events[e % total_micro];
+        const size_t r = e - n_fwd_ev;
+        return stages[r / n_minibatches]->events[total_micro + r % n_minibatches];
+    }
 
     // Block until the producer thread has recorded event e (or a thread failed), then make stream s wait for it.
     int wait_for(size_t e, hipStream_t s) {
@@ -63,11 +65,11 @@ struct RunCtx {
             if (err.load(std::memory_order_relaxed) != TMPS_OK) return TMPS_EINVAL;
             std::this_thread::yield();
         }
-        TMPS_HIP(hipStreamWaitEvent(s, pool.ev[e], 0));
+        TMPS_HIP(hipStreamWaitEvent(s, event(e), 0));
         return TMPS_OK;
     }
     int record(size_t e, hipStream_t s) {
-        TMPS_HIP(hipEventRecord(pool.ev[e], s));
+        TMPS_HIP(hipEventRecord(event(e), s));
         recorded[e].store(1, std::memory_order_release);
         return TMPS_OK;
     }
@@ -90,7 +92,7 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
     if (c.log) {
         int32_t* o = c.log + 7 * ti;
         o[0] = k.t; o[1] = k.stage; o[2] = k.kind; o[3] = k.b; o[4] = k.j;
-        o[5] = (int32_t)st->version; o[6] = k.net_version;
+        o[5] = (int32_t)(st->version - c.base_version[k.stage]); o[6] = k.net_version;
     }
     const int group = b0 % c.groups[k.stage];
     int rc;
@@ -178,8 +180,10 @@ static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, co
     c.groups.resize(K);
     for (int s = 0; s < K; ++s) c.groups[s] = stages[s]->cfg.max_stash / N;
     const size_t n_events = c.n_fwd_ev + (size_t)K * n_minibatches;
-    int rc = c.pool.grow(n_events);
-    if (rc != TMPS_OK) return rc;
+    for (int s = 0; s < K; ++s) {
+        int rc = grow_events(stages[s], c.total_micro + (size_t)n_minibatches);
+        if (rc != TMPS_OK) return rc;
+    }
     c.recorded = std::vector<std::atomic<unsigned char>>(n_events);
     for (auto& f : c.recorded) f.store(0, std::memory_order_relaxed);
 
@@ -223,7 +227,14 @@ static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, co
     }
     const auto t1 = std::chrono::steady_clock::now();
     for (int s = 0; s < K; ++s) TMPS_HIP(hipStreamSynchronize((hipStream_t)hip_streams[s]));
-    if (c.err.load() != TMPS_OK) return fail(c.err.load(), "%s", c.err_text);
+    if (c.err.load() != TMPS_OK) {
+        // the mini-batches in flight are lost: free their stash slots, so that the stages can run again
+        for (int s = 0; s < K; ++s) {
+            std::fill(stages[s]->slot_used.begin(), stages[s]->slot_used.end(), 0);
+            std::fill(stages[s]->slot_x.begin(), stages[s]->slot_x.end(), nullptr);
+        }
+        return fail(c.err.load(), "%s", c.err_text);
+    }
     if (report) {
         const auto t2 = std::chrono::steady_clock::now();
         fprintf(stderr, "tmps_schedule_run: %d mini-batches, host issue %.3f ms, until idle %.3f ms\n", n_minibatches,

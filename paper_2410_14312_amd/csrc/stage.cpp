@@ -543,6 +543,17 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
     } else {
         x0 = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->in_esize;
     }
+    // The arguments are accepted.  From here on the slots are given up whatever happens: a pass that fails midway
+    // has written part of the gradients, and the stage must be able to take the next mini-batch.
+    struct FreeSlots {
+        tmps_stage* st; int g0, N;
+        ~FreeSlots() {
+            for (int j = 0; j < N; ++j) {
+                st->slot_used[g0 + j] = 0;
+                st->slot_x[g0 + j] = nullptr;
+            }
+        }
+    } free_slots{st, g0, N};
 
     // Gradients are kept per result: grads[t + 1] is the gradient w.r.t. the result of layer t (t = -1: the stage
     // input).  Layers are visited last to first; every layer that reads a result contributes to its gradient: the
@@ -769,11 +780,7 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         if (L.d.kind == TMPS_RESADD && L.in_b >= 0 && remaining[L.in_b + 1] == 0 && st->layers[L.in_b].act != 0)
             return fail(TMPS_EUNSUPPORTED, "a residual connection must start at a result that another, earlier layer reads too");
     }
-    for (int j = 0; j < N; ++j) {
-        st->slot_used[g0 + j] = 0;
-        st->slot_x[g0 + j] = nullptr;
-    }
-    return TMPS_OK;
+    return TMPS_OK;   // (free_slots releases the group)
 }
 
 extern "C" int tmps_update(tmps_stage* st, void* hip_stream) {

@@ -51,6 +51,10 @@ struct tmps_stage {
     std::vector<char> slot_used;
     std::vector<const void*> slot_x;
     long version = 0;
+    std::vector<hipEvent_t> events;   // tmps_schedule_run: what this worker sends to its neighbours (kept between runs)
+    ~tmps_stage() {
+        for (hipEvent_t e : events) (void)hipEventDestroy(e);
+    }
     // vertical weight stashing: copies of the `params` region as it was after earlier updates
     char* shadow = nullptr;
     int shadow_n = 0;                 // copies the caller's region holds

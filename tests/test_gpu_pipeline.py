@@ -154,7 +154,9 @@ def test_resume_from_stage_checkpoints(name, tmp_path):
     losses_b, log_b = b.run(batches[6:])
     assert losses_b == losses_a
     assert [st.version() for st in b.stages] == [9] * cfg.K
-    assert int(log_b[:, 5].min()) == 6       # the version log goes on from the restored counters
+    # the version log counts from the run's start, as the plan and the oracle's resumed run do
+    from paper_2410_14312_amd import schedule_plan
+    assert np.array_equal(log_b, schedule_plan(cfg.K, cfg.N, 3))
     for s in range(cfg.K):
         for pa, pb in zip(a.get_params(s), b.get_params(s)):
             for k in pa:
@@ -210,3 +212,43 @@ def test_vertical_weight_stashing_deep_pipeline_and_errors():
     x = st.prepare_input(make_batch(cfg, 0)[0][:cfg.micro])
     with pytest.raises(TmpsError):
         st.forward_micro_at(5, 0, x)
+
+
+def test_second_run_and_failed_run_on_the_same_stages():
+    """A second tmps_schedule_run on the same stages logs the same numbers as the plan (versions count from the run's
+    start) and continues the oracle's trajectory; a run is refused while a stage still holds a forwarded micro-batch."""
+    import torch
+    from paper_2410_14312_amd import Pipeline, TmpsError, schedule_plan
+    cfg = get_config("tiny_mlp_f32")
+    params = init_params(cfg)
+    batches = [make_batch(cfg, i) for i in range(6)]
+    ref = pipeline.run(cfg, params, batches)
+    pipe = Pipeline(cfg, params)
+    l1, log1 = pipe.run(batches[:3])
+    l2, log2 = pipe.run(batches[3:])
+    plan = schedule_plan(cfg.K, cfg.N, 3)
+    assert np.array_equal(log1, plan) and np.array_equal(log2, plan)
+    assert [st.version() for st in pipe.stages] == [6] * cfg.K
+    # the two runs drain the pipeline in between, so their trajectory is that of two oracle runs in a row
+    mid = pipeline.run(cfg, params, batches[:3])
+    ref2 = pipeline.run(cfg, [[dict(p) for p in st.params] for st in mid["stages"]], batches[3:],
+                        momentum=[st.bufs for st in mid["stages"]], versions=[3] * cfg.K)
+    for a, b in zip(l1 + l2, mid["losses"] + ref2["losses"]):
+        assert abs(a - b) <= 1e-4 * abs(b)
+    del ref
+    # a run is refused while a stage holds a forwarded micro-batch, and runs again once that mini-batch is done
+    x, y = pipe.upload(batches[:2])
+    losses = torch.zeros(2, dtype=torch.float32, device=pipe.device)
+    last = pipe.stages[1]
+    xin = torch.zeros(cfg.M, last.in_elems, device=pipe.device)
+    last.forward_micro(0, xin[:cfg.micro], labels=y[:cfg.micro])
+    with pytest.raises(TmpsError) as e:
+        pipe.run_device(x, y, 2, losses)
+    assert e.value.code == -4
+    torch.cuda.synchronize()
+    for j in range(1, cfg.N):
+        last.forward_micro(j, xin[j * cfg.micro:(j + 1) * cfg.micro], labels=y[j * cfg.micro:(j + 1) * cfg.micro])
+    last.backward(list(range(cfg.N)), dx=torch.empty(cfg.M * last.in_elems, device=pipe.device))
+    torch.cuda.synchronize()
+    log3 = pipe.run_device(x, y, 2, losses)
+    assert np.array_equal(log3, schedule_plan(cfg.K, cfg.N, 2))

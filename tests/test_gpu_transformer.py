@@ -51,6 +51,34 @@ def test_embedding_block_stage(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("vocab,s,micro,N", [(3, 64, 4, 2),      # every token some 170 times: more rows than the in-wave list holds
+                                             (40, 48, 8, 2),     # a dozen rows per token
+                                             (5000, 16, 4, 2)])  # most tokens absent, a few twice
+def test_embedding_gradient_with_repeated_tokens(dtype, vocab, s, micro, N):
+    # the token-table gradient adds the rows of a token in row order (no atomic adds): compared with the oracle, and
+    # bit-identical between two passes over the same mini-batch
+    import torch
+    from paper_2410_14312_amd import Stage
+    from tests.test_gpu_stage import _params
+    d = 64
+    specs = [embedding(vocab, s, d), linear(d, 32, False, rows=s)]
+    run_stage_case(specs, dtype, micro, N, seed=vocab + s)
+    rng = np.random.default_rng(7)
+    st = Stage(specs, dtype, micro, N, N, 0.05, 0.9, device="cuda:0")
+    st.set_params(_params(specs, rng))
+    tok = torch.from_numpy(rng.integers(0, vocab, (micro * N, s)).astype(np.int32)).to(st.device)
+    dy = torch.randn(micro * N, s * 32, device=st.device).to(st.act_dtype)
+    seen = []
+    for _ in range(2):
+        for j in range(N):
+            st.forward_micro(j, tok[j * micro:(j + 1) * micro])
+        st.backward(list(range(N)), dy=dy)
+        torch.cuda.synchronize()
+        seen.append(st.get_grads()[0]["w"].copy())
+    assert np.array_equal(seen[0], seen[1])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("borrow", [False, True])
 def test_block_head_and_sequence_loss(dtype, borrow):
     s, d, vocab = 20, 64, 90
