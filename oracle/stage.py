@@ -103,12 +103,17 @@ class Stage:
         return (a, loss) if self.is_last else a
 
     # -- one backward pass over the mini-batch --------------------------------------------
-    def backward(self, slots, dy=None):
+    def backward(self, slots, dy=None, version=None):
         """dy: gradient w.r.t. the stage output for all M samples (rows in slot order); None on
         the last stage.  Returns the gradient w.r.t. the stage input, same row order.  Consumes
-        the slots.  Parameter gradients are summed over the micro-batches."""
+        the slots.  Parameter gradients are summed over the micro-batches.
+        version: None = differentiate at the weights as they are now (TiMePReSt).  A number = at this stage's
+        weights as they were after that many updates, kept by keep_versions: horizontal weight stashing, the
+        policy of the PipeDream baseline (related work, the update rule of PipeDream), where a backward pass
+        reads the version its forward pass read."""
         if len(slots) != self.N:
             raise ValueError("a backward pass covers the N micro-batches of one mini-batch")
+        weights = self.params if version is None or version == self.version else self.history[version]
         micro = self.M // self.N
         acc = [None] * len(self.specs)
         dxs = []
@@ -130,7 +135,7 @@ class Stage:
                 give(n_l - 1, dy[i * micro:(i + 1) * micro])
             held = {}   # layer index -> gradient of a residual connection that joins that layer's input
             for li in range(n_l - 1, -1, -1):
-                spec, p, c = self.specs[li], self.params[li], caches[li]
+                spec, p, c = self.specs[li], weights[li], caches[li]
                 k = spec["kind"]
                 dw = db = None
                 g = grad_of.pop(li, None)

@@ -132,6 +132,11 @@ struct G3Plan {
     int units;                                  // tiles_m * tiles_n * slices
     int col_major;                              // consecutive units walk down a column of tiles (share B) instead of along a row (share A)
     FastDiv d_tn, d_tiles;                      // by tiles_n (tiles_m when col_major) and by tiles_m * tiles_n
+    // gm > 0: the tiles of a slice are numbered block by block, a block being gm x gn tiles (gm * gn = 32, the
+    // workgroups of one XCD in a round; gm divides tiles_m, gn divides tiles_n): the 32 tiles an XCD works on at a time
+    // then share gm + gn operand panels instead of 1 + 32, and most LDS fills find their lines in the XCD's L2.
+    int gm, gn;
+    FastDiv d_blk, d_gn, d_nbn;                 // by 32, by gn, by tiles_n / gn
 };
 
 // ROWSUM: units of the first tile column also sum A over k (bias gradient of a weight-gradient GEMM, whose
@@ -167,7 +172,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     auto unit_coords = [&](int u, int& tm, int& tn, int& z) {
         uint32_t zz, rem, m_, n_;
         plan.d_tiles.divmod((uint32_t)u, zz, rem);
-        if (plan.col_major) plan.d_tn.divmod(rem, n_, m_);
+        if (plan.gm) {
+            uint32_t blk, w, bm, bn, i, j;
+            plan.d_blk.divmod(rem, blk, w);
+            plan.d_nbn.divmod(blk, bm, bn);
+            plan.d_gn.divmod(w, i, j);
+            m_ = bm * plan.gm + i;
+            n_ = bn * plan.gn + j;
+        } else if (plan.col_major) plan.d_tn.divmod(rem, n_, m_);
         else plan.d_tn.divmod(rem, m_, n_);
         z = (int)zz; tm = (int)m_; tn = (int)n_;
     };

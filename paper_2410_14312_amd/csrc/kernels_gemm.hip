@@ -245,6 +245,24 @@ static G3Plan g3_plan(int M, int N, int K, int slices, int bm = kG3Tile, int bn 
     p.col_major = N > M ? 1 : 0;   // the XCDs split the operand with more rows between them and each reads the other one whole
     p.d_tn = FastDiv(p.col_major ? p.tiles_m : p.tiles_n);
     p.d_tiles = FastDiv(p.tiles_m * p.tiles_n);
+    // Blocks of 32 tiles for outputs wide enough that a run of 32 tiles would span few rows and all columns (or the
+    // other way round): the squarest block whose sides divide the tile counts.
+    p.gm = p.gn = 0;
+    if (p.tiles_m >= 8 && p.tiles_n >= 8) {
+        for (int gn : {4, 8, 2, 16}) {
+            const int gm = 32 / gn;
+            if (p.tiles_n % gn == 0 && p.tiles_m % gm == 0) {
+                p.gm = gm;
+                p.gn = gn;
+                break;
+            }
+        }
+    }
+    if (p.gm) {
+        p.d_blk = FastDiv(32);
+        p.d_gn = FastDiv(p.gn);
+        p.d_nbn = FastDiv(p.tiles_n / p.gn);
+    }
     return p;
 }
 
@@ -310,16 +328,6 @@ static hipError_t dense_forward_as(int kc, int dtype, const void* x, const void*
                                    int Dout, int relu, int out_f32, const void* res, void* zout, float* ws, hipStream_t s) {
     if (dtype == kBF16) {
         const bool fast = (Din % 8 == 0) && aligned16(x) && aligned16(w);
-        static const int x_f128 = getenv("TMPS_X_F128") ? atoi(getenv("TMPS_X_F128")) : 0;
-        if (x_f128 && fast && Din % 64 == 0 && Dout % 8 == 0 && B <= 2048 && aligned16(y) && aligned16(bias) && aligned16(res) && aligned16(zout) && !out_f32) {
-            G3Operand<true> A{(const bf16_t*)x, B, Din};
-            G3Operand<true> Bv{(const bf16_t*)w, Dout, Din};
-            const G3Plan plan = g3_plan(B, Dout, Din, 1, 128, 128);
-            EpiBiasAct<bf16_t> epi{(bf16_t*)y, bias, Dout, relu, (const bf16_t*)res, (bf16_t*)zout};
-            if (x_f128 == 3) return launch3_inst<128, 128, 2, 2, 3, 1, true, true, false>(kc, A, Bv, epi, B, Dout, Din, plan, s);
-            if (x_f128 == 4) return launch3_inst<128, 128, 2, 2, 4, 1, true, true, false>(kc, A, Bv, epi, B, Dout, Din, plan, s);
-            return launch3_inst<128, 128, 2, 2, 2, 2, true, true, false>(kc, A, Bv, epi, B, Dout, Din, plan, s);
-        }
         if (fast && g3_forward_ok(B, Dout, Din) && aligned16(y) && aligned16(bias) && aligned16(res) && aligned16(zout)) {
             G3Operand<true> A{(const bf16_t*)x, B, Din};
             G3Operand<true> Bv{(const bf16_t*)w, Dout, Din};
@@ -354,14 +362,6 @@ static hipError_t dense_dgrad_as(int kc, int dtype, const void* dy, const void* 
     if (dtype == kBF16) {
         EpiMask<bf16_t, bf16_t> epi{(bf16_t*)dx, (const bf16_t*)mask, Din, mask_mode, (const bf16_t*)add};
         const bool fast = (Dout % 8 == 0) && (Din % 8 == 0) && aligned16(dy) && aligned16(w);
-        static const int x_d2 = getenv("TMPS_X_D2") ? atoi(getenv("TMPS_X_D2")) : 0;
-        if (x_d2 && fast && Dout % 64 == 0 && B >= 4096 && aligned16(dx) && aligned16(mask) && aligned16(add)) {
-            G3Operand<true> A{(const bf16_t*)dy, B, Dout};
-            G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
-            if (x_d2 == 1) return launch3_inst<256, 128, 2, 2, 2, 1, true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1, 256, 128), s);
-            if (x_d2 == 2) return launch3_inst<256, 128, 2, 2, 3, 1, true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1, 256, 128), s);
-            if (x_d2 == 3) return launch3_inst<128, 256, 1, 4, 3, 1, true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1, 128, 256), s);
-        }
         if (fast && g3_forward_ok(B, Din, Dout) && aligned16(dx) && aligned16(mask) && aligned16(add)) {
             G3Operand<true> A{(const bf16_t*)dy, B, Dout};
             G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
