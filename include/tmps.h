@@ -211,6 +211,30 @@ int tmps_schedule_run_vsync(tmps_stage** stages, int K, int N, int n_minibatches
                             const int32_t* labels, void** hip_streams, float* losses_out,
                             int32_t* version_log_out);
 
+/* ---- the comparison system: PipeDream-style training (related work; the update rule of PipeDream) ----
+ *
+ * Every batch makes its own forward pass and its own backward pass, workers take them in 1F1B order, and on every
+ * worker the backward pass of a batch reads the weights its forward pass read there (horizontal weight stashing); the
+ * gradient is applied to the worker's current weights.  Built on the calls above with n_micro = 1 (a batch is a
+ * mini-batch of one micro-batch) and on the kept versions of tmps_stage_set_shadow:
+ *
+ * tmps_backward_at is tmps_backward differentiating at the stage's weights as they were after `version` updates (the
+ * live ones when that is the current version, a kept copy otherwise; TMPS_EINVAL if not kept); gradients go to the
+ * stage's gradient array as always, and the tmps_update that follows changes the live weights.
+ * tmps_schedule_plan_1f1b (host only): the 1F1B task list of W workers for n_batches, 7 int32 per task as
+ * tmps_schedule_plan, with micro-batch = -1, field 5 = the number of updates in the weights the task READS and field 6
+ * = the number of updates the worker had applied before the task.  Worker s (from 0) has at most W - s batches between
+ * their forward and backward pass and reaches back at most W - s - 1 versions.
+ * tmps_schedule_run_1f1b runs n_batches that way on K streams: stages[s] created with n_micro = 1, max_stash >= K - s,
+ * borrow_input = 1 for s > 0, and a shadow region of at least K - s - 1 versions (TMPS_ESTASH otherwise); inputs,
+ * labels, losses_out (one loss per batch) and the log as in tmps_schedule_run, fields 5 and 6 read from the stage
+ * objects as the tasks are issued. */
+int tmps_backward_at(tmps_stage* stage, long version, const int* slots, int n_slots, const void* dy, void* dx,
+                     void* hip_stream);
+int tmps_schedule_plan_1f1b(int W, int n_batches, int32_t* ops_out, size_t cap_ops);
+int tmps_schedule_run_1f1b(tmps_stage** stages, int K, int n_batches, const void* inputs, const int32_t* labels,
+                           void** hip_streams, float* losses_out, int32_t* version_log_out);
+
 /* In-place update (the update rule for TiMePReSt, with momentum): buf <- mu*buf + g,
  * w <- w - lr*buf on the fp32 master values, refreshes the bf16 working copy, version += 1. */
 int tmps_update(tmps_stage* stage, void* hip_stream);

@@ -51,6 +51,10 @@ EXPORTS = {
     "tmps_forward_micro": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_forward_micro_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "tmps_backward": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tmps_backward_at": (C.c_int, [C.c_void_p, C.c_long, C.POINTER(C.c_int), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tmps_schedule_plan_1f1b": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int32), C.c_size_t]),
+    "tmps_schedule_run_1f1b": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                         C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_int32)]),
     "tmps_update": (C.c_int, [C.c_void_p, C.c_void_p]),
     "tmps_schedule_plan": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32), C.c_size_t]),
     "tmps_schedule_stash_groups": (C.c_int, [C.c_int, C.c_int, C.c_int]),
@@ -99,6 +103,13 @@ def schedule_plan(W, N, n_minibatches):
     n = _check(lib().tmps_schedule_plan(W, N, n_minibatches, None, 0))
     buf = (C.c_int32 * (7 * n))()
     _check(lib().tmps_schedule_plan(W, N, n_minibatches, buf, n))
+    return np.frombuffer(buf, dtype=np.int32).reshape(n, 7).copy()
+
+
+def schedule_plan_1f1b(W, n_batches):
+    n = _check(lib().tmps_schedule_plan_1f1b(W, n_batches, None, 0))
+    buf = (C.c_int32 * (7 * n))()
+    _check(lib().tmps_schedule_plan_1f1b(W, n_batches, buf, n))
     return np.frombuffer(buf, dtype=np.int32).reshape(n, 7).copy()
 
 
@@ -366,24 +377,53 @@ class Stage:
                                    C.c_void_p(dx.data_ptr()) if dx is not None else None,
                                    C.c_void_p(self._stream(stream))))
 
+    def backward_at(self, version, slots, dy=None, dx=None, stream=None):
+        arr = (C.c_int * len(slots))(*slots)
+        _check(lib().tmps_backward_at(self.handle, version, arr, len(slots),
+                                      C.c_void_p(dy.data_ptr()) if dy is not None else None,
+                                      C.c_void_p(dx.data_ptr()) if dx is not None else None,
+                                      C.c_void_p(self._stream(stream))))
+
     def update(self, stream=None):
         _check(lib().tmps_update(self.handle, C.c_void_p(self._stream(stream))))
+
+    def device_bytes(self):
+        """Bytes of the stage's device regions: parameters (masters + working copy), optimizer state and gradients,
+        activation stash, scratch, kept weight versions."""
+        names = ("params", "state", "stash", "scratch")
+        out = {n: int(r.numel()) for n, r in zip(names, self.regions)}
+        sh = getattr(self, "shadow", None)
+        out["kept_versions"] = int(sh.numel()) if sh is not None else 0
+        return out
 
 
 class Pipeline:
     """K stages of a workloads.Config on K streams of one GPU, run in nF1B order by tmps_schedule_run."""
 
-    def __init__(self, cfg, params, device="cuda:0", extra_groups=0, one_stream=False, vertical_sync=False):
+    def __init__(self, cfg, params, device="cuda:0", extra_groups=0, one_stream=False, vertical_sync=False,
+                 baseline_1f1b=False, batch=None):
         """vertical_sync: forward passes read the weight version they are tagged with (the paper's vertical weight
-        stashing; every stage keeps the older versions the schedule needs) instead of the live weights."""
+        stashing; every stage keeps the older versions the schedule needs) instead of the live weights.
+        baseline_1f1b: the comparison system instead of TiMePReSt: batches of `batch` samples (default: the
+        configuration's micro-batch size), each with its own forward and backward pass, in 1F1B order, backward passes
+        on the weights of their forward passes (every stage keeps the K - s - 1 older versions that takes)."""
         import torch
         self.torch = torch
         self.cfg = cfg
         self.vertical_sync = bool(vertical_sync)
+        self.baseline_1f1b = bool(baseline_1f1b)
         self.device = torch.device(device)
         K, N = cfg.K, cfg.N
+        self.batch = int(batch) if batch else cfg.micro
         self.stages = []
         for s in range(K):
+            if self.baseline_1f1b:
+                st = Stage(cfg.stages[s], cfg.dtype, self.batch, 1, K - s + extra_groups, cfg.lr, cfg.momentum,
+                           borrow_input=True, device=device)
+                st.set_params(params[s])
+                st.set_shadow(K - s - 1)
+                self.stages.append(st)
+                continue
             groups = schedule_stash_groups(K, N, s) + extra_groups
             st = Stage(cfg.stages[s], cfg.dtype, cfg.micro, N, groups * N, cfg.lr, cfg.momentum,
                        borrow_input=True, device=device)
@@ -428,12 +468,19 @@ class Pipeline:
         log = None
         logp = None
         if want_log:
-            n_tasks = _check(lib().tmps_schedule_plan(K, N, n_minibatches, None, 0))
+            if self.baseline_1f1b:
+                n_tasks = _check(lib().tmps_schedule_plan_1f1b(K, n_minibatches, None, 0))
+            else:
+                n_tasks = _check(lib().tmps_schedule_plan(K, N, n_minibatches, None, 0))
             log = (C.c_int32 * (7 * n_tasks))()
             logp = log
-        run = lib().tmps_schedule_run_vsync if self.vertical_sync else lib().tmps_schedule_run
-        _check(run(handles, K, N, n_minibatches, C.c_void_p(x_dev.data_ptr()), C.c_void_p(y_dev.data_ptr()), streams,
-                   C.c_void_p(losses_dev.data_ptr()), logp))
+        if self.baseline_1f1b:   # n_minibatches counts batches here
+            _check(lib().tmps_schedule_run_1f1b(handles, K, n_minibatches, C.c_void_p(x_dev.data_ptr()),
+                                                C.c_void_p(y_dev.data_ptr()), streams, C.c_void_p(losses_dev.data_ptr()), logp))
+        else:
+            run = lib().tmps_schedule_run_vsync if self.vertical_sync else lib().tmps_schedule_run
+            _check(run(handles, K, N, n_minibatches, C.c_void_p(x_dev.data_ptr()), C.c_void_p(y_dev.data_ptr()), streams,
+                       C.c_void_p(losses_dev.data_ptr()), logp))
         if log is None:
             return None
         return np.frombuffer(log, dtype=np.int32).reshape(-1, 7).copy()

@@ -35,6 +35,7 @@ int grow_events(tmps_stage* st, size_t n) {
 
 struct RunCtx {
     bool vsync = false;              // forward passes read the weight version they are tagged with
+    bool one_f1b = false;            // the comparison system: a backward pass per batch, on the weights of its forward pass
     std::vector<long> base_version;  // every stage's version when the run started
     tmps_stage** stages;
     int K, N, M, mb, n_minibatches;
@@ -92,28 +93,36 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
     if (c.log) {
         int32_t* o = c.log + 7 * ti;
         o[0] = k.t; o[1] = k.stage; o[2] = k.kind; o[3] = k.b; o[4] = k.j;
-        o[5] = (int32_t)(st->version - c.base_version[k.stage]); o[6] = k.net_version;
+        const int32_t live = (int32_t)(st->version - c.base_version[k.stage]);
+        if (c.one_f1b) {   // version the task reads (a backward pass: the one its forward pass read), version the worker is at
+            o[5] = k.kind == kFwd ? live : k.stage_version;
+            o[6] = live;
+        } else {
+            o[5] = live;
+            o[6] = k.net_version;
+        }
     }
     const int group = b0 % c.groups[k.stage];
     int rc;
     if (k.kind == kFwd) {
-        const size_t q = (size_t)b0 * N + k.j;
-        const int slot = group * N + k.j;
+        const int j = k.j < 0 ? 0 : k.j;   // (the comparison system has no micro-batches: N = 1)
+        const size_t q = (size_t)b0 * N + j;
+        const int slot = group * N + j;
         const void* x;
         if (k.stage == 0) {
-            x = (const char*)c.inputs + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->in_elems * st->in_esize;
+            x = (const char*)c.inputs + ((size_t)b0 * c.M + (size_t)j * c.mb) * st->in_elems * st->in_esize;
         } else {
-            x = tmps_stage_output_ptr(c.stages[k.stage - 1], (b0 % c.groups[k.stage - 1]) * N + k.j);
+            x = tmps_stage_output_ptr(c.stages[k.stage - 1], (b0 % c.groups[k.stage - 1]) * N + j);
             if ((rc = c.wait_for(c.fwd_ev(k.stage - 1, q), s)) != TMPS_OK) return rc;
         }
-        const int32_t* lab = st->cfg.is_last ? c.labels + ((size_t)b0 * c.M + (size_t)k.j * c.mb) * st->label_rps : nullptr;
+        const int32_t* lab = st->cfg.is_last ? c.labels + ((size_t)b0 * c.M + (size_t)j * c.mb) * st->label_rps : nullptr;
         if (c.vsync)
             rc = tmps_forward_micro_at(st, c.base_version[k.stage] + k.net_version, slot, x, nullptr, lab, nullptr, s);
         else
             rc = tmps_forward_micro(st, slot, x, nullptr, lab, nullptr, s);
         if (rc != TMPS_OK) return rc;
         if (k.stage < K - 1 && (rc = c.record(c.fwd_ev(k.stage, q), s)) != TMPS_OK) return rc;
-        if (st->cfg.is_last && k.j == N - 1 && c.losses_out) {
+        if (st->cfg.is_last && j == N - 1 && c.losses_out) {
             ProfileScope scope(kcReduce, s);
             const int rows = c.M * st->label_rps;
             TMPS_HIP(reduce_scaled_sum(stage_row_loss(st, group * N), rows, 1.0f / (float)rows, c.losses_out + b0, s));
@@ -132,7 +141,11 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
         }
         int slots[64];
         for (int j = 0; j < N; ++j) slots[j] = group * N + j;
-        if ((rc = tmps_backward(st, slots, N, dy, dx, s)) != TMPS_OK) return rc;
+        if (c.one_f1b)   // horizontal weight stashing: differentiate at the weights the forward pass read
+            rc = tmps_backward_at(st, c.base_version[k.stage] + k.stage_version, slots, N, dy, dx, s);
+        else
+            rc = tmps_backward(st, slots, N, dy, dx, s);
+        if (rc != TMPS_OK) return rc;
         if ((rc = c.record(c.bwd_ev(k.stage, b0), s)) != TMPS_OK) return rc;
         if ((rc = tmps_update(st, s)) != TMPS_OK) return rc;
     }
@@ -141,8 +154,11 @@ int issue(RunCtx& c, const Task& k, size_t ti) {
 
 }  // namespace
 
+enum { kModeInPlace = 0, kModeVsync = 1, kMode1F1B = 2 };
+
 static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs, const int32_t* labels,
-                        void** hip_streams, float* losses_out, int32_t* version_log_out, bool vsync) {
+                        void** hip_streams, float* losses_out, int32_t* version_log_out, int mode) {
+    const bool vsync = mode == kModeVsync, one_f1b = mode == kMode1F1B;
     if (!stages || !hip_streams || !inputs || !labels) return fail(TMPS_EINVAL, "null argument");
     if (K < 1 || N < 1 || n_minibatches < 1) return fail(TMPS_EINVAL, "K, N and n_minibatches must be positive");
     const int mb = stages[0] ? stages[0]->cfg.micro_batch : 0;
@@ -157,7 +173,7 @@ static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, co
             return fail(TMPS_ESHAPE, "stage %d output (%lld) does not match stage %d input (%lld)", s - 1,
                         (long long)stages[s - 1]->out_elems, s, (long long)st->in_elems);
         if (s > 0 && stages[s - 1]->cfg.dtype != st->cfg.dtype) return fail(TMPS_ESHAPE, "stages differ in dtype");
-        int need = stash_groups(K, N, s);
+        int need = one_f1b ? K - s : stash_groups(K, N, s);
         if (st->cfg.max_stash / N < need)
             return fail(TMPS_ESTASH, "stage %d can stash %d mini-batches, the schedule needs %d", s, st->cfg.max_stash / N, need);
         for (char u : st->slot_used)
@@ -165,14 +181,18 @@ static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, co
         if (vsync && st->shadow_n < shadow_versions(K, N, s))
             return fail(TMPS_ESTASH, "stage %d keeps %d older weight versions, vertical weight stashing needs %d", s,
                         st->shadow_n, shadow_versions(K, N, s));
+        if (one_f1b && st->shadow_n < K - s - 1)
+            return fail(TMPS_ESTASH, "stage %d keeps %d older weight versions, horizontal weight stashing needs %d", s,
+                        st->shadow_n, K - s - 1);
     }
-    const std::vector<Task> tasks = plan_nf1b(K, N, n_minibatches);
+    const std::vector<Task> tasks = one_f1b ? plan_1f1b(K, n_minibatches) : plan_nf1b(K, N, n_minibatches);
 
     RunCtx c;
     c.stages = stages; c.K = K; c.N = N; c.mb = mb; c.M = mb * N; c.n_minibatches = n_minibatches;
     c.inputs = inputs; c.labels = labels; c.streams = hip_streams; c.losses_out = losses_out;
     c.log = version_log_out;
     c.vsync = vsync;
+    c.one_f1b = one_f1b;
     for (int s = 0; s < K; ++s) c.base_version.push_back(stages[s]->version);
     c.asz = stages[0]->asz;
     c.total_micro = (size_t)n_minibatches * N;
@@ -247,13 +267,18 @@ static int schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, co
 extern "C" int tmps_schedule_run(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
                                  const int32_t* labels, void** hip_streams, float* losses_out,
                                  int32_t* version_log_out) {
-    return schedule_run(stages, K, N, n_minibatches, inputs, labels, hip_streams, losses_out, version_log_out, false);
+    return schedule_run(stages, K, N, n_minibatches, inputs, labels, hip_streams, losses_out, version_log_out, kModeInPlace);
 }
 
 extern "C" int tmps_schedule_run_vsync(tmps_stage** stages, int K, int N, int n_minibatches, const void* inputs,
                                        const int32_t* labels, void** hip_streams, float* losses_out,
                                        int32_t* version_log_out) {
-    return schedule_run(stages, K, N, n_minibatches, inputs, labels, hip_streams, losses_out, version_log_out, true);
+    return schedule_run(stages, K, N, n_minibatches, inputs, labels, hip_streams, losses_out, version_log_out, kModeVsync);
+}
+
+extern "C" int tmps_schedule_run_1f1b(tmps_stage** stages, int K, int n_batches, const void* inputs, const int32_t* labels,
+                                      void** hip_streams, float* losses_out, int32_t* version_log_out) {
+    return schedule_run(stages, K, 1, n_batches, inputs, labels, hip_streams, losses_out, version_log_out, kMode1F1B);
 }
 
 extern "C" int tmps_streams_create(void** out, int n) {

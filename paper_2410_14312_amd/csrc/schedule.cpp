@@ -60,6 +60,43 @@ std::vector<Task> plan_nf1b(int W, int N, int n_minibatches) {
     return tasks;
 }
 
+// 1F1B by the same time-point rules (one task per worker and time-point, results reach the neighbour at t+1, a
+// backward pass that has arrived goes first), plus the start-up depth of the related-work system: worker s takes a
+// forward pass only while fewer than W - s batches are between their forward and backward pass on it.
+std::vector<Task> plan_1f1b(int W, int n_batches) {
+    const int32_t never = INT32_MAX;
+    std::vector<std::vector<int32_t>> fwd_ready(W, std::vector<int32_t>(n_batches, never));
+    std::vector<std::vector<int32_t>> bwd_ready(W, std::vector<int32_t>(n_batches, never));
+    std::vector<std::vector<int32_t>> read_by_fwd(W, std::vector<int32_t>(n_batches, 0));
+    std::fill(fwd_ready[0].begin(), fwd_ready[0].end(), 1);
+    std::vector<int> next_fwd(W, 0), next_bwd(W, 0), updates(W, 0);
+    std::vector<Task> tasks;
+    tasks.reserve((size_t)W * 2 * n_batches);
+    int done = 0;
+    for (int32_t t = 1; done < n_batches; ++t) {
+        for (int s = 0; s < W; ++s) {
+            const int b = next_bwd[s];
+            if (b < n_batches && bwd_ready[s][b] <= t) {
+                tasks.push_back(Task{t, s, kBwd, b + 1, -1, read_by_fwd[s][b], updates[s]});
+                ++updates[s];
+                ++next_bwd[s];
+                if (s > 0) bwd_ready[s - 1][b] = t + 1;
+                else ++done;
+                continue;
+            }
+            const int q = next_fwd[s];
+            if (q < n_batches && fwd_ready[s][q] <= t && next_fwd[s] - next_bwd[s] < W - s) {
+                read_by_fwd[s][q] = updates[s];
+                tasks.push_back(Task{t, s, kFwd, q + 1, -1, updates[s], updates[s]});
+                ++next_fwd[s];
+                if (s < W - 1) fwd_ready[s + 1][q] = t + 1;
+                else bwd_ready[s][q] = t + 1;
+            }
+        }
+    }
+    return tasks;
+}
+
 int stash_groups(int W, int N, int stage) {
     const int n = 3 * W + 4;
     std::vector<Task> tasks = plan_nf1b(W, N, n);
@@ -100,6 +137,22 @@ using namespace tmps;
 extern "C" int tmps_schedule_plan(int W, int N, int n_minibatches, int32_t* ops_out, size_t cap_ops) {
     if (W < 1 || N < 1 || n_minibatches < 1) return fail(TMPS_EINVAL, "W, N and n_minibatches must be positive");
     std::vector<Task> tasks = plan_nf1b(W, N, n_minibatches);
+    if (ops_out) {
+        if (cap_ops < tasks.size())
+            return fail(TMPS_ECAP, "ops_out holds %zu tasks, %zu needed", cap_ops, tasks.size());
+        for (size_t i = 0; i < tasks.size(); ++i) {
+            const Task& k = tasks[i];
+            int32_t* o = ops_out + 7 * i;
+            o[0] = k.t; o[1] = k.stage; o[2] = k.kind; o[3] = k.b; o[4] = k.j;
+            o[5] = k.stage_version; o[6] = k.net_version;
+        }
+    }
+    return (int)tasks.size();
+}
+
+extern "C" int tmps_schedule_plan_1f1b(int W, int n_batches, int32_t* ops_out, size_t cap_ops) {
+    if (W < 1 || n_batches < 1) return fail(TMPS_EINVAL, "W and n_batches must be positive");
+    std::vector<Task> tasks = plan_1f1b(W, n_batches);
     if (ops_out) {
         if (cap_ops < tasks.size())
             return fail(TMPS_ECAP, "ops_out holds %zu tasks, %zu needed", cap_ops, tasks.size());

@@ -802,6 +802,29 @@ extern "C" int tmps_update(tmps_stage* st, void* hip_stream) {
     return TMPS_OK;
 }
 
+extern "C" int tmps_backward_at(tmps_stage* st, long version, const int* slots, int n_slots, const void* dy, void* dx,
+                                void* hip_stream) {
+    if (!st) return fail(TMPS_EINVAL, "stage is null");
+    if (version == st->version) return tmps_backward(st, slots, n_slots, dy, dx, hip_stream);
+    int found = -1;
+    for (int k = 0; k < st->shadow_n; ++k)
+        if (st->shadow_ver[k] == version) found = k;
+    if (found < 0)
+        return fail(TMPS_EINVAL, "weights after %ld updates are not kept (the stage is at %ld and keeps %d older versions)",
+                    version, st->version, st->shadow_n);
+    // as in tmps_forward_micro_at: the kernels take their weight pointers at launch; the gradients still go to the
+    // stage's own gradient array, and the update that follows changes the live weights
+    float* const live_master = st->master;
+    void* const live_wcopy = st->wcopy;
+    char* base = st->shadow + (size_t)found * st->param_bytes;
+    st->master = reinterpret_cast<float*>(base);
+    if (live_wcopy) st->wcopy = base + (size_t)st->P * 4;
+    const int rc = tmps_backward(st, slots, n_slots, dy, dx, hip_stream);
+    st->master = live_master;
+    st->wcopy = live_wcopy;
+    return rc;
+}
+
 extern "C" int tmps_forward_micro_at(tmps_stage* st, long version, int slot, const void* x, void* y, const int32_t* labels,
                                      float* loss_out, void* hip_stream) {
     if (!st) return fail(TMPS_EINVAL, "stage is null");

@@ -53,6 +53,21 @@ int main() {
             printf("\n");
             if (W >= 2 && N >= 2) bad += expect(tmps_version_diff_formula(W, N) == (W + N - 2) / N, "formula");
         }
+    for (int W = 1; W <= 9; ++W)
+        for (int n : {1, 2, W, 3 * W + 5}) {
+            const int tasks = tmps_schedule_plan_1f1b(W, n, nullptr, 0);
+            bad += expect(tasks == 2 * W * n, "1F1B task count");
+            std::vector<int32_t> ops((size_t)tasks * 7);
+            bad += expect(tmps_schedule_plan_1f1b(W, n, ops.data(), (size_t)tasks) == tasks, "1F1B plan");
+            std::vector<int32_t> small((size_t)(tasks - 1) * 7);
+            bad += expect(tmps_schedule_plan_1f1b(W, n, small.data(), (size_t)tasks - 1) == TMPS_ECAP, "1F1B capacity error");
+            if (n == 3 * W + 5) {
+                printf("plan1f1b %d %d", W, n);
+                for (int32_t v : ops) printf(" %d", v);
+                printf("\n");
+            }
+        }
+    bad += expect(tmps_schedule_plan_1f1b(0, 3, nullptr, 0) == TMPS_EINVAL, "1F1B W = 0");
     bad += expect(tmps_schedule_plan(0, 4, 3, nullptr, 0) == TMPS_EINVAL, "W = 0");
     bad += expect(tmps_schedule_plan(4, 0, 3, nullptr, 0) == TMPS_EINVAL, "N = 0");
     bad += expect(tmps_schedule_plan(4, 4, 0, nullptr, 0) == TMPS_EINVAL, "no mini-batches");

@@ -36,6 +36,16 @@ def test_planner_equals_oracle_simulation(W, N, n):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("W,n", [(1, 5), (2, 9), (3, 7), (4, 12), (7, 30)])
+def test_1f1b_planner_equals_oracle_simulation(W, n):
+    from oracle import baseline
+    got = T.schedule_plan_1f1b(W, n)
+    want = np.array(baseline.simulate_1f1b(W, n), dtype=np.int32)
+    assert got.shape == want.shape and np.array_equal(got, want)
+    with pytest.raises(T.TmpsError):
+        T.schedule_plan_1f1b(0, 3)
+
+
 def test_version_difference_exports():
     for W in range(2, 11):
         for N in range(2, 8):

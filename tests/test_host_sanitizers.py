@@ -60,6 +60,11 @@ def test_planner_is_clean_under_sanitizers_and_equals_the_oracle(driver):
             want = np.array(S.simulate(W, N, n)["ops"], dtype=np.int64)
             assert np.array_equal(got, want), (W, N, n)
             plans += 1
+        elif f[0] == "plan1f1b":
+            from oracle import baseline
+            W, n = int(f[1]), int(f[2])
+            got = np.array(f[3:], dtype=np.int64).reshape(-1, 7)
+            assert np.array_equal(got, np.array(baseline.simulate_1f1b(W, n), dtype=np.int64)), (W, n)
         elif f[0] == "v":
             W, N = int(f[1]), int(f[2])
             assert int(f[3]) == S.version_difference_simulated(W, N), (W, N)
