@@ -54,12 +54,16 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
 }
 
 static int g3_wgrad_slices(int64_t M, int64_t N, int64_t K);
+static int g3_long_k_slices(int64_t M, int64_t N, int64_t K);
 
 size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t K, int with_rowsum) {
     GemmPlan p = plan_gemm(M, N, K);
     int slices = p.slices;
     if (with_rowsum) {   // a weight gradient may go to the persistent path, with its own number of slices
         const int s3 = g3_wgrad_slices(M, N, K);
+        if (s3 > slices) slices = s3;
+    } else {             // and so may an input gradient with a very long contraction
+        const int s3 = g3_long_k_slices(M, N, K);
         if (s3 > slices) slices = s3;
     }
     if (slices <= 1) return 0;
@@ -234,6 +238,30 @@ static bool g3_forward_ok(int64_t M, int64_t N, int64_t K) {
     return K % 64 == 0 && K >= 128 && N % 8 == 0 && g3_tiles(M, N) >= 192 && (int64_t)cdiv(N, 256) * 256 * 3 <= N * 4;
 }
 
+// An output of few 256-wide tiles with a very long contraction (the input gradient of a vocabulary-wide output layer:
+// 96 tiles, k = 32000) goes to the persistent kernel in k-slices: the slice count is the one whose (tile, slice) units
+// fill whole rounds of the device best, weighed against the fp32 partial sums it writes and the finishing pass reads
+// (rates measured: 1 PFLOP/s in the k-loop, 5 TB/s for the partial sums).  0: leave it to the tiled kernel.
+static int g3_long_k_slices(int64_t M, int64_t N, int64_t K) {
+    if (K % 64 != 0 || N % 8 != 0 || K < 8192) return 0;
+    const int64_t tiles = g3_tiles(M, N);
+    if (tiles >= 192 || tiles < 32 || (int64_t)cdiv(N, 256) * 256 * 3 > N * 4) return 0;
+    const int cus = compute_units();
+    int best = 0;
+    double best_us = 0.0;
+    for (int sl = 2; sl <= 16; ++sl) {
+        if (K / sl < 2048) break;
+        const int64_t units = tiles * sl;
+        const double fill = (double)units / (double)((units + cus - 1) / cus * cus);
+        const double us = 2.0 * M * N * K / (fill * 1e9) + (double)sl * M * N * 8.0 / 5e6;
+        if (best == 0 || us < best_us) {
+            best = sl;
+            best_us = us;
+        }
+    }
+    return best;
+}
+
 static G3Plan g3_plan(int M, int N, int K, int slices, int bm = kG3Tile, int bn = kG3Tile) {
     G3Plan p;
     p.tiles_m = cdiv(M, bm);
@@ -366,6 +394,18 @@ static hipError_t dense_dgrad_as(int kc, int dtype, const void* dy, const void* 
             G3Operand<true> A{(const bf16_t*)dy, B, Dout};
             G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
             return launch3<true, false, false>(kc, A, Bv, epi, B, Din, Dout, g3_plan(B, Din, Dout, 1), s);
+        }
+        const int s3 = (fast && ws && aligned16(ws) && aligned16(dx) && aligned16(mask) && aligned16(add) && epi.wide_ok())
+                           ? g3_long_k_slices(B, Din, Dout) : 0;
+        if (s3 > 1) {
+            G3Operand<true> A{(const bf16_t*)dy, B, Dout};
+            G3Operand<false> Bv{(const bf16_t*)w, Din, Din};
+            const G3Plan plan = g3_plan(B, Din, Dout, s3);
+            EpiPartial part{ws, Din, (int64_t)B * Din};
+            hipError_t e = launch3<true, false, false>(kc, A, Bv, part, B, Din, Dout, plan, s);
+            if (e != hipSuccess) return e;
+            return launch_timed(kcSplitFinish, splitk_finish8_kernel<EpiMask<bf16_t, bf16_t>>, dim3(cdiv((int64_t)B * Din / 8, 256)),
+                                dim3(256), 0, s, (const float*)ws, epi, B, Din, plan.slices);
         }
         if (fast) {
             DenseKC A{(const bf16_t*)dy, B, Dout, Dout};

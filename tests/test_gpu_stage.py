@@ -219,6 +219,7 @@ DENSE_CASES = [
     (128, 6144, False, 2048, 1), # wide output, many rows: the persistent 256x256 kernel in the forward pass
     (6144, 128, False, 1024, 2), # wide input: the persistent kernel in the input-gradient pass
     (1024, 1024, False, 4608, 2),  # long batch: the persistent kernel, k-split, in the weight-gradient pass
+    (768, 8192, False, 2048, 2),   # long contraction, few wide tiles: the persistent kernel in k-slices in the input-gradient pass
 ]
 
 
