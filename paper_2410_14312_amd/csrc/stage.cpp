@@ -539,7 +539,8 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         const size_t step = (size_t)mb * st->in_elems * st->in_esize;
         for (int j = 1; j < N; ++j)
             if ((const char*)st->slot_x[g0 + j] != x0 + j * step)
-                return fail(TMPS_ESHAPE, "borrowed inputs of a mini-batch must be consecutive in memory");
+                return fail(TMPS_ESHAPE, "borrowed inputs of a mini-batch must be consecutive in memory: slot %d holds %p, expected %p (slot %d + %d x %zu bytes)",
+                            g0 + j, st->slot_x[g0 + j], (const void*)(x0 + j * step), g0, j, step);
     } else {
         x0 = st->stash + st->in_off + (size_t)row0 * st->in_elems * st->in_esize;
     }

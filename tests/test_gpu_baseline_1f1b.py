@@ -69,8 +69,8 @@ def test_backward_at_needs_a_kept_version_and_the_run_enough_of_them():
     from paper_2410_14312_amd import Pipeline, Stage, TmpsError
     st = Stage([linear(16, 16, True)], "f32", 4, 1, 2, 0.1, 0.9)
     st.set_params([{"w": np.eye(16, dtype=np.float32), "b": np.zeros(16, np.float32)}])
-    x = torch.ones(4, 16, device="cuda:0")
-    dy = torch.ones(4, 16, device="cuda:0")
+    x = torch.ones(4, 16, dtype=torch.float32, device="cuda:0")
+    dy = torch.ones(4, 16, dtype=torch.float32, device="cuda:0")
     st.forward_micro(0, x)
     with pytest.raises(TmpsError) as e:
         st.backward_at(3, [0], dy=dy)           # no such version
@@ -83,7 +83,7 @@ def test_backward_at_needs_a_kept_version_and_the_run_enough_of_them():
     pipe.stages[0].set_shadow(0)                # the first worker keeps no older version: the run must refuse
     xs, ys = pipe.upload([make_batch(cfg, 0, M=8)] * 2)
     with pytest.raises(TmpsError) as e:
-        pipe.run_device(xs, ys, 2, torch.zeros(2, device="cuda:0"))
+        pipe.run_device(xs, ys, 2, torch.zeros(2, dtype=torch.float32, device="cuda:0"))
     assert e.value.code == -5
 
 

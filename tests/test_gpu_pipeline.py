@@ -120,9 +120,9 @@ def test_run_rejects_small_stash_and_mismatched_stages():
     from paper_2410_14312_amd.binding import _check
     a = Stage([linear(16, 16, True)], "f32", 4, 2, 2, 0.1, 0.9)                      # one group only
     b = Stage([linear(16, 10, False), softmax_ce(10)], "f32", 4, 2, 2, 0.1, 0.9, borrow_input=True)
-    x = torch.zeros(16, 16, device="cuda:0")
+    x = torch.zeros(16, 16, dtype=torch.float32, device="cuda:0")
     y = torch.zeros(16, dtype=torch.int32, device="cuda:0")
-    losses = torch.zeros(2, device="cuda:0")
+    losses = torch.zeros(2, dtype=torch.float32, device="cuda:0")
     handles = (C.c_void_p * 2)(a.handle, b.handle)
     streams = (C.c_void_p * 2)(0, 0)
     with pytest.raises(TmpsError) as e:
@@ -240,7 +240,7 @@ def test_second_run_and_failed_run_on_the_same_stages():
     x, y = pipe.upload(batches[:2])
     losses = torch.zeros(2, dtype=torch.float32, device=pipe.device)
     last = pipe.stages[1]
-    xin = torch.zeros(cfg.M, last.in_elems, device=pipe.device)
+    xin = torch.zeros(cfg.M, last.in_elems, dtype=torch.float32, device=pipe.device)
     last.forward_micro(0, xin[:cfg.micro], labels=y[:cfg.micro])
     with pytest.raises(TmpsError) as e:
         pipe.run_device(x, y, 2, losses)
@@ -248,7 +248,7 @@ def test_second_run_and_failed_run_on_the_same_stages():
     torch.cuda.synchronize()
     for j in range(1, cfg.N):
         last.forward_micro(j, xin[j * cfg.micro:(j + 1) * cfg.micro], labels=y[j * cfg.micro:(j + 1) * cfg.micro])
-    last.backward(list(range(cfg.N)), dx=torch.empty(cfg.M * last.in_elems, device=pipe.device))
+    last.backward(list(range(cfg.N)), dx=torch.empty(cfg.M * last.in_elems, dtype=torch.float32, device=pipe.device))
     torch.cuda.synchronize()
     log3 = pipe.run_device(x, y, 2, losses)
     assert np.array_equal(log3, schedule_plan(cfg.K, cfg.N, 2))

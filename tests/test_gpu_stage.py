@@ -310,8 +310,8 @@ def test_slot_errors():
     from paper_2410_14312_amd import Stage, TmpsError
     st = Stage([linear(16, 16, True)], "f32", 4, 2, 4, 0.1, 0.9)
     st.set_params([{"w": np.zeros((16, 16), np.float32), "b": np.zeros(16, np.float32)}])
-    x = torch.zeros(4, 16, device="cuda:0")
-    dy = torch.zeros(8, 16, device="cuda:0")
+    x = torch.zeros(4, 16, dtype=torch.float32, device="cuda:0")
+    dy = torch.zeros(8, 16, dtype=torch.float32, device="cuda:0")
     st.forward_micro(0, x)
     with pytest.raises(TmpsError) as e:
         st.forward_micro(0, x)          # slot in use

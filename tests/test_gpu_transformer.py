@@ -67,7 +67,7 @@ def test_embedding_gradient_with_repeated_tokens(dtype, vocab, s, micro, N):
     st = Stage(specs, dtype, micro, N, N, 0.05, 0.9, device="cuda:0")
     st.set_params(_params(specs, rng))
     tok = torch.from_numpy(rng.integers(0, vocab, (micro * N, s)).astype(np.int32)).to(st.device)
-    dy = torch.randn(micro * N, s * 32, device=st.device).to(st.act_dtype)
+    dy = torch.randn(micro * N, s * 32, dtype=torch.float32, device=st.device).to(st.act_dtype)
     seen = []
     for _ in range(2):
         for j in range(N):
