@@ -288,13 +288,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                         if (ahead == NS - 1) wait_vmcnt<(NS - 2) * G>();
                         else wait_vmcnt<0>();
                     }
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's reads of the current stage are done
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's reads of the current stage are done
                     __builtin_amdgcn_s_barrier();
-                    asm volatile("" ::: "memory");
                     // All waves are past their last read of the current stage (it is refilled after this k-tile's last
                     // multiply step, or after the unit's results have been staged through it), and the next k-tile
-                    // is visible to all: fetch its first fragments under the cover of that multiply step.
-                    if (ahead > 0) {
+                    // is visible to all: fetch its first fragments under the cover of that multiply step.  (While the
+                    // pipeline drains there is no next k-tile: the reads then fetch stale bytes that nothing uses.)
+                    {
                         const unsigned char* na = smem + nstage * STAGE;
 #pragma unroll
                         for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = fa.read(na, i, 0);
@@ -307,6 +307,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+                {
+                    // instruction order of this step: one fragment read of the next step, one multiply of this one, in turn
+                    constexpr int READS = (AKC ? TM : 2 * TM) + (BKC ? TN : 2 * TN);
+                    constexpr int PER = READS > TM * TN ? (READS + TM * TN - 1) / (TM * TN) : 1;
+#pragma unroll
+                    for (int g = 0; g < TM * TN; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    }
+                }
             }
             if (kt + 1 < nk) {
                 if (issue_next()) ++ahead;
