@@ -23,12 +23,19 @@
 // a later copy has landed (both are counted by the same counter), so slow scattered stores would stall the
 // k-loop of the next unit.
 #pragma once
+#include <type_traits>
+
 #include "gemm2.hip.h"
 
 namespace tmps {
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef __attribute__((address_space(1))) const void* global_void_ptr;
+// LDS is addressed by 32-bit byte addresses throughout this kernel (lds_t), turned into LDS pointers where a value is
+// read or written: generic pointers into LDS make the compiler carry null checks and aperture tests around (and, in
+// some arrangements of this kernel's control flow, fail in its instruction verifier).
+typedef uint32_t lds_t;
+template <class T> __device__ __forceinline__ __attribute__((address_space(3))) T* lds_ptr(lds_t a) {
+    return (__attribute__((address_space(3))) T*)(uintptr_t)a;
+}
 
 template <bool KC> struct G3Operand {
     static constexpr bool kContig = KC;
@@ -41,6 +48,34 @@ template <bool KC> struct G3Operand {
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// One wave instruction that copies 16 bytes per lane from `src` (per lane) to 1 KB of consecutive LDS at `dst` (the same
+// for all lanes).  Written out as instructions rather than through the compiler's builtin: the compiler cannot tell
+// which LDS reads a copy in flight may alias and makes the wave wait for ALL its outstanding copies before the next
+// LDS read it sees, which serialises the copy pipeline; here the kernel's own counter waits and barriers order copies
+// and reads (a stage is read only after the wait and barrier that follow its copies, and refilled only after the
+// barrier that follows its last read).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is reserved: the compiler keeps nothing in it across statements
+__device__ __forceinline__ void copy16_to_lds(const void* src, lds_t dst) {
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(src) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+// Makes the compiler treat every 32-bit word of `t` (values requested from memory earlier) as read here, on every
+// path: a request whose result is never read stays "in flight" in the compiler's book-keeping, and the wait it then
+// inserts wherever the register is next written — in the k-loop of the following unit — would drain the copy pipeline
+// on every k-tile.
+template <class T> __device__ __forceinline__ void settle(const T& t) {
+    if constexpr (!std::is_empty<T>::value) {
+        static_assert(sizeof(T) % 4 == 0, "whole registers");
+        uint32_t w[sizeof(T) / 4];
+        __builtin_memcpy(w, &t, sizeof(T));
+#pragma unroll
+        for (unsigned i = 0; i < sizeof(T) / 4; ++i) asm volatile("" ::"v"(w[i]));
+    }
 }
 
 // LDS bytes of one launch
@@ -77,12 +112,14 @@ template <int ROWS, int BK, int NW, bool KC> struct G3Loader {
         }
     }
     // copy this wave's groups of the current k-tile into `tile` (LDS) and step to the next k-tile
-    __device__ __forceinline__ void issue(unsigned char* tile, int64_t ld, int wave) {
+    __device__ __forceinline__ void issue(lds_t tile, int64_t ld, int wave) {
 #pragma unroll
-        for (int g = 0; g < GROUPS; ++g) {
-            __builtin_amdgcn_global_load_lds((global_void_ptr)ptr[g], (lds_void_ptr)(tile + (wave + g * NW) * 1024), 16, 0, 0);
-            ptr[g] += KC ? BK : BK * ld;
-        }
+        for (int g = 0; g < GROUPS; ++g) issue_group(tile, ld, wave, g);
+    }
+    // the same, one group at a time (every group of a k-tile exactly once, in any order)
+    __device__ __forceinline__ void issue_group(lds_t tile, int64_t ld, int wave, int g) {
+        copy16_to_lds(ptr[g], tile + (wave + g * NW) * 1024);
+        ptr[g] += KC ? BK : BK * ld;
     }
 };
 
@@ -111,16 +148,15 @@ template <int ROWS, int BK, int T, bool KC> struct G3Frags {
             }
         }
     }
-    __device__ __forceinline__ bf16x8_t read(const unsigned char* tile, int i, int kk) const {
+    __device__ __forceinline__ bf16x8_t read(lds_t tile, int i, int kk) const {
         if constexpr (KC) {
-            return *reinterpret_cast<const bf16x8_t*>(tile + base[0] + i * (32 * BK * 2) + koff[kk]);
+            return *lds_ptr<const bf16x8_t>(tile + base[0] + i * (32 * BK * 2) + koff[kk]);
         } else {
-            typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
-            const unsigned char* p0 = tile + koff[0] + kk * 16 * (ROWS * 2) + base[i];
-            const unsigned char* p1 = p0 + 4 * (ROWS * 2);
+            const lds_t p0 = tile + koff[0] + kk * 16 * (ROWS * 2) + base[i];
+            const lds_t p1 = p0 + 4 * (ROWS * 2);
             union { s16x4_t h[2]; bf16x8_t v; } u;
-            u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p0));
-            u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p1));
+            u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lds_ptr<s16x4_t>(p0));
+            u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lds_ptr<s16x4_t>(p1));
             return u.v;
         }
     }
@@ -154,7 +190,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     static_assert((NS - 1) * G <= 63, "too many copies in flight for the vmcnt counter");
     static_assert(!ROWSUM || !AKC, "row sums are built for a row-contiguous A");
     static_assert(TN % 2 == 0 && G >= 8, "results are staged 32 x 64 at a time through 8 KB of a wave's own copy targets");
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+    const lds_t smem = (lds_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN, half = lane >> 5;
@@ -203,17 +240,27 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
         }
         ikt = 0;
     };
-    // copy the next k-tile (if any is left) into stage `istage`; returns false when all is issued
-    auto issue_next = [&]() -> bool {
-        if (iu >= plan.units) return false;
-        unsigned char* st = smem + istage * STAGE;
-        la.issue(st, A.ld, wave);
-        lb.issue(st + A_BYTES, B.ld, wave);
+    auto copies_left = [&]() { return iu < plan.units; };
+    // copy group g (of G) of the cursor's k-tile into stage `istage`
+    auto issue_group = [&](int g) {
+        const lds_t st = smem + istage * STAGE;
+        if (g < LoaderA::GROUPS) la.issue_group(st, A.ld, wave, g);
+        else lb.issue_group(st + A_BYTES, B.ld, wave, g - LoaderA::GROUPS);
+    };
+    // all G groups of the cursor's k-tile are issued: step the cursor
+    auto advance = [&]() {
         istage = istage + 1 == NS ? 0 : istage + 1;
         if (++ikt == ink) {
             iu += grid;
             seek_unit();
         }
+    };
+    // copy the cursor's whole k-tile (if any is left); returns false when all is issued
+    auto issue_next = [&]() -> bool {
+        if (!copies_left()) return false;
+#pragma unroll
+        for (int g = 0; g < G; ++g) issue_group(g);
+        advance();
         return true;
     };
 
@@ -234,14 +281,23 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    bf16x8_t af[2][TM], bfr[2][TN];
+    // Fragments are fetched PD multiply steps (of 16 k) ahead of their use.  With two waves per SIMD one step is
+    // enough: the other wave's multiplies cover a wave's LDS latency.  With one wave per SIMD (the 4-wave instances)
+    // a fragment requested during a step of TM * TN multiplies has not arrived when the next step starts, so these
+    // run two steps ahead, with four sets of fragment registers.
+    constexpr int PD = NW <= 4 ? 2 : 1, NBUF = PD == 2 ? 4 : 2;
+    static_assert(PD < KK && KK % NBUF == 0, "the fragment sets rotate once per k-tile");
+    bf16x8_t af[NBUF][TM], bfr[NBUF][TN];
     int cstage = 0;
     {
-        const unsigned char* sa = smem;
+        const lds_t sa = smem;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[0][i] = fa.read(sa, i, 0);
+        for (int p = 0; p < PD; ++p) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[0][j] = fb.read(sa + A_BYTES, j, 0);
+            for (int i = 0; i < TM; ++i) af[p][i] = fa.read(sa, i, p);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[p][j] = fb.read(sa + A_BYTES, j, p);
+        }
     }
 
     for (int cu = vb; cu < plan.units; cu += grid) {
@@ -258,28 +314,52 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
         float rsum = 0.0f;
 
+        // What the epilogue reads from memory (a bias per column, a residual source or a mask per element), block by
+        // block of 32 rows x 64 columns of this wave's results (block b: rows 32 (b / (TN / 2)), columns 64 (b % (TN / 2))).
+        constexpr int NB = TM * (TN / 2);
+        const int64_t epi_ld = epi.ld;
+        typename Epi::Col8 pcol[TN / 2];
+        typename Epi::Row8 prow[NB][4];
+        auto epi_n = [&](int jp) { return n0 + wn * (BN / WN) + jp * 64 + (lane & 7) * 8; };
+        auto epi_request = [&](int b) {
+            const int i = b / (TN / 2), jp = b % (TN / 2), n = epi_n(jp);
+            if (i == 0) pcol[jp] = epi.col8(n < N ? n : 0);
+#pragma unroll
+            for (int sp = 0; sp < 4; ++sp) {
+                const int pm = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
+                prow[b][sp] = epi.row8((int64_t)pm * epi_ld + n, pm < M && n < N);
+            }
+        };
+        // With registers to spare (the 4-wave instances: 512 per lane) all of it is requested before the k-loop; the
+        // 8-wave instances, which would spill, request a block's data when they come to the block.  A wave waits for
+        // its requests in issue order, stores included: waiting for data requested after a store means waiting for the
+        // store to be acknowledged.
+        constexpr bool EARLY = NW <= 4;
+        if constexpr (EARLY) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) epi_request(b);
+        }
+
         for (int kt = 0; kt < nk; ++kt) {
-            // Invariant: the fragments of this k-tile's first 16 k are in registers (fetched during the previous
-            // k-tile's last multiply step); `ahead` younger k-tiles are in flight or have landed.
-            const unsigned char* sa = smem + cstage * STAGE;
-            const unsigned char* sb = sa + A_BYTES;
+            // Invariant: the fragments of this k-tile's first PD multiply steps are in registers or on their way
+            // (requested during the previous k-tile's last PD steps); `ahead` younger k-tiles are in flight or have landed.
+            const lds_t sa = smem + cstage * STAGE;
             const int nstage = cstage + 1 == NS ? 0 : cstage + 1;
             if constexpr (ROWSUM) {
                 if (tn == 0 && tid < BM) {
                     // column tid of the [BK][BM] tile: chunk (tid / 8) ^ ((k & 3) << 2) of k-row k
 #pragma unroll 8
                     for (int k = 0; k < BK; ++k)
-                        rsum += (float)*reinterpret_cast<const bf16_t*>(sa + k * (BM * 2) + ((((tid >> 3) ^ ((k & 3) << 2)) << 4) | ((tid & 7) << 1)));
+                        rsum += (float)*lds_ptr<const bf16_t>(sa + k * (BM * 2) + ((((tid >> 3) ^ ((k & 3) << 2)) << 4) | ((tid & 7) << 1)));
                 }
             }
+            // After the barrier of this k-tile its stage is free; unless the unit's results go through it first (the
+            // unit's last k-tile) it is refilled at once, the copies spread over the multiplies that follow the barrier.
+            bool fill = false;
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                if (kk < KK - 1) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = fa.read(sa, i, kk + 1);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) bfr[(kk + 1) & 1][j] = fb.read(sb, j, kk + 1);
-                } else {
+                const int nx = kk + PD;   // the step whose fragments are requested during this one
+                if (nx == KK) {
                     // Every fragment of this k-tile has been requested.  The next k-tile is the oldest copy in
                     // flight: copies complete in issue order, so it has landed once at most (ahead - 1) * G younger
                     // copies are outstanding.  Result stores of an earlier unit are younger than it too and only
@@ -290,36 +370,40 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                     }
                     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's reads of the current stage are done
                     __builtin_amdgcn_s_barrier();
-                    // All waves are past their last read of the current stage (it is refilled after this k-tile's last
-                    // multiply step, or after the unit's results have been staged through it), and the next k-tile
-                    // is visible to all: fetch its first fragments under the cover of that multiply step.  (While the
+                    // All waves are past their last read of the current stage, and the next k-tile is visible to all:
+                    // its first fragments are fetched under the cover of the remaining multiply steps.  (While the
                     // pipeline drains there is no next k-tile: the reads then fetch stale bytes that nothing uses.)
-                    {
-                        const unsigned char* na = smem + nstage * STAGE;
-#pragma unroll
-                        for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = fa.read(na, i, 0);
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) bfr[(kk + 1) & 1][j] = fb.read(na + A_BYTES, j, 0);
-                    }
+                    fill = kt + 1 < nk && copies_left();
                 }
+                // This step in program order, kept by the scheduling barriers: before multiply g, the g-th share of
+                // the fragment requests of step nx and, after the barrier, of the copies: a wave has one instruction
+                // stream, and what it issues between two multiplies costs nothing while the matrix unit is busy.
+                const lds_t ra = nx < KK ? sa : smem + nstage * STAGE;
+                const int rk = nx < KK ? nx : nx - KK;
+                constexpr int NM = TM * TN, NR = TM + TN, CPS = G / PD;
+                static_assert(G % PD == 0, "the copies of a k-tile are spread evenly over the steps after the barrier");
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                for (int g = 0; g < NM; ++g) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-                {
-                    // instruction order of this step: one fragment read of the next step, one multiply of this one, in turn
-                    constexpr int READS = (AKC ? TM : 2 * TM) + (BKC ? TN : 2 * TN);
-                    constexpr int PER = READS > TM * TN ? (READS + TM * TN - 1) / (TM * TN) : 1;
-#pragma unroll
-                    for (int g = 0; g < TM * TN; ++g) {
-                        __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    for (int r = g * NR / NM; r < (g + 1) * NR / NM; ++r) {
+                        if (r < TM) af[nx % NBUF][r] = fa.read(ra, r, rk);
+                        else bfr[nx % NBUF][r - TM] = fb.read(ra + A_BYTES, r - TM, rk);
                     }
+                    if (nx >= KK) {
+                        if (fill) {
+#pragma unroll
+                            for (int c = g * CPS / NM; c < (g + 1) * CPS / NM; ++c) issue_group((nx - KK) * CPS + c);
+                        }
+                    }
+                    acc[g / TN][g % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % NBUF][g / TN], bfr[kk % NBUF][g % TN], acc[g / TN][g % TN], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            if (fill) {
+                advance();
+                ++ahead;
+            }
             if (kt + 1 < nk) {
-                if (issue_next()) ++ahead;
                 --ahead;   // kt + 1 < nk: a next k-tile exists
                 cstage = nstage;
             }
@@ -327,53 +411,59 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
 
         // ---- results ----
         // The stage of the unit's last k-tile is free and not yet refilled: each wave transposes its accumulators
-        // through the 8 KB of that stage that its own copies write (so no other wave touches them), 32 rows x 64
-        // columns of fp32 at a time, and leaves with 8 consecutive columns of one row per lane: a store
+        // through the 8 KB of that stage that its own copies write (so no other wave touches them), one block of
+        // 32 rows x 64 columns of fp32 at a time, and leaves with 8 consecutive columns of one row per lane: a store
         // instruction then writes 8 rows of 128 (bf16) or 256 (fp32) consecutive bytes.
         {
-            unsigned char* stg = smem + cstage * STAGE;
+            const lds_t stg = smem + cstage * STAGE;
             // piece p (1 KB = 4 staged rows) of this wave: its p-th copy group
             // (computed where it is used: an array of them indexed by the lane's half would live in scratch memory)
             auto piece = [&](int p) {
                 return p < LoaderA::GROUPS ? (wave + p * NW) * 1024 : A_BYTES + (wave + (p - LoaderA::GROUPS) * NW) * 1024;
             };
-            const int64_t ld = epi.ld;
             const int col_in = lane & 31;
+            if constexpr (EARLY) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int b = 0; b < NB; ++b) {
+                    if (b < TN / 2) settle(pcol[b]);
 #pragma unroll
-                for (int jp = 0; jp < TN / 2; ++jp) {
-                    // what the epilogue reads from memory for the four groups of 8 rows of this block is requested before
-                    // the block is transposed: one memory latency per block, not one per group of rows
-                    const int n = n0 + wn * (BN / WN) + jp * 64 + (lane & 7) * 8;
-                    const typename Epi::Col8 pcol = epi.col8(n < N ? n : 0);
-                    typename Epi::Row8 prow[4];
-#pragma unroll
-                    for (int sp = 0; sp < 4; ++sp) {
-                        const int pm = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
-                        prow[sp] = epi.row8((int64_t)pm * ld + n, pm < M && n < N);
-                    }
-                    // accumulator register r of a lane: row 8 (r / 4) + 4 half + r % 4, column lane % 32
-#pragma unroll
-                    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int base = half ? piece(2 * (r >> 2) + 1) : piece(2 * (r >> 2));
-                            *reinterpret_cast<float*>(stg + base + (r & 3) * 256 + (jj * 32 + col_in) * 4) = acc[i][2 * jp + jj][r];
-                        }
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-                    for (int sp = 0; sp < 4; ++sp) {
-                        // staged row 8 sp + lane / 8 lies in piece 2 sp + half, at row (lane / 8) % 4 of the piece
-                        const int base = half ? piece(2 * sp + 1) : piece(2 * sp);
-                        const unsigned char* src = stg + base + ((lane >> 3) & 3) * 256 + (lane & 7) * 32;
-                        const float4 lo = *reinterpret_cast<const float4*>(src), hi = *reinterpret_cast<const float4*>(src + 16);
-                        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                        const int m = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
-                        if (m < M && n < N) epi.at8(pcol, prow[sp], (int64_t)m * ld + n, v, z);   // N is a multiple of 8
-                    }
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten
+                    for (int sp = 0; sp < 4; ++sp) settle(prow[b][sp]);
                 }
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int i = b / (TN / 2), jp = b % (TN / 2);
+                // (requested before the block is transposed: one memory latency per block, not one per group of rows)
+                if constexpr (!EARLY) epi_request(b);
+                const int n = epi_n(jp);
+                // accumulator register r of a lane: row 8 (r / 4) + 4 half + r % 4, column lane % 32
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int base = half ? piece(2 * (r >> 2) + 1) : piece(2 * (r >> 2));
+                        *lds_ptr<float>(stg + base + (r & 3) * 256 + (jj * 32 + col_in) * 4) = acc[i][2 * jp + jj][r];
+                    }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if constexpr (!EARLY) {
+                    // before the block's first store, where the block's data is the wave's youngest request
+                    if (i == 0) settle(pcol[jp]);
+#pragma unroll
+                    for (int sp = 0; sp < 4; ++sp) settle(prow[b][sp]);
+                }
+#pragma unroll
+                for (int sp = 0; sp < 4; ++sp) {
+                    // staged row 8 sp + lane / 8 lies in piece 2 sp + half, at row (lane / 8) % 4 of the piece
+                    const int base = half ? piece(2 * sp + 1) : piece(2 * sp);
+                    const lds_t src = stg + base + ((lane >> 3) & 3) * 256 + (lane & 7) * 32;
+                    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+                    const f32x4_t lo = *lds_ptr<const f32x4_t>(src), hi = *lds_ptr<const f32x4_t>(src + 16);
+                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    const int m = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
+                    if (m < M && n < N) epi.at8(pcol[jp], prow[b][sp], (int64_t)m * epi_ld + n, v, z);   // N is a multiple of 8
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten
+            }
         }
         if constexpr (ROWSUM) {
             if (tn == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
