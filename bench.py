@@ -248,6 +248,8 @@ def main():
                     help="instead of the benchmark proper: the paper's comparison system (PipeDream-style 1F1B, a backward pass "
                          "and an update per micro-batch-sized batch, backward passes on the stashed weights of their forward "
                          "passes) beside TiMePReSt on the same workload: time per mini-batch's worth of samples and per-stage bytes")
+    ap.add_argument("--graphs", action="store_true",
+                    help="every stage replays captured HIP graphs of its forward and backward passes (tmps_stage_use_graphs)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short throughput runs of the other benchmark configurations (reported under other_workloads)")
     ap.add_argument("--one-stream-passes", type=int, default=3,
@@ -288,7 +290,7 @@ def main():
                           "config": {"workload": cfg.name, "mini_batch": cfg.M, "micro_batches": cfg.N, "stages": cfg.K},
                           "comparison": rep}))
         return
-    pipe = T.Pipeline(cfg, params, one_stream=args.one_stream, vertical_sync=args.vertical_sync)
+    pipe = T.Pipeline(cfg, params, one_stream=args.one_stream, vertical_sync=args.vertical_sync, graphs=args.graphs)
     shadow_bytes = sum(int(st.shadow.numel()) for st in pipe.stages if getattr(st, "shadow", None) is not None)
     n_distinct = min(32, max(args.steps, args.warmup, 1))
     distinct = [make_batch(cfg, i) for i in range(n_distinct)]
@@ -440,7 +442,7 @@ def main():
                 continue
             ocfg = get_config(name)
             oparams = init_params(ocfg)
-            opipe_ = T.Pipeline(ocfg, oparams)
+            opipe_ = T.Pipeline(ocfg, oparams, graphs=args.graphs)
             n = 20 if name in ("resnet50_bf16", "gpt2_small_bf16") else 60
             ob = [make_batch(ocfg, i) for i in range(min(n, 8))]
             ox, oy = opipe_.upload([ob[i % len(ob)] for i in range(n)])
@@ -482,7 +484,8 @@ def main():
                    "version_difference": T.version_diff_simulated(cfg.K, cfg.N),
                    "weight_policy": "vertical weight stashing" if args.vertical_sync else "in place",
                    "shadow_weight_bytes": shadow_bytes,
-                   "streams": 1 if args.one_stream else cfg.K, "hw_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
+                   "streams": 1 if args.one_stream else cfg.K, "hw_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4")),
+                   "graphs": bool(args.graphs)},
         "mfma_frac_of_bf16_peak_end_to_end": flops_step / (dt / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "stage_steps": stage_steps, "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "kernels_one_stream": kernels_alone,
         "final_loss": float(losses[-1]) if np.isfinite(losses[-1]) else None, "diverged": diverged, "other_workloads": others,

@@ -151,6 +151,20 @@ long tmps_stage_version(const tmps_stage* stage);
  * TMPS_ESLOT while a stash slot is in use: checkpoints are taken between mini-batches).  After writing master
  * parameters into `params`, call tmps_stage_sync_params to refresh the working copy. */
 int tmps_stage_set_version(tmps_stage* stage, long version);
+/* Graph replay, for stages whose passes are many short kernels (the host then spends longer issuing a pass than the
+ * device runs it).  With on != 0, tmps_forward_micro and tmps_backward capture their kernels into a HIP graph the second
+ * time they are called with the same device addresses (stash slot, input, upstream gradient, gradient destination, loss
+ * destination) and launch that graph from then on; calls with addresses that never repeat keep launching kernel by
+ * kernel.  Results are those of the kernel-by-kernel path, bit for bit (the same kernels in the same order).  On the
+ * last stage the labels are first copied into the stash (the copy is part of tmps_stage_bytes' stash size), so that
+ * the captured loss kernel reads a fixed address; a stage that copies its input (borrow_input = 0) makes that copy
+ * outside the graph for the same reason.  While kernel timing is enabled (tmps_profile_enable), and for passes issued on
+ * the default stream (which cannot be captured), nothing is captured or replayed.  While a pass is being captured, the
+ * runtime refuses to make any other stream wait for an event recorded on the capturing stream (tmps_schedule_run keeps
+ * its own threads apart; a caller with threads of its own must do the same around the second call with a set of
+ * addresses).  Graphs live with the stage.  Off by default.  Errors: TMPS_EINVAL; a failed capture or instantiation is
+ * reported by the pass that attempted it as TMPS_EHIP. */
+int tmps_stage_use_graphs(tmps_stage* stage, int on);
 
 /* ---- the three steps of a stage's training step ----
  *

@@ -44,6 +44,7 @@ EXPORTS = {
     "tmps_stage_output_ptr": (C.c_void_p, [C.c_void_p, C.c_int]),
     "tmps_stage_version": (C.c_long, [C.c_void_p]),
     "tmps_stage_set_version": (C.c_int, [C.c_void_p, C.c_long]),
+    "tmps_stage_use_graphs": (C.c_int, [C.c_void_p, C.c_int]),
     "tmps_stage_set_shadow": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]),
     "tmps_forward_micro_at": (C.c_int, [C.c_void_p, C.c_long, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p]),
@@ -387,6 +388,10 @@ class Stage:
     def update(self, stream=None):
         _check(lib().tmps_update(self.handle, C.c_void_p(self._stream(stream))))
 
+    def use_graphs(self, on=True):
+        """Forward and backward passes replay captured HIP graphs (see tmps_stage_use_graphs)."""
+        _check(lib().tmps_stage_use_graphs(self.handle, 1 if on else 0))
+
     def device_bytes(self):
         """Bytes of the stage's device regions: parameters (masters + working copy), optimizer state and gradients,
         activation stash, scratch, kept weight versions."""
@@ -401,8 +406,11 @@ class Pipeline:
     """K stages of a workloads.Config on K streams of one GPU, run in nF1B order by tmps_schedule_run."""
 
     def __init__(self, cfg, params, device="cuda:0", extra_groups=0, one_stream=False, vertical_sync=False,
-                 baseline_1f1b=False, batch=None):
-        """vertical_sync: forward passes read the weight version they are tagged with (the paper's vertical weight
+                 baseline_1f1b=False, batch=None, graphs=False):
+        """graphs: every stage replays captured HIP graphs of its passes (for configurations of many short kernels);
+        the first stage then copies its input into its stash instead of borrowing the caller's array, whose
+        addresses never repeat.
+        vertical_sync: forward passes read the weight version they are tagged with (the paper's vertical weight
         stashing; every stage keeps the older versions the schedule needs) instead of the live weights.
         baseline_1f1b: the comparison system instead of TiMePReSt: batches of `batch` samples (default: the
         configuration's micro-batch size), each with its own forward and backward pass, in 1F1B order, backward passes
@@ -426,8 +434,10 @@ class Pipeline:
                 continue
             groups = schedule_stash_groups(K, N, s) + extra_groups
             st = Stage(cfg.stages[s], cfg.dtype, cfg.micro, N, groups * N, cfg.lr, cfg.momentum,
-                       borrow_input=True, device=device)
+                       borrow_input=not (graphs and s == 0), device=device)
             st.set_params(params[s])
+            if graphs:
+                st.use_graphs(True)
             if self.vertical_sync:
                 st.set_shadow(schedule_shadow_versions(K, N, s))
             self.stages.append(st)

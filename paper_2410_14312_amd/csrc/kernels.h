@@ -121,5 +121,7 @@ hipError_t relu_mask(int dtype, const void* dy, const void* y, void* dz, int64_t
 hipError_t sgd_momentum(float* w, float* buf, const float* g, void* wcopy_bf16, int64_t n, float lr,
                         float mu, hipStream_t s);
 hipError_t cast_f32_to_bf16(const float* in, void* out, int64_t n, hipStream_t s);
+// dst[0..bytes) = src[0..bytes), both on the device, by a kernel
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 }  // namespace tmps

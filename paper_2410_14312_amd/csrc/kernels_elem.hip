@@ -309,6 +309,26 @@ hipError_t cast_f32_to_bf16(const float* in, void* out, int64_t n, hipStream_t s
     return hipGetLastError();
 }
 
+// dst[0..bytes) = src[0..bytes) as a kernel (a captured graph of the backward pass then holds kernel nodes only):
+// 16 bytes per thread and step where both addresses allow it, single bytes for the rest.
+__global__ void copy_bytes_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst, int64_t n16, int64_t bytes) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = t; i < n16; i += stride) reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(src)[i];
+    for (int64_t i = n16 * 16 + t; i < bytes; i += stride) dst[i] = src[i];
+}
+
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return hipSuccess;
+    const bool wide = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15) == 0;
+    const int64_t n16 = wide ? (int64_t)(bytes / 16) : 0;
+    int blocks = cdiv64(wide ? (n16 > 0 ? n16 : 1) : (int64_t)bytes, 256);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(copy_bytes_kernel, dim3(blocks), dim3(256), 0, s, (const unsigned char*)src, (unsigned char*)dst, n16,
+                       (int64_t)bytes);
+    return hipGetLastError();
+}
+
 // --------------------------------------------------------------------------------- max pooling
 // One thread per output element (channels fastest, so a wave reads/writes consecutive channels).
 template <typename T>

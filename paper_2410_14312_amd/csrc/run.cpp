@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <shared_mutex>
 #include <thread>
 #include <vector>
 
@@ -66,6 +67,7 @@ struct RunCtx {
             if (err.load(std::memory_order_relaxed) != TMPS_OK) return TMPS_EINVAL;
             std::this_thread::yield();
         }
+        std::shared_lock<std::shared_mutex> no_capture(capture_lock());   // (see capture_lock)
         TMPS_HIP(hipStreamWaitEvent(s, event(e), 0));
         return TMPS_OK;
     }

@@ -260,6 +260,10 @@ int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, co
             soff = align_up(soff + (size_t)rows_all * L.out_elems * st.asz, 256);
         }
     }
+    if (cfg->is_last) {
+        st.lab_off = soff;
+        soff = align_up(soff + (size_t)rows_all * st.label_rps * 4, 256);
+    }
     st.stash_bytes = soff;
 
     // scratch: gradient buffers of M rows, two boundary-gradient buffers, fp32 workspace
@@ -397,6 +401,55 @@ extern "C" void* tmps_stage_output_ptr(const tmps_stage* stage, int slot) {
 }
 
 // what layer li reads: the stage input (x0, rows from row0 on) or the stashed output of the layer before it
+// Runs `work` (which launches kernels on stream s and nothing else) either directly or, on a stage that replays
+// graphs, as a captured graph: the first call with a key runs directly (one-off argument sets are never captured, and
+// every kernel's first-launch set-up happens outside a capture), the second is captured, instantiated and launched,
+// later ones launch the instantiated graph.  While per-kernel timing is on, and on the default stream, everything
+// runs directly.
+std::shared_mutex& tmps::capture_lock() {
+    static std::shared_mutex m;
+    return m;
+}
+
+template <class Work> static int run_or_replay(tmps_stage* st, const tmps_stage::GraphKey& key, hipStream_t s, Work&& work) {
+    if (!st->use_graphs || s == nullptr || profile_on()) return work();   // (the default stream cannot be captured)
+    auto it = st->graphs.find(key);
+    if (it != st->graphs.end()) {
+        TMPS_HIP(hipGraphLaunch(it->second, s));
+        return TMPS_OK;
+    }
+    if (st->graph_seen.size() > 4096) st->graph_seen.clear();   // addresses that never repeat: forget them
+    if (++st->graph_seen[key] < 2) return work();
+    hipGraph_t graph = nullptr;
+    int rc;
+    hipError_t e;
+    {
+        std::unique_lock<std::shared_mutex> alone(capture_lock());
+        TMPS_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+        rc = work();
+        e = hipStreamEndCapture(s, &graph);
+    }
+    if (rc != TMPS_OK || e != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        if (rc != TMPS_OK) return rc;
+        return fail(TMPS_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    }
+    hipGraphExec_t exec = nullptr;
+    const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (ei != hipSuccess) return fail(TMPS_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(ei));
+    st->graph_seen.erase(key);
+    st->graphs[key] = exec;
+    TMPS_HIP(hipGraphLaunch(exec, s));
+    return TMPS_OK;
+}
+
+extern "C" int tmps_stage_use_graphs(tmps_stage* st, int on) {
+    if (!st) return fail(TMPS_EINVAL, "stage is null");
+    st->use_graphs = on != 0;
+    return TMPS_OK;
+}
+
 static const void* layer_input(const tmps_stage* st, int li, const void* x0, int64_t row0) {
     return li == 0 ? x0 : (const void*)st->out_ptr(st->layers[li - 1], row0);
 }
@@ -424,6 +477,15 @@ int tmps::forward_with_workspace(tmps_stage* st, int slot, const void* x, void* 
         x0 = dst;
     }
     st->slot_x[slot] = x;
+    if (st->use_graphs && st->cfg.is_last) {
+        // a captured loss kernel reads its labels at a fixed address: the stage's own copy of this slot's labels
+        int32_t* lab = reinterpret_cast<int32_t*>(st->stash + st->lab_off) + (size_t)row0 * st->label_rps;
+        TMPS_RUN(kcCopy, s, hipMemcpyAsync(lab, labels, (size_t)mb * st->label_rps * 4, hipMemcpyDeviceToDevice, s));
+        labels = lab;
+    }
+    const tmps_stage::GraphKey key = {1, (uintptr_t)slot, (uintptr_t)x0, (uintptr_t)labels, (uintptr_t)loss_out, (uintptr_t)ws,
+                                      (uintptr_t)st->master, (uintptr_t)st->wcopy};
+    const int rc = run_or_replay(st, key, s, [&]() -> int {
     for (size_t li = 0; li < st->layers.size(); ++li) {
         const LayerRT& L = st->layers[li];
         void* out = st->out_ptr(L, row0);
@@ -506,6 +568,9 @@ int tmps::forward_with_workspace(tmps_stage* st, int slot, const void* x, void* 
             }
         }
     }
+    return TMPS_OK;
+    });
+    if (rc != TMPS_OK) return rc;
     if (y) {
         const LayerRT& L = st->cfg.is_last ? st->layers[st->layers.size() - 2] : st->layers.back();
         TMPS_RUN(kcCopy, s, hipMemcpyAsync(y, st->out_ptr(L, row0), (size_t)mb * L.out_elems * L.out_esize,
@@ -556,6 +621,9 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         }
     } free_slots{st, g0, N};
 
+    const tmps_stage::GraphKey key = {2, (uintptr_t)g0, (uintptr_t)x0, (uintptr_t)dy, (uintptr_t)dx, 0,
+                                      (uintptr_t)st->master, (uintptr_t)st->wcopy};
+    return run_or_replay(st, key, s, [&]() -> int {
     // Gradients are kept per result: grads[t + 1] is the gradient w.r.t. the result of layer t (t = -1: the stage
     // input).  Layers are visited last to first; every layer that reads a result contributes to its gradient: the
     // first contribution is written, later ones are added to what is there (in the epilogue of the kernel that
@@ -641,7 +709,7 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         const int64_t n = (int64_t)M * st->tensor_elems(t);
         if (t < 0) {
             if (G.set) TMPS_GEMM(resadd_forward(dt, dx, g.ptr, dx, n, 0, s));
-            else TMPS_RUN(kcCopy, s, hipMemcpyAsync(dx, g.ptr, (size_t)n * st->asz, hipMemcpyDeviceToDevice, s));
+            else TMPS_RUN(kcCopy, s, copy_bytes(dx, g.ptr, (size_t)n * st->asz, s));
             G.ptr = dx; G.buf = -1; G.set = true;
         } else if (!G.set) {
             G = g;
@@ -781,7 +849,8 @@ extern "C" int tmps_backward(tmps_stage* st, const int* slots, int n_slots, cons
         if (L.d.kind == TMPS_RESADD && L.in_b >= 0 && remaining[L.in_b + 1] == 0 && st->layers[L.in_b].act != 0)
             return fail(TMPS_EUNSUPPORTED, "a residual connection must start at a result that another, earlier layer reads too");
     }
-    return TMPS_OK;   // (free_slots releases the group)
+    return TMPS_OK;
+    });   // (free_slots releases the group)
 }
 
 extern "C" int tmps_update(tmps_stage* st, void* hip_stream) {

@@ -1,5 +1,9 @@
 // One pipeline worker: consecutive layers, activation stash, backward pass, in-place update.
 #pragma once
+#include <array>
+#include <map>
+#include <mutex>
+#include <shared_mutex>
 #include <vector>
 
 #include "common.h"
@@ -52,8 +56,17 @@ struct tmps_stage {
     std::vector<const void*> slot_x;
     long version = 0;
     std::vector<hipEvent_t> events;   // tmps_schedule_run: what this worker sends to its neighbours (kept between runs)
+    // Graph replay (tmps_stage_use_graphs): the kernels of a forward or backward pass, captured once per distinct
+    // set of device addresses they work on and launched as one graph from then on.  A key is the kind of pass and
+    // every address that varies between calls; the stage's own regions never move.
+    typedef std::array<uintptr_t, 8> GraphKey;
+    bool use_graphs = false;
+    std::map<GraphKey, hipGraphExec_t> graphs;
+    std::map<GraphKey, int> graph_seen;   // calls with a key that has no graph yet (captured at the second)
+    size_t lab_off = 0;                   // last stage: stash offset of the copied labels (read by captured loss kernels)
     ~tmps_stage() {
         for (hipEvent_t e : events) (void)hipEventDestroy(e);
+        for (auto& g : graphs) (void)hipGraphExecDestroy(g.second);
     }
     // vertical weight stashing: copies of the `params` region as it was after earlier updates
     char* shadow = nullptr;
@@ -79,6 +92,11 @@ struct tmps_stage {
 };
 
 namespace tmps {
+// While a stream is being captured the runtime refuses, in every thread, to make another stream wait for an event that
+// was recorded on the capturing stream, also one recorded before the capture began.  A pass that captures holds this
+// lock exclusively from the beginning to the end of the capture; the scheduler's threads hold it shared around their
+// cross-stream waits.  (Captures are rare: one per distinct set of addresses of a pass.)
+std::shared_mutex& capture_lock();
 // Fills `st` from the descriptors: shapes, flat parameter layout, stash and scratch layout.
 int stage_layout(tmps_stage& st, const tmps_layer_desc* layers, int n_layers, const tmps_stage_cfg* cfg);
 // Device address of the boundary-gradient buffer `which` (0/1) of a stage.

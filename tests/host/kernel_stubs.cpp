@@ -2,6 +2,8 @@
 // the stage executor: nothing is launched, every launcher reports success, and the workspace sizes are small fixed
 // functions of the shape.  Only the host logic of csrc/stage.cpp (layout, argument checks, slot and buffer
 // bookkeeping) is exercised by such a build.
+#include <string.h>
+
 #include "../../paper_2410_14312_amd/csrc/kernels.h"
 
 namespace tmps {
@@ -30,6 +32,7 @@ hipError_t reduce_scaled_sum(const float* in, int n, float scale, float* out, hi
 hipError_t relu_mask(int dtype, const void* dy, const void* y, void* dz, int64_t n, hipStream_t s) { return hipSuccess; }
 hipError_t sgd_momentum(float* w, float* buf, const float* g, void* wcopy_bf16, int64_t n, float lr, float mu, hipStream_t s) { return hipSuccess; }
 hipError_t cast_f32_to_bf16(const float* in, void* out, int64_t n, hipStream_t s) { return hipSuccess; }
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t) { memcpy(dst, src, bytes); return hipSuccess; }
 GemmPlan plan_gemm(int64_t, int64_t, int64_t) { return GemmPlan{64, 1}; }
 size_t gemm_workspace_elems(int64_t M, int64_t N, int64_t, int with_rowsum) { return (size_t)(2 * (M * N + (with_rowsum ? M : 0))); }
 size_t affine_workspace_elems(int64_t, int C) { return (size_t)(2 * C * 8); }
@@ -57,4 +60,11 @@ extern "C" hipError_t hipMemcpyAsync(void* dst, const void* src, size_t bytes, h
     return hipSuccess;
 }
 extern "C" hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
+// (graph replay is off in these builds: the calls exist for the linker only)
+extern "C" hipError_t hipGraphExecDestroy(hipGraphExec_t) { return hipSuccess; }
+extern "C" hipError_t hipGraphDestroy(hipGraph_t) { return hipSuccess; }
+extern "C" hipError_t hipGraphLaunch(hipGraphExec_t, hipStream_t) { return hipErrorNotSupported; }
+extern "C" hipError_t hipGraphInstantiate(hipGraphExec_t*, hipGraph_t, hipGraphNode_t*, char*, size_t) { return hipErrorNotSupported; }
+extern "C" hipError_t hipStreamBeginCapture(hipStream_t, hipStreamCaptureMode) { return hipErrorNotSupported; }
+extern "C" hipError_t hipStreamEndCapture(hipStream_t, hipGraph_t*) { return hipErrorNotSupported; }
 extern "C" const char* hipGetErrorString(hipError_t) { return "stub"; }
