@@ -45,9 +45,10 @@ template <bool KC> struct G3Operand {
 };
 
 // wait until at most N vector-memory operations of this wave are outstanding
+// (the trailing comment tells this wait from the ones the compiler inserts, for tests/test_gemm3_isa.py)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) ; tmps" ::"n"(N) : "memory");
 }
 
 // One wave instruction that copies 16 bytes per lane from `src` (per lane) to 1 KB of consecutive LDS at `dst` (the same
@@ -343,6 +344,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
         for (int kt = 0; kt < nk; ++kt) {
             // Invariant: the fragments of this k-tile's first PD multiply steps are in registers or on their way
             // (requested during the previous k-tile's last PD steps); `ahead` younger k-tiles are in flight or have landed.
+            asm volatile("; tmps k-tile begin");
             const lds_t sa = smem + cstage * STAGE;
             const int nstage = cstage + 1 == NS ? 0 : cstage + 1;
             if constexpr (ROWSUM) {
@@ -407,6 +409,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                 --ahead;   // kt + 1 < nk: a next k-tile exists
                 cstage = nstage;
             }
+            asm volatile("; tmps k-tile end");
         }
 
         // ---- results ----

@@ -1,0 +1,103 @@
+"""The k-loop of the persistent GEMM (csrc/gemm3.hip.h) keeps its global->LDS copies in flight across k-tiles; that only
+works while the ONLY waits on the vector-memory counter inside a k-tile are the kernel's own (before the stage barrier).
+The compiler inserts such waits of its own when it believes a register or an LDS location may still be the target of an
+operation in flight, and one of them at the head of the loop serialises copies and multiplies without changing any
+result, so no numerical test sees it.  This test compiles the kernels for gfx950 and reads the instruction stream of
+every instance between the kernel's k-tile markers: every `vmcnt` wait there must carry the kernel's own tag, nothing
+may be spilled there, and every instance must show the copies, the transposing or 16-byte fragment reads and the MFMAs.
+"""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2410_14312_amd", "csrc", "kernels_gemm.hip")
+
+
+@pytest.fixture(scope="module")
+def isa(tmp_path_factory):
+    if shutil.which("hipcc") is None:
+        pytest.skip("no hipcc")
+    out = str(tmp_path_factory.mktemp("isa") / "kernels_gemm.s")
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "--cuda-device-only", "-S", "-x", "hip", SRC, "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    return open(out).read().split("\n")
+
+
+def kernels(lines):
+    name, start = None, 0
+    for i, l in enumerate(lines):
+        m = re.match(r"^(_ZN4tmps12gemm3_kernel\S+):", l)
+        if m:
+            name, start = m.group(1), i
+        elif name and "s_endpgm" in l:
+            yield name, lines[start:i]
+            name = None
+
+
+def k_tile_loop(body):
+    """The instructions of the loop over k-tiles: every basic block the compiler lists as part of the innermost loop
+    that holds the kernel's k-tile marker (the blocks of a loop need not be contiguous, nor in program order)."""
+    blocks, cur, child_of = [], None, {}   # (label, header of the depth-2 loop it belongs to or None, lines)
+    for i, l in enumerate(body):
+        m = re.match(r"^\.(LBB\d+_\d+):", l)
+        if m:
+            label = m.group(1)[1:]
+            note, j = l, i + 1
+            while j < len(body) and body[j].lstrip().startswith(";") and "#ASM" not in body[j]:   # the block's loop comments
+                note += " " + body[j]
+                j += 1
+            header = None
+            if re.search(r"Loop Header: Depth=2", note):
+                header = label
+            else:
+                inner = re.search(r"in Loop: Header=(BB\d+_\d+) Depth=2", note) or re.search(r"Parent Loop (BB\d+_\d+) Depth=2", note)
+                if inner:
+                    header = inner.group(1)
+                else:
+                    deeper = re.search(r"in Loop: Header=(BB\d+_\d+) Depth=3", note)   # a block of a loop inside the k-tile loop
+                    if deeper:
+                        header = child_of.get(deeper.group(1))
+            if header and re.search(r"Loop Header: Depth=3", note):
+                child_of[label] = header
+            cur = [label, header, []]
+            blocks.append(cur)
+        elif cur is not None:
+            cur[2].append(l)
+    mine = [b for b in blocks if any("; tmps k-tile begin" in l for l in b[2])]
+    assert len(mine) == 1 and mine[0][1], "the k-tile marker sits in exactly one block of a depth-2 loop"
+    head = mine[0][1]
+    loop = [b for b in blocks if b[1] == head]
+    # The part every k-tile executes, as opposed to the blocks that move the copy cursor to the next work unit (once
+    # per unit: they recompute the lanes' global addresses, with 64-bit multiplies that nothing else in the loop
+    # needs; the compiler does wait there, for registers that the previous unit's result stores read).
+    seek = [b for b in loop if any(("v_mad_u64_u32" in l) or ("v_mul_lo_u32" in l) for l in b[2])]
+    hot = [b for b in loop if b not in seek]
+    assert not any("v_mfma" in l or "s_barrier" in l or "global_load_lds" in l for b in seek for l in b[2])
+    return [l for b in hot for l in b[2]], [l for b in loop for l in b[2]]
+
+
+def test_k_loops_wait_only_where_the_kernel_says(isa):
+    seen = 0
+    for name, body in kernels(isa):
+        tile, whole = k_tile_loop(body)
+        text = "\n".join(tile)
+        assert text.count("; tmps k-tile begin") == 1 and text.count("; tmps k-tile end") == 1, name
+        waits = [l.strip() for l in tile if "vmcnt" in l]
+        foreign = [w for w in waits if "; tmps" not in w]
+        assert not foreign, "%s: compiler-inserted waits on the copy counter inside a k-tile: %s" % (name, foreign)
+        assert 1 <= len(waits) <= 2, (name, waits)          # the two arms of the wait before the stage barrier
+        assert "scratch_" not in text, "%s: spills inside a k-tile" % name
+        assert sum("scratch_" in l for l in whole) <= 4, "%s: spills in the k-tile loop" % name
+        assert text.count("s_barrier") == 1, name
+        n_mfma = text.count("v_mfma_f32_32x32x16_bf16")
+        assert n_mfma == 32, (name, n_mfma)                 # four steps of eight multiplies (wave tiles of 128 x 64)
+        assert text.count("global_load_lds_dwordx4") >= 8, name
+        assert "ds_read_b128" in text or "ds_read_b64_tr_b16" in text, name
+        seen += 1
+    assert seen >= 6, "expected the forward, input-gradient, partial-sum, weight-gradient, convolution and narrow instances"
