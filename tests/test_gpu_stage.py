@@ -220,6 +220,7 @@ DENSE_CASES = [
     (6144, 128, False, 1024, 2), # wide input: the persistent kernel in the input-gradient pass
     (1024, 1024, False, 4608, 2),  # long batch: the persistent kernel, k-split, in the weight-gradient pass
     (768, 8192, False, 2048, 2),   # long contraction, few wide tiles: the persistent kernel in k-slices in the input-gradient pass
+    (768, 512, False, 3000, 2),    # tall narrow input gradient, ragged last row of tiles: the 256x128 four-wave instance
 ]
 
 
