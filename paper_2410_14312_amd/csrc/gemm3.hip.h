@@ -177,7 +177,7 @@ struct G3Plan {
 };
 
 // ROWSUM: units of the first tile column also sum A over k (bias gradient of a weight-gradient GEMM, whose
-// A operand is dY, row-contiguous); the sums go to epi.rowsum(m, v, slice).
+// A operand is dY, row-contiguous), from the fragments in registers; the sums go to epi.rowsum(m, v, slice).
 template <int BM, int BN, int BK, int WM, int WN, int NS, bool AKC, bool BKC, bool ROWSUM, class Epi>
 __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G3Operand<BKC> B, Epi epi, int M, int N,
                                                               int K, G3Plan plan) {
@@ -313,7 +313,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        float rsum = 0.0f;
+        // ROWSUM: the waves of the first wave column add up the A fragments they multiply with anyway (a lane holds 8
+        // consecutive k of one row: four two-element dot products with ones), in units of the first tile column.
+        float rs[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) rs[i] = 0.0f;
+        const bool sum_rows = ROWSUM && tn == 0 && wn == 0;
 
         // What the epilogue reads from memory (a bias per column, a residual source or a mask per element), block by
         // block of 32 rows x 64 columns of this wave's results (block b: rows 32 (b / (TN / 2)), columns 64 (b % (TN / 2))).
@@ -347,14 +352,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             asm volatile("; tmps k-tile begin");
             const lds_t sa = smem + cstage * STAGE;
             const int nstage = cstage + 1 == NS ? 0 : cstage + 1;
-            if constexpr (ROWSUM) {
-                if (tn == 0 && tid < BM) {
-                    // column tid of the [BK][BM] tile: chunk (tid / 8) ^ ((k & 3) << 2) of k-row k
-#pragma unroll 8
-                    for (int k = 0; k < BK; ++k)
-                        rsum += (float)*lds_ptr<const bf16_t>(sa + k * (BM * 2) + ((((tid >> 3) ^ ((k & 3) << 2)) << 4) | ((tid & 7) << 1)));
-                }
-            }
             // After the barrier of this k-tile its stage is free; unless the unit's results go through it first (the
             // unit's last k-tile) it is refilled at once, the copies spread over the multiplies that follow the barrier.
             bool fill = false;
@@ -398,6 +395,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                         }
                     }
                     acc[g / TN][g % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % NBUF][g / TN], bfr[kk % NBUF][g % TN], acc[g / TN][g % TN], 0, 0, 0);
+                    if constexpr (ROWSUM) {
+                        // Behind the fragment's first multiply, so that it is issued while that one runs; written as
+                        // instructions because the compiler otherwise turns the branch into selects and moves the
+                        // additions, which nothing in the loop depends on, below the multiplies of the k-tile.
+                        if (g % TN == 0 && sum_rows) {
+                            typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+                            const u32x4_t f = __builtin_bit_cast(u32x4_t, af[kk % NBUF][g / TN]);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)   // rs += f[q].lo * 1 + f[q].hi * 1 (0x3f80 = 1.0 in bf16)
+                                asm volatile("v_dot2c_f32_bf16_e32 %0, 0x3f803f80, %1" : "+v"(rs[g / TN]) : "v"(f[q]));
+                        }
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -469,7 +478,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             }
         }
         if constexpr (ROWSUM) {
-            if (tn == 0 && tid < BM && m0 + tid < M) epi.rowsum(m0 + tid, rsum, z);
+            if (sum_rows) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    // lanes l and l + 32 hold the two halves of every 16 k of row 32 i + l % 32
+                    const float total = rs[i] + __shfl_xor(rs[i], 32, 64);
+                    const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
+                    if (lane < 32 && m < M) epi.rowsum(m, total, z);
+                }
+            }
         }
         // refill the stage the results went through, and move on to the next unit's first k-tile
         if (issue_next()) ++ahead;
