@@ -313,12 +313,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        // ROWSUM: the waves of the first wave column add up the A fragments they multiply with anyway (a lane holds 8
-        // consecutive k of one row: four two-element dot products with ones), in units of the first tile column.
+        // ROWSUM: in units of the first tile column the waves add up the A fragments they multiply with anyway (a lane
+        // holds 8 consecutive k of one row: four two-element dot products with ones).  The WN waves of a wave row hold
+        // the same fragments: wave column c takes the fragments i with i % WN == c, so that no wave falls behind.
         float rs[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) rs[i] = 0.0f;
-        const bool sum_rows = ROWSUM && tn == 0 && wn == 0;
+        const bool sum_rows = ROWSUM && tn == 0;
 
         // What the epilogue reads from memory (a bias per column, a residual source or a mask per element), block by
         // block of 32 rows x 64 columns of this wave's results (block b: rows 32 (b / (TN / 2)), columns 64 (b % (TN / 2))).
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                         // Behind the fragment's first multiply, so that it is issued while that one runs; written as
                         // instructions because the compiler otherwise turns the branch into selects and moves the
                         // additions, which nothing in the loop depends on, below the multiplies of the k-tile.
-                        if (g % TN == 0 && sum_rows) {
+                        if (g % TN == 0 && sum_rows && (g / TN) % WN == wn) {
                             typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
                             const u32x4_t f = __builtin_bit_cast(u32x4_t, af[kk % NBUF][g / TN]);
 #pragma unroll
@@ -481,6 +482,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             if (sum_rows) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
+                    if (i % WN != wn) continue;
                     // lanes l and l + 32 hold the two halves of every 16 k of row 32 i + l % 32
                     const float total = rs[i] + __shfl_xor(rs[i], 32, 64);
                     const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
