@@ -86,6 +86,7 @@ template <int BM, int BN, int BK, int NS> constexpr int gemm3_lds_bytes() { retu
 template <int ROWS, int BK, int NW, bool KC> struct G3Loader {
     static constexpr int GROUPS = ROWS * BK * 2 / 1024 / NW;
     static_assert(GROUPS >= 1 && GROUPS * NW * 1024 == ROWS * BK * 2, "the waves must share a tile evenly");
+    static_assert(KC || (ROWS / 8 <= 64 && 64 % (ROWS / 8) == 0), "a 1 KB group of a row-contiguous tile covers whole k-rows");
     const bf16_t* ptr[GROUPS];
     // (re)compute the lane addresses for the tile starting at row0, k range starting at k0
     __device__ __forceinline__ void seek(const G3Operand<KC>& op, int row0, int k0, int wave, int lane) {
