@@ -195,7 +195,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     const lds_t smem = (lds_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // (the wave's index as a scalar: what derives from it — LDS addresses of its copies, its place in the tile — then
+    // lives in scalar registers and is computed by the scalar unit)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN, half = lane >> 5;
     const int grid = gridDim.x;
     // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin in launch order.  Renumber them so that
@@ -328,13 +331,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
         const int64_t epi_ld = epi.ld;
         typename Epi::Col8 pcol[TN / 2];
         typename Epi::Row8 prow[NB][4];
-        auto epi_n = [&](int jp) { return n0 + wn * (BN / WN) + jp * 64 + (lane & 7) * 8; };
-        auto epi_request = [&](int b) {
-            const int i = b / (TN / 2), jp = b % (TN / 2), n = epi_n(jp);
+        // (ln: the lane's index as the caller has it; see the epilogue)
+        auto epi_n = [&](int jp, int ln) { return n0 + wn * (BN / WN) + jp * 64 + (ln & 7) * 8; };
+        auto epi_request = [&](int b, int ln) {
+            const int i = b / (TN / 2), jp = b % (TN / 2), n = epi_n(jp, ln);
             if (i == 0) pcol[jp] = epi.col8(n < N ? n : 0);
 #pragma unroll
             for (int sp = 0; sp < 4; ++sp) {
-                const int pm = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
+                const int pm = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (ln >> 3);
                 prow[b][sp] = epi.row8((int64_t)pm * epi_ld + n, pm < M && n < N);
             }
         };
@@ -345,7 +349,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
         constexpr bool EARLY = NW <= 4;
         if constexpr (EARLY) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) epi_request(b);
+            for (int b = 0; b < NB; ++b) epi_request(b, lane);
         }
 
         for (int kt = 0; kt < nk; ++kt) {
@@ -435,7 +439,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             auto piece = [&](int p) {
                 return p < LoaderA::GROUPS ? (wave + p * NW) * 1024 : A_BYTES + (wave + (p - LoaderA::GROUPS) * NW) * 1024;
             };
-            const int col_in = lane & 31;
+            // Everything the epilogue derives from the lane's index is derived here, from a copy of the index that the
+            // compiler cannot trace back: otherwise it computes these offsets before the k-loop and, in the 8-wave
+            // instances, whose loop leaves no register free, spills them around it — and every reload from scratch
+            // memory is a wait for all of the wave's requests, result stores included.
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int half = ln >> 5, col_in = ln & 31;
             if constexpr (EARLY) {
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
@@ -448,8 +458,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
             for (int b = 0; b < NB; ++b) {
                 const int i = b / (TN / 2), jp = b % (TN / 2);
                 // (requested before the block is transposed: one memory latency per block, not one per group of rows)
-                if constexpr (!EARLY) epi_request(b);
-                const int n = epi_n(jp);
+                if constexpr (!EARLY) epi_request(b, ln);
+                const int n = epi_n(jp, ln);
                 // accumulator register r of a lane: row 8 (r / 4) + 4 half + r % 4, column lane % 32
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj)
@@ -469,11 +479,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm3_kernel(G3Operand<AKC> A, G
                 for (int sp = 0; sp < 4; ++sp) {
                     // staged row 8 sp + lane / 8 lies in piece 2 sp + half, at row (lane / 8) % 4 of the piece
                     const int base = half ? piece(2 * sp + 1) : piece(2 * sp);
-                    const lds_t src = stg + base + ((lane >> 3) & 3) * 256 + (lane & 7) * 32;
+                    const lds_t src = stg + base + ((ln >> 3) & 3) * 256 + (ln & 7) * 32;
                     typedef float f32x4_t __attribute__((ext_vector_type(4)));
                     const f32x4_t lo = *lds_ptr<const f32x4_t>(src), hi = *lds_ptr<const f32x4_t>(src + 16);
                     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                    const int m = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (lane >> 3);
+                    const int m = m0 + wm * (BM / WM) + i * 32 + sp * 8 + (ln >> 3);
                     if (m < M && n < N) epi.at8(pcol[jp], prow[b][sp], (int64_t)m * epi_ld + n, v, z);   // N is a multiple of 8
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged values are in registers before they are overwritten

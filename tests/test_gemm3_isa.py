@@ -94,6 +94,10 @@ def test_k_loops_wait_only_where_the_kernel_says(isa):
         assert 1 <= len(waits) <= 2, (name, waits)          # the two arms of the wait before the stage barrier
         assert "scratch_" not in text, "%s: spills inside a k-tile" % name
         assert sum("scratch_" in l for l in whole) <= 4, "%s: spills in the k-tile loop" % name
+        # around the loop a few spills remain in two of the 8-wave instances; every reload of one is a wait for all of
+        # the wave's requests, so their number is held (it was 40-70 per instance before the epilogue's lane offsets
+        # were derived after the loop, and cost the residual network's 1x1 input gradients 12 %)
+        assert sum("scratch_" in l for l in body) <= 24, "%s: %d spill instructions" % (name, sum("scratch_" in l for l in body))
         assert text.count("s_barrier") == 1, name
         n_mfma = text.count("v_mfma_f32_32x32x16_bf16")
         assert n_mfma == 32, (name, n_mfma)                 # four steps of eight multiplies (wave tiles of 128 x 64)
