@@ -464,7 +464,7 @@ template <int BM, int BN, class AOp, class BOp> constexpr int gemm2_lds_bytes() 
 // a second, nearly empty round.
 template <int BM, int BN, int D, bool ROWSUM, class AOp, class BOp, class Epi>
 __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_kernel(AOp A, BOp B, Epi epi, int M, int N, int K, int k_per_slice,
-                                                    int col_major, int wide) {
+                                                    int col_major, int wide, FastDiv d_plane, FastDiv d_minor) {
     constexpr bool AKC = AOp::kContig, BKC = BOp::kContig;
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int A_CH = BM * (kBK2 / 8) / 256, B_CH = BN * (kBK2 / 8) / 256;
@@ -489,14 +489,16 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 3 : 2) void gemm2_ker
             const int lin = (z * gy + tile_y) * gx + tile_x;
             const int xcd = lin & 7, idx = lin >> 3;
             const int q = total >> 3, r = total & 7;
+            // (d_plane divides by the tiles of a k-slice, d_minor by the tiles along the direction walked first: the host
+            // prepares the multipliers, so that the workgroup reaches its first loads without integer divisions)
             int moved = xcd * q + min(xcd, r) + idx;
-            z = moved / nb;
+            z = (int)d_plane.div((uint32_t)moved);
             moved -= z * nb;
             if (col_major) {
-                tile_x = moved / gy;
+                tile_x = (int)d_minor.div((uint32_t)moved);
                 tile_y = moved - tile_x * gy;
             } else {
-                tile_y = moved / gx;
+                tile_y = (int)d_minor.div((uint32_t)moved);
                 tile_x = moved - tile_y * gx;
             }
         }

@@ -147,8 +147,9 @@ static hipError_t launch2_inst(int kc, const AOp& A, const BOp& B, const Epi& ep
     }
     dim3 grid(cdiv(N, BN), cdiv(M, BM), nz);
     // the XCDs split the operand with more rows between them and each reads the other one whole
-    return launch_timed(kc, kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per, N > M ? 1 : 0,
-                        (N % 8 == 0 && epi.wide_ok()) ? 1 : 0);
+    const int col_major = N > M ? 1 : 0;
+    return launch_timed(kc, kern, grid, dim3(256), lds, s, A, B, epi, M, N, K, per, col_major,
+                        (N % 8 == 0 && epi.wide_ok()) ? 1 : 0, FastDiv(grid.x * grid.y), FastDiv(col_major ? grid.y : grid.x));
 }
 
 // tile: the plan's tile edge.  Where it is 64, the output has 512 rows or more and 128 x 64 tiles still make 192
