@@ -221,6 +221,9 @@ DENSE_CASES = [
     (1024, 1024, False, 4608, 2),  # long batch: the persistent kernel, k-split, in the weight-gradient pass
     (768, 8192, False, 2048, 2),   # long contraction, few wide tiles: the persistent kernel in k-slices in the input-gradient pass
     (768, 512, False, 3000, 2),    # tall narrow input gradient, ragged last row of tiles: the 256x128 four-wave instance
+    (192, 3080, False, 2000, 2),   # the persistent kernel in the forward pass with ragged tiles in both directions
+    (3080, 192, False, 2000, 2),   # ... in the input-gradient pass
+    (2056, 2056, False, 2048, 2),  # ... in the weight-gradient pass (k-slices, row sums from the fragments, ragged tiles)
 ]
 
 
