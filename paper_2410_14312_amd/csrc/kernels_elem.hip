@@ -154,9 +154,88 @@ __global__ __launch_bounds__(kCeThreads) void softmax_ce_lds_kernel(const float*
     if (tid == 0) row_loss[row] = label_ok ? logf(bs) - (logits[row * C + label] - bm) : NAN;
 }
 
+// The same with the row in registers (C <= 4096 * NV): NV 16-byte pieces per thread, no LDS beyond the block reductions,
+// so that a compute unit holds two rows at a time and one row's memory phase overlaps the other's arithmetic (with the row
+// in LDS a unit holds one).  The same values are combined in the same order as above: the results are the same bit for bit.
+template <typename TG, int NV>
+__global__ __launch_bounds__(kCeThreads, 8) void softmax_ce_reg_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                                       TG* __restrict__ dlogits, float* __restrict__ row_loss, int C,
+                                                                       float inv_M) {
+    constexpr int NWV = kCeThreads / 64;
+    __shared__ float sm[NWV], ss[NWV];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const float4* z4 = reinterpret_cast<const float4*>(logits + row * C);
+    const int C4 = C >> 2;
+    float4 v[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int c = tid + k * kCeThreads;
+        if (c < C4) v[k] = z4[c];
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < NV; ++k)
+        if (tid + k * kCeThreads < C4) mx = fmaxf(fmaxf(mx, fmaxf(v[k].x, v[k].y)), fmaxf(v[k].z, v[k].w));
+    mx = wave_max(mx);
+    if (lane == 0) sm[wave] = mx;
+    __syncthreads();
+    float bm = sm[0];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) bm = fmaxf(bm, sm[w]);
+    float sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k)
+        if (tid + k * kCeThreads < C4) {
+            v[k].x = __expf(v[k].x - bm); v[k].y = __expf(v[k].y - bm); v[k].z = __expf(v[k].z - bm); v[k].w = __expf(v[k].w - bm);
+            sum += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+        }
+    sum = wave_sum(sum);
+    if (lane == 0) ss[wave] = sum;
+    __syncthreads();
+    float bs = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) bs += ss[w];
+    const float inv = 1.0f / bs;
+    const int label = labels[row];
+    const bool label_ok = label >= 0 && label < C;
+    TG* g = dlogits + row * C;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int c = tid + k * kCeThreads;
+        if (c < C4) {
+            float p[4] = {v[k].x * inv, v[k].y * inv, v[k].z * inv, v[k].w * inv};
+            const int c0 = c * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p[e] = (p[e] - (c0 + e == label ? 1.0f : 0.0f)) * inv_M;
+            if constexpr (sizeof(TG) == 2) {
+                union { bf16_t h[4]; uint2 u; } pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk.h[e] = (bf16_t)p[e];
+                *reinterpret_cast<uint2*>(g + c0) = pk.u;
+            } else {
+                *reinterpret_cast<float4*>(g + c0) = make_float4(p[0], p[1], p[2], p[3]);
+            }
+        }
+    }
+    if (tid == 0) row_loss[row] = label_ok ? logf(bs) - (logits[row * C + label] - bm) : NAN;
+}
+
 hipError_t softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
                       int rows, int C, float inv_M, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
+    if (C > 2048 && C % 4 == 0 && C <= 4096 * 8 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(dlogits) & 15) == 0) {
+        const bool small = C <= 4096 * 4;
+        if (dtype == kBF16) {
+            if (small) hipLaunchKernelGGL((softmax_ce_reg_kernel<bf16_t, 4>), dim3(rows), dim3(kCeThreads), 0, s, logits, labels, (bf16_t*)dlogits, row_loss, C, inv_M);
+            else hipLaunchKernelGGL((softmax_ce_reg_kernel<bf16_t, 8>), dim3(rows), dim3(kCeThreads), 0, s, logits, labels, (bf16_t*)dlogits, row_loss, C, inv_M);
+        } else {
+            if (small) hipLaunchKernelGGL((softmax_ce_reg_kernel<float, 4>), dim3(rows), dim3(kCeThreads), 0, s, logits, labels, (float*)dlogits, row_loss, C, inv_M);
+            else hipLaunchKernelGGL((softmax_ce_reg_kernel<float, 8>), dim3(rows), dim3(kCeThreads), 0, s, logits, labels, (float*)dlogits, row_loss, C, inv_M);
+        }
+        return hipGetLastError();
+    }
     if (C > 2048 && C % 4 == 0 && (size_t)C * 4 <= 150 * 1024 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(dlogits) & 15) == 0) {
         const unsigned lds = (unsigned)C * 4;

@@ -240,7 +240,8 @@ def test_last_stage_two_linears_and_loss(dtype, borrow):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("classes", [1000, 2600, 2601])   # one wave per row; one block per row with the row in LDS; without
+# one wave per row; one block per row with the row in registers (4 and 8 pieces per thread); the row in LDS; neither
+@pytest.mark.parametrize("classes", [1000, 2600, 20000, 33000, 2601])
 def test_last_stage_many_classes(dtype, classes):
     run_stage_case([linear(96, classes, False), softmax_ce(classes)], dtype, 6, 2, seed=6)
 
