@@ -105,3 +105,57 @@ def test_k_loops_wait_only_where_the_kernel_says(isa):
         assert "ds_read_b128" in text or "ds_read_b64_tr_b16" in text, name
         seen += 1
     assert seen >= 6, "expected the forward, input-gradient, partial-sum, weight-gradient, convolution and narrow instances"
+
+
+def innermost_mfma_loop(body):
+    """Lines of the innermost loop that multiplies, by the compiler's loop comments (None if the kernel has no such loop)."""
+    blocks, cur = [], None
+    for i, l in enumerate(body):
+        m = re.match(r"^\.(LBB\d+_\d+):", l)
+        if m:
+            label = m.group(1)[1:]
+            note, j = l, i + 1
+            while j < len(body) and body[j].lstrip().startswith(";") and "#ASM" not in body[j]:
+                note += " " + body[j]
+                j += 1
+            head = None
+            if re.search(r"This Inner Loop Header: Depth=\d+", note):
+                head = label
+            else:
+                inner = re.search(r"in Loop: Header=(BB\d+_\d+) Depth=\d+", note)
+                if inner:
+                    head = inner.group(1)
+            cur = [label, head, []]
+            blocks.append(cur)
+        elif cur is not None:
+            cur[2].append(l)
+    heads = {b[0] for b in blocks if b[1] == b[0]}
+    best = None
+    for h in heads:
+        lines = [l for b in blocks if b[1] == h for l in b[2]]
+        n = sum("v_mfma" in l for l in lines)
+        if n and (best is None or n > best[0]):
+            best = (n, lines)
+    return best[1] if best else None
+
+
+def test_tiled_gemm_loops_never_wait_for_all_their_loads(isa):
+    # The tiled GEMM (csrc/gemm2.hip.h) keeps the global loads of the next k-tiles in flight in a register ring and
+    # issues every load unconditionally, so that the compiler can count them: each tile is then waited for with the
+    # exact number of younger loads still allowed in flight.  A wait for ALL loads inside the k-loop would mean that
+    # the counting broke (a branch around a load, a select on its result) and that the ring no longer overlaps anything.
+    checked = 0
+    name, start = None, 0
+    for i, l in enumerate(isa):
+        m = re.match(r"^(_ZN4tmps12gemm2_kernel\S+):", l)
+        if m:
+            name, start = m.group(1), i
+        elif name and "s_endpgm" in l:
+            loop = innermost_mfma_loop(isa[start:i])
+            if loop is not None and sum("v_mfma" in x for x in loop) >= 8:
+                waits = [re.search(r"vmcnt\((\d+)\)", x).group(1) for x in loop if "vmcnt" in x]
+                assert waits and "0" not in waits, "%s: waits %s" % (name, waits)
+                assert not any("scratch_" in x for x in loop), "%s: spills in the k-loop" % name
+                checked += 1
+            name = None
+    assert checked >= 12, checked
